@@ -1,0 +1,203 @@
+"""Pins for the oracle's quantizer (Section 3.2, Eq. 2) that do not come from the oracle itself:
+hand-worked groups, exact rational arithmetic, the s/2 error bound and structural invariants."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "eq2_handworked_groups.txt")
+
+
+def _golden_rows():
+    rows = []
+    with open(GOLD) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            bits, vals, s, z, codes = [p.strip() for p in line.split("|")]
+            rows.append((int(bits), [float(v) for v in vals.split()], float(s), float(z),
+                         [int(c) for c in codes.split()]))
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_rows())
+def test_handworked_groups(oracle_mod, row):
+    bits, vals, s, z, codes = row
+    x = np.array(vals, dtype=np.float16).astype(np.float32)
+    assert np.array_equal(x.astype(np.float64), np.array(vals))      # fixture values are exact halves
+    gs, gz, gc = oracle_mod.quantize_group(x, bits)
+    assert float(gs) == s and float(gz) == z
+    assert gc.tolist() == codes
+
+
+# ---- exact rational model of the fp32 pipeline, independent of any float hardware ----
+
+def _rne_int(fr: Fraction) -> int:
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+def _rne_f32(fr: Fraction) -> Fraction:
+    """Round a rational to the nearest IEEE binary32 value (ties to even), as a rational."""
+    if fr == 0:
+        return fr
+    sign = -1 if fr < 0 else 1
+    a = abs(fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1                      # now 2^e <= a < 2^(e+1)
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1)
+    e = max(e, -126)
+    quantum = Fraction(2) ** (e - 23)
+    return sign * _rne_int(a / quantum) * quantum
+
+
+def _model_group(halves, bits):
+    xs = [Fraction(float(h)) for h in halves]
+    qmax = (1 << bits) - 1
+    z = min(xs)
+    rng = _rne_f32(max(xs) - z)
+    s = _rne_f32(rng / qmax)
+    codes = []
+    for x in xs:
+        if s == 0:
+            codes.append(0)
+            continue
+        t = _rne_f32(_rne_f32(x - z) / s)
+        codes.append(min(max(_rne_int(t), 0), qmax))
+    return s, z, codes
+
+
+def _check_against_model(oracle_mod, halves, bits):
+    s, z, codes = oracle_mod.quantize_group(halves.astype(np.float32), bits)
+    ms, mz, mc = _model_group(halves, bits)
+    assert Fraction(float(s)) == ms
+    assert Fraction(float(z)) == mz
+    assert codes.tolist() == mc
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_exact_rational_model_random_groups(oracle_mod, bits):
+    rng = np.random.default_rng(100 + bits)
+    for trial in range(60):
+        scale = 10.0 ** rng.integers(-4, 3)
+        offset = rng.standard_normal() * 20.0 * (trial % 3)
+        halves = (rng.standard_normal(32) * scale + offset).astype(np.float16)
+        _check_against_model(oracle_mod, halves, bits)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_exact_rational_model_tie_heavy_grids(oracle_mod, bits):
+    """Values on a coarse dyadic grid make exact .5 quotients common: pins the tie rule and the division."""
+    rng = np.random.default_rng(200 + bits)
+    qmax = (1 << bits) - 1
+    n_ties = 0
+    for trial in range(60):
+        step = 2.0 ** rng.integers(-6, 2)
+        lo = float(rng.integers(-2000, 2000)) * step
+        ks = rng.integers(0, 2 * qmax + 1, 32)
+        ks[0], ks[1] = 0, 2 * qmax            # range = 2*qmax*step, so s = 2*step and odd k are ties
+        halves = (lo + ks * step).astype(np.float16)
+        if not np.array_equal(halves.astype(np.float64), lo + ks * step):
+            continue                           # grid fell off the fp16 lattice; skip
+        n_ties += int(np.sum(ks % 2 == 1))
+        _check_against_model(oracle_mod, halves, bits)
+        s, z, codes = oracle_mod.quantize_group(halves.astype(np.float32), bits)
+        assert float(s) == 2 * step
+        expect = [(k // 2) + ((k // 2) % 2 if k % 2 else 0) for k in ks]   # k/2 rounded half-to-even
+        assert codes.tolist() == expect
+    assert n_ties > 100
+
+
+def test_exact_rational_model_all_fp16_values_in_a_fixed_range(oracle_mod):
+    """Every fp16 value inside [z, z + range] for a few fixed (z, range), 31 at a time."""
+    allh = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    allh = allh[np.isfinite(allh)]
+    for bits, zv, top in [(2, -1.0, 2.0), (4, 0.0, 1.0), (8, -3.0, 5.0)]:
+        inside = allh[(allh >= np.float16(zv)) & (allh <= np.float16(top))]
+        inside = inside[:: max(1, inside.size // 2000)]
+        for i in range(0, inside.size, 30):
+            halves = np.concatenate([[np.float16(zv), np.float16(top)], inside[i:i + 30]]).astype(np.float16)
+            _check_against_model(oracle_mod, halves, bits)
+
+
+# ---- what Eq. 2 guarantees mathematically ----
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_reconstruction_error_at_most_half_a_step(oracle_mod, bits):
+    rng = np.random.default_rng(300 + bits)
+    qmax = (1 << bits) - 1
+    for trial in range(200):
+        halves = (rng.standard_normal(32) * (1 + 9 * (trial % 2)) + rng.standard_normal() * 20).astype(np.float16)
+        x = halves.astype(np.float64)
+        s, z, codes = oracle_mod.quantize_group(halves.astype(np.float32), bits)
+        xhat = codes.astype(np.float64) * float(s) + float(z)
+        slack = float(s) / 2 * (1 + 2.0 ** -20) + 4 * np.spacing(np.float32(max(np.abs(x).max(), abs(float(z)))))
+        assert np.all(np.abs(x - xhat) <= slack)
+        assert float(z) == x.min()
+        assert codes[np.argmin(x)] == 0
+        if s > 0:
+            assert codes[np.argmax(x)] == qmax
+        assert codes.max() <= qmax
+        # scale is the fp32 quotient of the range, within one rounding of the real number
+        assert abs(float(s) - (x.max() - x.min()) / qmax) <= 2.0 ** -22 * float(s)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_constant_group_is_exact(oracle_mod, bits):
+    halves = np.full(32, -7.25, dtype=np.float16)
+    s, z, codes = oracle_mod.quantize_group(halves.astype(np.float32), bits)
+    assert float(s) == 0.0 and float(z) == -7.25 and not codes.any()
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_shift_equivariance_with_representable_shifts(oracle_mod, bits):
+    """Adding a constant that keeps every value exactly representable leaves codes and s alone and shifts z."""
+    rng = np.random.default_rng(400 + bits)
+    for trial in range(50):
+        base = (rng.integers(-64, 64, 32) / 8.0)          # multiples of 1/8 in [-8, 8)
+        shift = float(rng.integers(-40, 40))              # integer shift: still multiples of 1/8, < 64 in size
+        a = base.astype(np.float16)
+        b = (base + shift).astype(np.float16)
+        assert np.array_equal(b.astype(np.float64), base + shift)
+        s1, z1, c1 = oracle_mod.quantize_group(a.astype(np.float32), bits)
+        s2, z2, c2 = oracle_mod.quantize_group(b.astype(np.float32), bits)
+        assert float(s1) == float(s2) and float(z2) == float(z1) + shift
+        assert np.array_equal(c1, c2)
+
+
+def test_eight_bit_requantization_is_idempotent(oracle_mod):
+    """Quantizing X^ of a group whose step is a power of two (so X^ is exact in fp16) returns the same codes."""
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        codes0 = rng.integers(0, 256, 32)
+        codes0[0], codes0[1] = 0, 255
+        z0 = float(rng.integers(-100, 100)) / 4.0
+        x = (codes0 * 0.25 + z0).astype(np.float16)       # s = 0.25 exactly
+        assert np.array_equal(x.astype(np.float64), codes0 * 0.25 + z0)
+        s, z, codes = oracle_mod.quantize_group(x.astype(np.float32), 8)
+        assert float(s) == 0.25 and float(z) == z0 and np.array_equal(codes, codes0)
+        xhat = (codes.astype(np.float64) * float(s) + float(z)).astype(np.float16)
+        s2, z2, codes2 = oracle_mod.quantize_group(xhat.astype(np.float32), 8)
+        assert float(s2) == 0.25 and np.array_equal(codes2, codes0)
+
+
+def test_error_shrinks_with_bits_on_gaussian_groups(oracle_mod):
+    """i.i.d. N(0,1) groups of 32: mean |x - x^| is about range / (4 (2^B - 1)) with E[range] ~ 4.1."""
+    rng = np.random.default_rng(6)
+    means = {}
+    for bits in (2, 4, 8):
+        errs = []
+        for trial in range(300):
+            halves = rng.standard_normal(32).astype(np.float16)
+            s, z, codes = oracle_mod.quantize_group(halves.astype(np.float32), bits)
+            errs.append(np.abs(halves.astype(np.float64) - (codes * float(s) + float(z))).mean())
+        means[bits] = float(np.mean(errs))
+    assert means[8] < means[4] < means[2]
+    for bits, expect in ((8, 4.1 / (4 * 255)), (4, 4.1 / (4 * 15)), (2, 4.1 / (4 * 3))):
+        assert 0.75 * expect < means[bits] < 1.25 * expect
