@@ -1,0 +1,140 @@
+/*
+ * kvq.h -- C ABI of the MI355X (gfx950) mixed-precision KV-cache library.
+ *
+ * The library implements the inference-side hot path of layer-wise mixed-precision
+ * KV-cache quantization (KVTuner, arXiv 2502.04420): every transformer layer l owns a
+ * precision pair (key bits, value bits) (Section 5.1); cached keys and values are stored
+ * with the round-to-nearest asymmetric quantizer of Section 3.2, Eq. 2,
+ *     z = min(X),  s = (max(X) - min(X)) / (2^B - 1),  Q(X) = round((X - z) / s),
+ * keys grouped per channel over `group` consecutive tokens and values per token over
+ * `group` consecutive channels (the KIVI mode of the experimental-settings appendix:
+ * group 32, residual length 32), while the newest tokens stay in fp16; a decode step
+ * evaluates Section 3.1, Eq. 1,
+ *     a = softmax(q K^T / sqrt(D)),  o = a V,
+ * over the dequantized tokens X^ = Q(X) s + z and the fp16 tail without ever writing X^
+ * back to memory.
+ *
+ * Conventions
+ *   - Every pointer named *device* points to GPU memory of the current HIP device; every
+ *     other pointer is host memory.  The caller owns all device memory, including the
+ *     workspace; the library only keeps a small host-side context.
+ *   - All GPU work is enqueued on the HIP stream given to kvq_configure (a hipStream_t
+ *     passed as void*, NULL = the default stream).  No call synchronises the device.
+ *   - Calls on one context are not thread-safe; serialise them.
+ *   - fp16 means IEEE binary16.  All sequences of the batch have the same length.
+ *   - Functions returning int return KVQ_OK (0) or a negative kvq_status; nothing is
+ *     enqueued when an error is returned.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kvq_status {
+    KVQ_OK = 0,
+    KVQ_EINVAL = -1,      /* NULL pointer, bad layer index, unsupported bits / shape / group      */
+    KVQ_ECAPACITY = -2,   /* append would exceed max_tokens                                       */
+    KVQ_ESTATE = -3,      /* decode on a layer that holds no token                                */
+    KVQ_EWORKSPACE = -4,  /* workspace NULL, misaligned (needs 256 B) or smaller than required    */
+    KVQ_ELAUNCH = -5      /* the HIP runtime refused a launch (message via kvq_last_error)        */
+} kvq_status;
+
+typedef struct kvq_ctx kvq_ctx;
+
+/*
+ * Shapes and the layer-wise precision table P (Section 5.1: one (P_k, P_v) per layer,
+ * each in {2, 4, 8}; 16 keeps that tensor in fp16, the paper's half-precision baseline).
+ */
+typedef struct kvq_config {
+    int32_t n_layers;      /* L >= 1                                                             */
+    int32_t batch;         /* sequences, >= 1                                                    */
+    int32_t n_q_heads;     /* multiple of n_kv_heads (grouped-query attention)                   */
+    int32_t n_kv_heads;    /* >= 1                                                               */
+    int32_t head_dim;      /* D of Eq. 1 (per head); this build supports 128                     */
+    int32_t max_tokens;    /* capacity per sequence, >= 1                                        */
+    int32_t group;         /* G: tokens per key group = channels per value group; must be 32     */
+    int32_t residual;      /* R >= 0: at least this many newest tokens stay fp16 once T >= R     */
+    const uint8_t *kbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
+    const uint8_t *vbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
+} kvq_config;
+
+/* Bytes of device workspace kvq_configure needs for this configuration; 0 if it is invalid. */
+size_t kvq_workspace_bytes(const kvq_config *cfg);
+
+/*
+ * Create a context (Section 5.1: the offline-searched table is loaded once, no online
+ * decision remains).  `workspace_device` must be 256-byte aligned, at least
+ * kvq_workspace_bytes(cfg) long and stay valid and untouched by the caller until
+ * kvq_destroy.  The kbits / vbits arrays are copied.  All layers start empty.
+ */
+int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, size_t workspace_bytes,
+                  void *hip_stream);
+
+/*
+ * Append n_tokens >= 1 new tokens to one layer's cache (Eq. 1: K = concat(K_past, k_i)).
+ *   k_device, v_device : fp16 [batch, n_kv_heads, n_tokens, head_dim], contiguous, device.
+ * With T tokens appended in total, the oldest N_p = G * floor(max(T - R, 0) / G) are held
+ * quantized (Eq. 2 at the layer's bits, keys per channel over the G tokens of a group,
+ * values per token over each G channels) and the newest T - N_p stay in fp16.  The result
+ * depends only on the concatenated token sequence, not on how it was split into calls.
+ * The inputs may be reused once the enqueued work has run.  Inputs must be finite.
+ */
+int kvq_quantize_append(kvq_ctx *ctx, int32_t layer, const void *k_device, const void *v_device,
+                        int32_t n_tokens);
+
+/*
+ * One decode step of Eq. 1 for one layer over every token appended so far (no mask).
+ *   q_device   : fp16 [batch, n_q_heads, head_dim], device.
+ *   out_device : fp16 [batch, n_q_heads, head_dim], device, written.
+ * Query head h attends kv head h / (n_q_heads / n_kv_heads).  Quantized tokens enter as
+ * X^ = Q(X) s + z (Section 3.2), fp16 tokens as they are; accumulation is fp32.
+ */
+int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void *out_device);
+
+/* Tokens currently held quantized / in fp16 by a layer (host-side bookkeeping, no GPU work). */
+int kvq_layer_tokens(const kvq_ctx *ctx, int32_t layer, int32_t *n_packed, int32_t *n_residual);
+
+/* Forget every token of one layer (layer >= 0) or of all layers (layer == -1). */
+int kvq_reset(kvq_ctx *ctx, int32_t layer);
+
+/*
+ * Write a layer's cache in a layout-independent canonical form into caller-provided
+ * DEVICE buffers (any pointer may be NULL to skip that part).  With N_p, N_r from
+ * kvq_layer_tokens, B = batch, H = n_kv_heads, D = head_dim, G = group:
+ *   k_codes : kbits < 16: uint8 [B, H, N_p/G, D, G*kbits/8] -- per channel, the G codes of
+ *             a token group packed little-endian (token i at bits [i*kbits, (i+1)*kbits));
+ *             kbits = 16: fp16 [B, H, N_p, D].
+ *   k_scale, k_zero : fp32 [B, H, N_p/G, D]   (s and z of Eq. 2; untouched when kbits = 16)
+ *   v_codes : vbits < 16: uint8 [B, H, N_p, D*vbits/8] -- per token, the D codes packed
+ *             little-endian; vbits = 16: fp16 [B, H, N_p, D].
+ *   v_scale, v_zero : fp32 [B, H, N_p, D/G]   (untouched when vbits = 16)
+ *   k_res, v_res    : fp16 [B, H, N_r, D], oldest token first.
+ */
+int kvq_debug_export(kvq_ctx *ctx, int32_t layer, void *k_codes, void *k_scale, void *k_zero,
+                     void *v_codes, void *v_scale, void *v_zero, void *k_res, void *v_res);
+
+/*
+ * Tuning knobs (optional).  variant: 0 = choose automatically, 1 = vector-ALU kernel,
+ * 2 = matrix-core kernel.  splits: 0 = automatic, else the number of token-range splits
+ * per (batch, kv head) used to fill the GPU.  Returns KVQ_EINVAL for unknown values.
+ */
+int kvq_set_decode_options(kvq_ctx *ctx, int32_t variant, int32_t splits);
+
+/* Release the host-side context.  The workspace stays with the caller. */
+void kvq_destroy(kvq_ctx *ctx);
+
+/* Static description of a status code. */
+const char *kvq_strerror(int status);
+
+/* Detail of the last KVQ_ELAUNCH on this thread (empty string if none). */
+const char *kvq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

@@ -1,0 +1,9 @@
+"""MI355X-native mixed-precision KV-cache quantization and fused decode attention.
+
+The work is done by hand-written HIP kernels behind the C ABI of ``include/kvq.h``
+(built into ``libkvq.so`` by ``paper_2502_04420_amd.build``); this package is the thin
+Python binding with the same call names.  There is no CPU fallback: using the binding
+without the built library raises.
+"""
+from .binding import KVQ, KVQError, library_path, load_library  # noqa: F401
+from .schedule import equivalent_precision, bytes_per_token, parse_pairs  # noqa: F401

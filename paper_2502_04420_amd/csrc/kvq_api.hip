@@ -1,0 +1,307 @@
+// Host side of the C ABI declared in include/kvq.h: argument validation, workspace
+// planning, the per-layer token bookkeeping of the full-precision window, and the
+// kernel launches.  No device memory is allocated here and nothing synchronises.
+#include "../../include/kvq.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kvq_internal.h"
+
+namespace {
+
+constexpr int kMaxSplits = 64;
+constexpr size_t kAlign = 256;
+
+thread_local char g_last_error[256] = "";
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+
+bool config_ok(const kvq_config *c)
+{
+    if (!c || !c->kbits || !c->vbits) return false;
+    if (c->n_layers < 1 || c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    if (c->head_dim != kvq::kD || c->group != kvq::kG) return false;
+    if (c->max_tokens < 1 || c->residual < 0 || c->residual > (1 << 20)) return false;
+    if ((int64_t)c->batch * c->n_q_heads > (1 << 24)) return false;
+    for (int l = 0; l < c->n_layers; l++)
+        if (!bits_ok(c->kbits[l]) || !bits_ok(c->vbits[l])) return false;
+    return true;
+}
+
+struct LayerPlan {
+    size_t kcode, kmeta, vcode, vmeta, kres, vres;   // byte offsets into the workspace
+};
+
+struct Plan {
+    std::vector<LayerPlan> layer;
+    size_t part_o, part_ml, total;
+    int NB, RC;
+};
+
+Plan make_plan(const kvq_config *c)
+{
+    Plan p;
+    const size_t BH = (size_t)c->batch * c->n_kv_heads;
+    p.NB = c->max_tokens / kvq::kG;                 // N_p never exceeds G * floor(max_tokens / G)
+    p.RC = c->residual + kvq::kG;                   // the fp16 window never holds R + G tokens or more
+    size_t off = 0;
+    p.layer.resize(c->n_layers);
+    for (int l = 0; l < c->n_layers; l++) {
+        LayerPlan &y = p.layer[l];
+        const int kb = c->kbits[l], vb = c->vbits[l];
+        y.kcode = off; off = align_up(off + BH * p.NB * kvq::block_code_bytes(kb));
+        y.kmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(kb));
+        y.vcode = off; off = align_up(off + BH * p.NB * kvq::block_code_bytes(vb));
+        y.vmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(vb));
+        y.kres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
+        y.vres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
+    }
+    const size_t rows = (size_t)c->batch * c->n_q_heads;
+    p.part_o = off; off = align_up(off + rows * kMaxSplits * kvq::kD * sizeof(float));
+    p.part_ml = off; off = align_up(off + rows * kMaxSplits * 2 * sizeof(float));
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+
+struct kvq_ctx {
+    kvq_config cfg;
+    std::vector<uint8_t> kbits, vbits;
+    std::vector<int> tokens;        // T per layer
+    Plan plan;
+    uint8_t *ws;
+    hipStream_t stream;
+    int variant;                    // 0 auto, 1 vector ALU, 2 matrix core
+    int splits;                     // 0 auto
+};
+
+namespace {
+
+int packed_tokens(const kvq_ctx *c, int T)
+{
+    const int over = T - c->cfg.residual;
+    return over > 0 ? kvq::kG * (over / kvq::kG) : 0;
+}
+
+kvq::LayerView view(const kvq_ctx *c, int l)
+{
+    const LayerPlan &y = c->plan.layer[l];
+    kvq::LayerView v;
+    v.kcode = c->ws + y.kcode;
+    v.kmeta = reinterpret_cast<float *>(c->ws + y.kmeta);
+    v.vcode = c->ws + y.vcode;
+    v.vmeta = reinterpret_cast<float *>(c->ws + y.vmeta);
+    v.kres = reinterpret_cast<uint16_t *>(c->ws + y.kres);
+    v.vres = reinterpret_cast<uint16_t *>(c->ws + y.vres);
+    v.kbits = c->kbits[l];
+    v.vbits = c->vbits[l];
+    return v;
+}
+
+int launch_failed(const char *what, hipError_t e)
+{
+    snprintf(g_last_error, sizeof g_last_error, "%s: %s", what, hipGetErrorString(e));
+    return KVQ_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kvq_workspace_bytes(const kvq_config *cfg)
+{
+    if (!config_ok(cfg)) return 0;
+    return make_plan(cfg).total;
+}
+
+int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, size_t workspace_bytes,
+                  void *hip_stream)
+{
+    if (!out) return KVQ_EINVAL;
+    *out = nullptr;
+    if (!config_ok(cfg)) return KVQ_EINVAL;
+    Plan plan = make_plan(cfg);
+    if (!workspace_device || (reinterpret_cast<uintptr_t>(workspace_device) % kAlign) || workspace_bytes < plan.total)
+        return KVQ_EWORKSPACE;
+    kvq_ctx *c = new (std::nothrow) kvq_ctx();
+    if (!c) return KVQ_EINVAL;
+    c->cfg = *cfg;
+    c->kbits.assign(cfg->kbits, cfg->kbits + cfg->n_layers);
+    c->vbits.assign(cfg->vbits, cfg->vbits + cfg->n_layers);
+    c->cfg.kbits = c->kbits.data();
+    c->cfg.vbits = c->vbits.data();
+    c->tokens.assign(cfg->n_layers, 0);
+    c->plan = plan;
+    c->ws = static_cast<uint8_t *>(workspace_device);
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->variant = 0;
+    c->splits = 0;
+    *out = c;
+    return KVQ_OK;
+}
+
+int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const void *v_device, int32_t n_tokens)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_device || !v_device || n_tokens < 1) return KVQ_EINVAL;
+    const int t_old = c->tokens[layer];
+    if ((int64_t)t_old + n_tokens > c->cfg.max_tokens) return KVQ_ECAPACITY;
+    const int t_new = t_old + n_tokens;
+    const int np_old = packed_tokens(c, t_old), np_new = packed_tokens(c, t_new);
+    const int BH = c->cfg.batch * c->cfg.n_kv_heads;
+
+    // 1. quantize the groups that leave the fp16 window: positions [np_old, np_new)
+    if (np_new > np_old) {
+        kvq::QuantArgs a;
+        a.lv = view(c, layer);
+        a.k_in = static_cast<const uint16_t *>(k_device);
+        a.v_in = static_cast<const uint16_t *>(v_device);
+        a.n_in = n_tokens;
+        a.t_old = t_old;
+        a.first_block = np_old / kvq::kG;
+        a.n_blocks = (np_new - np_old) / kvq::kG;
+        a.BH = BH;
+        a.NB = c->plan.NB;
+        a.RC = c->plan.RC;
+        hipError_t e = kvq::launch_quantize(a, c->stream);
+        if (e != hipSuccess) return launch_failed("quantize kernel", e);
+    }
+    // 2. new tokens that stay in the window go to the ring (after step 1 has read the old slots)
+    const int pos0 = np_new > t_old ? np_new : t_old;
+    if (t_new > pos0) {
+        kvq::ResidualCopyArgs a;
+        a.lv = view(c, layer);
+        a.k_in = static_cast<const uint16_t *>(k_device);
+        a.v_in = static_cast<const uint16_t *>(v_device);
+        a.n_in = n_tokens;
+        a.t_old = t_old;
+        a.pos0 = pos0;
+        a.pos1 = t_new;
+        a.BH = BH;
+        a.RC = c->plan.RC;
+        hipError_t e = kvq::launch_residual_copy(a, c->stream);
+        if (e != hipSuccess) return launch_failed("window copy kernel", e);
+    }
+    c->tokens[layer] = t_new;
+    return KVQ_OK;
+}
+
+int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *out_device)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
+    const int T = c->tokens[layer];
+    if (T < 1) return KVQ_ESTATE;
+    const int np = packed_tokens(c, T);
+    kvq::DecodeArgs a;
+    a.lv = view(c, layer);
+    a.q = static_cast<const uint16_t *>(q_device);
+    a.out = static_cast<uint16_t *>(out_device);
+    a.part_o = reinterpret_cast<float *>(c->ws + c->plan.part_o);
+    a.part_ml = reinterpret_cast<float *>(c->ws + c->plan.part_ml);
+    a.B = c->cfg.batch;
+    a.Hq = c->cfg.n_q_heads;
+    a.Hkv = c->cfg.n_kv_heads;
+    a.n_blocks = np / kvq::kG;
+    a.n_res = T - np;
+    a.NB = c->plan.NB;
+    a.RC = c->plan.RC;
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
+    const int units = a.n_blocks + (a.n_res + 31) / 32;
+    int splits = c->splits;
+    if (splits <= 0) {
+        const int BH = a.B * a.Hkv;
+        splits = (1024 + BH - 1) / BH;           // about four 256-thread groups per compute unit
+        const int cap = (units + 3) / 4;         // at least four units per group
+        if (splits > cap) splits = cap;
+    }
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits > units) splits = units;
+    if (splits < 1) splits = 1;
+    a.units_per_split = (units + splits - 1) / splits;
+    a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
+    const int variant = c->variant == 0 ? 1 : c->variant;
+    hipError_t e = variant == 2 ? kvq::launch_decode_mfma(a, c->stream) : kvq::launch_decode_valu(a, c->stream);
+    if (e != hipSuccess) return launch_failed("decode kernel", e);
+    e = kvq::launch_combine(a, c->stream);
+    if (e != hipSuccess) return launch_failed("combine kernel", e);
+    return KVQ_OK;
+}
+
+int kvq_layer_tokens(const kvq_ctx *c, int32_t layer, int32_t *n_packed, int32_t *n_residual)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !n_packed || !n_residual) return KVQ_EINVAL;
+    const int T = c->tokens[layer];
+    *n_packed = packed_tokens(c, T);
+    *n_residual = T - *n_packed;
+    return KVQ_OK;
+}
+
+int kvq_reset(kvq_ctx *c, int32_t layer)
+{
+    if (!c || layer < -1 || layer >= c->cfg.n_layers) return KVQ_EINVAL;
+    for (int l = 0; l < c->cfg.n_layers; l++)
+        if (layer < 0 || l == layer) c->tokens[l] = 0;
+    return KVQ_OK;
+}
+
+int kvq_debug_export(kvq_ctx *c, int32_t layer, void *k_codes, void *k_scale, void *k_zero, void *v_codes,
+                     void *v_scale, void *v_zero, void *k_res, void *v_res)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVQ_EINVAL;
+    const int T = c->tokens[layer];
+    kvq::ExportArgs a;
+    a.lv = view(c, layer);
+    a.k_codes = static_cast<uint8_t *>(k_codes);
+    a.v_codes = static_cast<uint8_t *>(v_codes);
+    a.k_scale = static_cast<float *>(k_scale);
+    a.k_zero = static_cast<float *>(k_zero);
+    a.v_scale = static_cast<float *>(v_scale);
+    a.v_zero = static_cast<float *>(v_zero);
+    a.k_res = static_cast<uint16_t *>(k_res);
+    a.v_res = static_cast<uint16_t *>(v_res);
+    a.n_packed = packed_tokens(c, T);
+    a.n_res = T - a.n_packed;
+    a.BH = c->cfg.batch * c->cfg.n_kv_heads;
+    a.NB = c->plan.NB;
+    a.RC = c->plan.RC;
+    if (T == 0) return KVQ_OK;
+    hipError_t e = kvq::launch_export(a, c->stream);
+    if (e != hipSuccess) return launch_failed("export kernel", e);
+    return KVQ_OK;
+}
+
+int kvq_set_decode_options(kvq_ctx *c, int32_t variant, int32_t splits)
+{
+    if (!c || variant < 0 || variant > 2 || splits < 0 || splits > kMaxSplits) return KVQ_EINVAL;
+    c->variant = variant;
+    c->splits = splits;
+    return KVQ_OK;
+}
+
+void kvq_destroy(kvq_ctx *c) { delete c; }
+
+const char *kvq_strerror(int status)
+{
+    switch (status) {
+    case KVQ_OK: return "ok";
+    case KVQ_EINVAL: return "invalid argument (null pointer, layer index, bits, shape or group)";
+    case KVQ_ECAPACITY: return "append exceeds max_tokens";
+    case KVQ_ESTATE: return "layer holds no token";
+    case KVQ_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case KVQ_ELAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+const char *kvq_last_error(void) { return g_last_error; }
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvq_layout.h"
+
+namespace kvq {
+
+// Device pointers of one layer's cache inside the workspace.
+struct LayerView {
+    uint8_t *kcode;       // [BH][NB] blocks of block_code_bytes(kbits)
+    float *kmeta;         // [BH][NB][256] (absent when kbits == 16)
+    uint8_t *vcode;       // [BH][NB] blocks of block_code_bytes(vbits)
+    float *vmeta;         // [BH][NB][256] (absent when vbits == 16)
+    uint16_t *kres;       // [BH][RC][128] fp16 ring, slot = position % RC
+    uint16_t *vres;
+    int kbits, vbits;
+};
+
+struct QuantArgs {
+    LayerView lv;
+    const uint16_t *k_in, *v_in;   // fp16 [BH][n_in][128], the tokens of this append
+    int n_in;                      // tokens in this append
+    int t_old;                     // tokens held before this append
+    int first_block;               // first block to write (= old N_p / 32)
+    int n_blocks;                  // blocks to write
+    int BH;                        // batch * kv heads
+    int NB;                        // block capacity per (b, h)
+    int RC;                        // ring capacity (R + G)
+};
+
+struct ResidualCopyArgs {
+    LayerView lv;
+    const uint16_t *k_in, *v_in;
+    int n_in, t_old;
+    int pos0, pos1;                // absolute positions [pos0, pos1) to copy from the input into the ring
+    int BH, RC;
+};
+
+struct ExportArgs {
+    LayerView lv;
+    uint8_t *k_codes, *v_codes;
+    float *k_scale, *k_zero, *v_scale, *v_zero;
+    uint16_t *k_res, *v_res;
+    int n_packed, n_res;
+    int BH, NB, RC;
+};
+
+struct DecodeArgs {
+    LayerView lv;
+    const uint16_t *q;     // fp16 [B][Hq][128]
+    uint16_t *out;         // fp16 [B][Hq][128]
+    float *part_o;         // [B*Hq][splits][128] un-normalised partial outputs
+    float *part_ml;        // [B*Hq][splits][2]   (running max in log2 units, sum)
+    int B, Hq, Hkv;
+    int n_blocks;          // quantized blocks (N_p / 32)
+    int n_res;             // fp16 tokens at positions [32*n_blocks, 32*n_blocks + n_res)
+    int NB, RC;
+    int splits;            // gridDim.x
+    int units_per_split;   // work units (blocks, then chunks of <= 32 fp16 tokens) per split
+    float scale_log2e;     // log2(e) / sqrt(D)
+};
+
+hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);
+hipError_t launch_residual_copy(const ResidualCopyArgs &a, hipStream_t s);
+hipError_t launch_export(const ExportArgs &a, hipStream_t s);
+hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s);
+hipError_t launch_combine(const DecodeArgs &a, hipStream_t s);
+
+}  // namespace kvq

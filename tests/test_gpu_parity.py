@@ -1,0 +1,255 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: packed codes, scales, zero-points and the fp16 window are compared bit for bit through the
+canonical export; attention outputs must satisfy max|gpu - oracle| <= 2e-3 and
+||gpu - oracle||_2 / ||oracle||_2 <= 1e-3 per layer tensor (fp16 outputs, fp32 accumulation).
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvq_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-3
+REL_L2 = 1e-3
+
+
+@pytest.fixture(scope="module")
+def kvq_mod():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_04420_amd as pkg
+
+    pkg.load_library()          # raises if the HIP library is not built: no fallback
+    return pkg
+
+
+def _np(t):
+    t = t.cpu()
+    return t.view(torch.uint16).numpy() if t.dtype == torch.float16 else t.numpy()
+
+
+def assert_export_equal(gpu_dump, ora_dump, where=""):
+    assert gpu_dump["n_packed"] == ora_dump["n_packed"] and gpu_dump["n_residual"] == ora_dump["n_residual"], where
+    for key in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_res", "v_res"):
+        if key not in ora_dump:
+            assert key not in gpu_dump
+            continue
+        g, o = _np(gpu_dump[key]), ora_dump[key]
+        assert g.shape == o.shape, (where, key, g.shape, o.shape)
+        gb, ob = g.view(np.uint8), o.view(np.uint8)
+        if not np.array_equal(gb, ob):
+            bad = np.argwhere(gb != ob)
+            raise AssertionError("%s %s: %d differing bytes, first at %s" % (where, key, len(bad), bad[0]))
+
+
+def assert_outputs_close(gpu_out, ora_out16, ora_out64, where=""):
+    g = gpu_out.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(g)), where
+    err = np.abs(g - ora_out64)
+    rel = np.linalg.norm(g - ora_out64) / max(np.linalg.norm(ora_out64), 1e-30)
+    assert err.max() <= MAX_ABS, (where, "max abs", err.max())
+    assert rel <= REL_L2, (where, "rel l2", rel)
+    return err.max(), rel
+
+
+def _pair(kvq_mod, oracle_mod, w, max_tokens, kbits=None, vbits=None, residual=32):
+    kb = w.kbits if kbits is None else kbits
+    vb = w.vbits if vbits is None else vbits
+    g = kvq_mod.KVQ(len(kb), w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, max_tokens, kb, vb, residual=residual)
+    o = oracle_mod.OracleCache(len(kb), w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, kb, vb, residual=residual)
+    return g, o
+
+
+def test_generator_is_bit_identical_on_cpu_and_gpu(kvq_mod):
+    w = W.config4(batch=2, context=200)
+    for layer in (0, 3):
+        kc, vc = W.kv_tokens(w, layer, 0, 200)
+        kg, vg = W.kv_tokens(w, layer, 0, 200, device="cuda:0")
+        assert torch.equal(kc, kg.cpu()) and torch.equal(vc, vg.cpu())
+        assert torch.equal(W.query(w, layer, 5), W.query(w, layer, 5, device="cuda:0").cpu())
+
+
+def test_config1_every_element(kvq_mod, oracle_mod):
+    """The small correctness configuration: 1 layer, 8 q / 2 kv heads, 512 tokens, K8V4, 4 outlier channels."""
+    w = W.config1()
+    g, o = _pair(kvq_mod, oracle_mod, w, 1024)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    q = W.query(w, 0)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    assert g.layer_tokens(0) == (480, 32)
+    assert_export_equal(g.debug_export(0), o.export(0), "cfg1")
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "cfg1")
+
+
+PAIRS = [(8, 8), (8, 4), (8, 2), (4, 8), (4, 4), (4, 2), (2, 8), (2, 4), (2, 2), (16, 16), (16, 4), (2, 16), (8, 16), (16, 8)]
+
+
+@pytest.mark.parametrize("kb,vb", PAIRS)
+def test_all_precision_pairs(kvq_mod, oracle_mod, kb, vb):
+    """Several blocks plus a ragged fp16 tail (5 blocks + 51 window tokens), batch 2, g_q = 4."""
+    w = W.Workload("pairs", 1, 2, 8, 2, 128, 32 * 6 + 19, [kb], [vb], seed=100 + kb * 17 + vb, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 512)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    q = W.query(w, 0)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    assert_export_equal(g.debug_export(0), o.export(0), "K%dV%d" % (kb, vb))
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "K%dV%d" % (kb, vb))
+
+
+@pytest.mark.parametrize("gq,hkv", [(1, 3), (2, 2), (3, 1), (4, 2), (5, 1), (7, 4), (8, 1), (12, 1), (16, 1)])
+def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv):
+    w = W.Workload("gq", 1, 2, gq * hkv, hkv, 128, 32 * 4 + 7, [4], [2], seed=200 + gq, key_bias_std=20.0)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    q = W.query(w, 0)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    assert_export_equal(g.debug_export(0), o.export(0), "gq%d" % gq)
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "gq%d" % gq)
+
+
+@pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 128])
+def test_short_and_ragged_lengths(kvq_mod, oracle_mod, T):
+    w = W.Workload("short", 1, 1, 4, 1, 128, T, [2], [4], seed=300 + T)
+    g, o = _pair(kvq_mod, oracle_mod, w, 128)
+    K, V = W.kv_tokens(w, 0, 0, T)
+    q = W.query(w, 0)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    assert g.layer_tokens(0) == o.tokens(0)
+    assert_export_equal(g.debug_export(0), o.export(0), "T%d" % T)
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "T%d" % T)
+
+
+@pytest.mark.parametrize("residual", [0, 32, 64])
+@pytest.mark.parametrize("chunks", [[1] * 70, [31, 33, 1, 64, 38, 30], [197], [63, 1, 1, 132]])
+def test_chunked_appends_match_oracle_bulk(kvq_mod, oracle_mod, chunks, residual):
+    """However the tokens arrive, the cache equals the oracle's after one bulk append (window flush logic)."""
+    T = sum(chunks)
+    w = W.Workload("chunks", 1, 2, 4, 2, 128, T, [8], [2], seed=400 + len(chunks), outlier_channels=2)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256, residual=residual)
+    K, V = W.kv_tokens(w, 0, 0, T)
+    o.quantize_append(0, K.numpy(), V.numpy())
+    Kd, Vd = K.cuda(), V.cuda()
+    t = 0
+    for n in chunks:
+        g.quantize_append(0, Kd[:, :, t:t + n].contiguous(), Vd[:, :, t:t + n].contiguous())
+        t += n
+    assert_export_equal(g.debug_export(0), o.export(0), "chunks")
+    q = W.query(w, 0)
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "chunks")
+
+
+def test_decode_loop_with_flushes(kvq_mod, oracle_mod):
+    """Prefill, then 70 decode steps that append one token each (two window flushes), checked every step."""
+    w = W.Workload("loop", 2, 2, 8, 2, 128, 100, [4, 8], [2, 4], seed=500, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256)
+    for layer in range(2):
+        K, V = W.kv_tokens(w, layer, 0, 100)
+        g.quantize_append(layer, K.cuda(), V.cuda())
+        o.quantize_append(layer, K.numpy(), V.numpy())
+    for step in range(70):
+        for layer in range(2):
+            K, V = W.kv_tokens(w, layer, step, step + 1, stream=1, total=70)
+            g.quantize_append(layer, K.cuda(), V.cuda())
+            o.quantize_append(layer, K.numpy(), V.numpy())
+            q = W.query(w, layer, step)
+            out = g.decode_attention(layer, q.cuda())
+            o16, o64 = o.decode_attention(layer, q.numpy())
+            assert_outputs_close(out, o16, o64, "step %d layer %d" % (step, layer))
+        if step in (0, 27, 28, 59, 60, 69):
+            for layer in range(2):
+                assert_export_equal(g.debug_export(layer), o.export(layer), "step %d layer %d" % (step, layer))
+
+
+@pytest.mark.parametrize("variant", [1])
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 64])
+def test_result_does_not_depend_on_splits(kvq_mod, oracle_mod, variant, splits):
+    w = W.Workload("splits", 1, 1, 8, 2, 128, 32 * 40 + 45, [4], [4], seed=600, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 2048)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    q = W.query(w, 0)
+    o16, o64 = o.decode_attention(0, q.numpy())
+    g.set_decode_options(variant, splits)
+    out = g.decode_attention(0, q.cuda())
+    assert_outputs_close(out, o16, o64, "splits %d" % splits)
+    # deterministic: same launch twice gives the same bits
+    out2 = g.decode_attention(0, q.cuda())
+    assert torch.equal(out, out2)
+
+
+def test_biased_keys_gq7_mixed_layers(kvq_mod, oracle_mod):
+    """Shape of the Qwen configuration in small: g_q = 7, keys with a large per-channel offset, K8V2 / K4V2 layers."""
+    w = W.config4(batch=2, context=32 * 20 + 32)
+    w.n_layers, w.kbits, w.vbits = 2, [8, 4], [2, 2]
+    g, o = _pair(kvq_mod, oracle_mod, w, 1024)
+    for layer in range(2):
+        K, V = W.kv_tokens(w, layer, 0, w.context)
+        g.quantize_append(layer, K.cuda(), V.cuda())
+        o.quantize_append(layer, K.numpy(), V.numpy())
+        assert_export_equal(g.debug_export(layer), o.export(layer), "layer %d" % layer)
+        q = W.query(w, layer)
+        out = g.decode_attention(layer, q.cuda())
+        o16, o64 = o.decode_attention(layer, q.numpy())
+        assert_outputs_close(out, o16, o64, "layer %d" % layer)
+
+
+def test_tie_heavy_keys_are_coded_identically(kvq_mod, oracle_mod):
+    """Keys on a coarse dyadic grid (many exact .5 quotients) and constant groups: codes still match bit for bit."""
+    torch.manual_seed(7)
+    B, H, T, D = 1, 2, 96, 128
+    K = (torch.randint(-40, 40, (B, H, T, D)).float() * 0.25).to(torch.float16)
+    K[:, :, :, 5] = 3.0                      # constant channel -> s = 0
+    V = (torch.randint(-6, 7, (B, H, T, D)).float() * 0.5).to(torch.float16)
+    V[:, :, 10, 32:64] = -2.0                # constant value group
+    for kb, vb in ((2, 2), (4, 4), (8, 8)):
+        w = W.Workload("ties", 1, B, 4, H, D, T, [kb], [vb], seed=1)
+        g, o = _pair(kvq_mod, oracle_mod, w, 128)
+        g.quantize_append(0, K.cuda(), V.cuda())
+        o.quantize_append(0, K.numpy(), V.numpy())
+        assert_export_equal(g.debug_export(0), o.export(0), "ties K%dV%d" % (kb, vb))
+
+
+def test_sixteen_bit_mode_equals_exact_attention(kvq_mod, oracle_mod):
+    w = W.Workload("fp16", 1, 2, 8, 2, 128, 300, [16], [16], seed=700)
+    g, _ = _pair(kvq_mod, oracle_mod, w, 512)
+    K, V = W.kv_tokens(w, 0, 0, 300)
+    q = W.query(w, 0)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    out = g.decode_attention(0, q.cuda())
+    e16, e64 = oracle_mod.attention_exact(q.numpy(), K.numpy(), V.numpy())
+    assert_outputs_close(out, e16, e64, "fp16 exact")
+
+
+def test_reset_and_reuse(kvq_mod, oracle_mod):
+    w = W.Workload("reset", 1, 1, 4, 1, 128, 80, [4], [4], seed=800)
+    g, o = _pair(kvq_mod, oracle_mod, w, 128)
+    K, V = W.kv_tokens(w, 0, 0, 80)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    g.reset(0)
+    assert g.layer_tokens(0) == (0, 0)
+    with pytest.raises(kvq_mod.KVQError):
+        g.decode_attention(0, W.query(w, 0).cuda())
+    K2, V2 = W.kv_tokens(w, 0, 0, 70, stream=1, total=70)
+    g.quantize_append(0, K2.cuda(), V2.cuda())
+    o.quantize_append(0, K2.numpy(), V2.numpy())
+    assert_export_equal(g.debug_export(0), o.export(0), "after reset")
+    with pytest.raises(kvq_mod.KVQError):
+        g.quantize_append(0, K.cuda(), V.cuda())       # 70 + 80 > 128 tokens
