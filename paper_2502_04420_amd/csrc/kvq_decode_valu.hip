@@ -190,11 +190,13 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
             *reinterpret_cast<float4 *>(&vmeta_lds[wave][4 * lane]) =
                 *reinterpret_cast<const float4 *>(a.lv.vmeta + blk_index * 256 + 4 * lane);
             wave_lds_sync();
-            float sv[8][4], zv[8][4];
+            float sv[4][8], zv[4][8];     // [channel group][token 8*kq + e]
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                *reinterpret_cast<float4 *>(&sv[e][0]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][4 * (8 * kq + e)]);
-                *reinterpret_cast<float4 *>(&zv[e][0]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][kD + 4 * (8 * kq + e)]);
+            for (int gd = 0; gd < 4; gd++) {
+                *reinterpret_cast<float4 *>(&sv[gd][0]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][32 * gd + 8 * kq]);
+                *reinterpret_cast<float4 *>(&sv[gd][4]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][32 * gd + 8 * kq + 4]);
+                *reinterpret_cast<float4 *>(&zv[gd][0]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][kD + 32 * gd + 8 * kq]);
+                *reinterpret_cast<float4 *>(&zv[gd][4]) = *reinterpret_cast<const float4 *>(&vmeta_lds[wave][kD + 32 * gd + 8 * kq + 4]);
             }
             float p8[GQ][8];
 #pragma unroll
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 float vh[8];
 #pragma unroll
                 for (int e = 0; e < 8; e++)
-                    vh[e] = fmaf(code_as_float<VB>(dw, 8 * cblk + e), sv[e][cblk >> 1], zv[e][cblk >> 1]);
+                    vh[e] = fmaf(code_as_float<VB>(dw, 8 * cblk + e), sv[cblk >> 1][e], zv[cblk >> 1][e]);
 #pragma unroll
                 for (int j = 0; j < GQ; j++)
 #pragma unroll

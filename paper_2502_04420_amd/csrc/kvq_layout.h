@@ -21,7 +21,7 @@
 //
 // Metadata of a block: 128 scales then 128 zero-points, fp32.
 //   keys  : index = channel              (per channel over the block's 32 tokens)
-//   values: index = 4*token + channel/32 (per token over 32 channels)
+//   values: index = 32*(channel/32) + token (per token over 32 channels)
 //
 // 16-"bit" tensors keep fp16 rows [token][128] (no metadata); a block is 8 KiB.
 #pragma once

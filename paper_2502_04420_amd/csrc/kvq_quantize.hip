@@ -130,8 +130,8 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             if ((c16 & 3) == 0) {
                 const int gd = c16 >> 2;
                 const float s = scale_of(mn, mx, VB);
-                vs[4 * t + gd] = s; vz[4 * t + gd] = mn;
-                meta[4 * t + gd] = s; meta[kD + 4 * t + gd] = mn;
+                vs[32 * gd + t] = s; vz[32 * gd + t] = mn;
+                meta[32 * gd + t] = s; meta[kD + 32 * gd + t] = mn;
             }
         }
     }
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             for (int e = 0; e < 8; e++) {
                 const int t = 8 * kq + e;
                 const float x = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                const uint32_t c = encode<VB>(x, vs[4 * t + gd], vz[4 * t + gd]);
+                const uint32_t c = encode<VB>(x, vs[32 * gd + t], vz[32 * gd + t]);
                 dw[code_dword<VB>(8 * m + e)] |= c << code_shift<VB>(8 * m + e);
             }
         }
@@ -268,8 +268,10 @@ __global__ void export_meta(ExportArgs a, int which)   // 0 = keys, 1 = values
     const int bh = (int)(idx / ((long long)kD * (a.n_packed / kG)));
     const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * 256;
     float *so = which == 0 ? a.k_scale : a.v_scale, *zo = which == 0 ? a.k_zero : a.v_zero;
-    if (so) so[idx] = meta[within];
-    if (zo) zo[idx] = meta[kD + within];
+    // canonical value metadata is [token][group]; the device keeps [group][token]
+    const int src = which == 0 ? within : 32 * (within & 3) + (within >> 2);
+    if (so) so[idx] = meta[src];
+    if (zo) zo[idx] = meta[kD + src];
 }
 
 // fp16 tensors: rows [bh][token][128]; one thread per 16 bytes.  which: 0/1 = 16-bit keys / values of the

@@ -26,6 +26,12 @@ def kvq_mod():
     return pkg
 
 
+@pytest.fixture(params=[1, 2], ids=["valu", "mfma"])
+def variant(request):
+    """Decode kernel variant: 1 = vector ALU, 2 = matrix core."""
+    return request.param
+
+
 def _np(t):
     t = t.cpu()
     return t.view(torch.uint16).numpy() if t.dtype == torch.float16 else t.numpy()
@@ -55,10 +61,11 @@ def assert_outputs_close(gpu_out, ora_out16, ora_out64, where=""):
     return err.max(), rel
 
 
-def _pair(kvq_mod, oracle_mod, w, max_tokens, kbits=None, vbits=None, residual=32):
+def _pair(kvq_mod, oracle_mod, w, max_tokens, kbits=None, vbits=None, residual=32, variant=0):
     kb = w.kbits if kbits is None else kbits
     vb = w.vbits if vbits is None else vbits
     g = kvq_mod.KVQ(len(kb), w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, max_tokens, kb, vb, residual=residual)
+    g.set_decode_options(variant, 0)
     o = oracle_mod.OracleCache(len(kb), w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, kb, vb, residual=residual)
     return g, o
 
@@ -72,10 +79,10 @@ def test_generator_is_bit_identical_on_cpu_and_gpu(kvq_mod):
         assert torch.equal(W.query(w, layer, 5), W.query(w, layer, 5, device="cuda:0").cpu())
 
 
-def test_config1_every_element(kvq_mod, oracle_mod):
+def test_config1_every_element(kvq_mod, oracle_mod, variant):
     """The small correctness configuration: 1 layer, 8 q / 2 kv heads, 512 tokens, K8V4, 4 outlier channels."""
     w = W.config1()
-    g, o = _pair(kvq_mod, oracle_mod, w, 1024)
+    g, o = _pair(kvq_mod, oracle_mod, w, 1024, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, w.context)
     q = W.query(w, 0)
     g.quantize_append(0, K.cuda(), V.cuda())
@@ -91,10 +98,10 @@ PAIRS = [(8, 8), (8, 4), (8, 2), (4, 8), (4, 4), (4, 2), (2, 8), (2, 4), (2, 2),
 
 
 @pytest.mark.parametrize("kb,vb", PAIRS)
-def test_all_precision_pairs(kvq_mod, oracle_mod, kb, vb):
+def test_all_precision_pairs(kvq_mod, oracle_mod, kb, vb, variant):
     """Several blocks plus a ragged fp16 tail (5 blocks + 51 window tokens), batch 2, g_q = 4."""
     w = W.Workload("pairs", 1, 2, 8, 2, 128, 32 * 6 + 19, [kb], [vb], seed=100 + kb * 17 + vb, outlier_channels=3)
-    g, o = _pair(kvq_mod, oracle_mod, w, 512)
+    g, o = _pair(kvq_mod, oracle_mod, w, 512, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, w.context)
     q = W.query(w, 0)
     g.quantize_append(0, K.cuda(), V.cuda())
@@ -106,9 +113,9 @@ def test_all_precision_pairs(kvq_mod, oracle_mod, kb, vb):
 
 
 @pytest.mark.parametrize("gq,hkv", [(1, 3), (2, 2), (3, 1), (4, 2), (5, 1), (7, 4), (8, 1), (12, 1), (16, 1)])
-def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv):
+def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv, variant):
     w = W.Workload("gq", 1, 2, gq * hkv, hkv, 128, 32 * 4 + 7, [4], [2], seed=200 + gq, key_bias_std=20.0)
-    g, o = _pair(kvq_mod, oracle_mod, w, 256)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, w.context)
     q = W.query(w, 0)
     g.quantize_append(0, K.cuda(), V.cuda())
@@ -120,9 +127,9 @@ def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv):
 
 
 @pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 128])
-def test_short_and_ragged_lengths(kvq_mod, oracle_mod, T):
+def test_short_and_ragged_lengths(kvq_mod, oracle_mod, T, variant):
     w = W.Workload("short", 1, 1, 4, 1, 128, T, [2], [4], seed=300 + T)
-    g, o = _pair(kvq_mod, oracle_mod, w, 128)
+    g, o = _pair(kvq_mod, oracle_mod, w, 128, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, T)
     q = W.query(w, 0)
     g.quantize_append(0, K.cuda(), V.cuda())
@@ -136,11 +143,11 @@ def test_short_and_ragged_lengths(kvq_mod, oracle_mod, T):
 
 @pytest.mark.parametrize("residual", [0, 32, 64])
 @pytest.mark.parametrize("chunks", [[1] * 70, [31, 33, 1, 64, 38, 30], [197], [63, 1, 1, 132]])
-def test_chunked_appends_match_oracle_bulk(kvq_mod, oracle_mod, chunks, residual):
+def test_chunked_appends_match_oracle_bulk(kvq_mod, oracle_mod, chunks, residual, variant):
     """However the tokens arrive, the cache equals the oracle's after one bulk append (window flush logic)."""
     T = sum(chunks)
     w = W.Workload("chunks", 1, 2, 4, 2, 128, T, [8], [2], seed=400 + len(chunks), outlier_channels=2)
-    g, o = _pair(kvq_mod, oracle_mod, w, 256, residual=residual)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256, residual=residual, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, T)
     o.quantize_append(0, K.numpy(), V.numpy())
     Kd, Vd = K.cuda(), V.cuda()
@@ -155,10 +162,10 @@ def test_chunked_appends_match_oracle_bulk(kvq_mod, oracle_mod, chunks, residual
     assert_outputs_close(out, o16, o64, "chunks")
 
 
-def test_decode_loop_with_flushes(kvq_mod, oracle_mod):
+def test_decode_loop_with_flushes(kvq_mod, oracle_mod, variant):
     """Prefill, then 70 decode steps that append one token each (two window flushes), checked every step."""
     w = W.Workload("loop", 2, 2, 8, 2, 128, 100, [4, 8], [2, 4], seed=500, outlier_channels=3)
-    g, o = _pair(kvq_mod, oracle_mod, w, 256)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256, variant=variant)
     for layer in range(2):
         K, V = W.kv_tokens(w, layer, 0, 100)
         g.quantize_append(layer, K.cuda(), V.cuda())
@@ -177,7 +184,6 @@ def test_decode_loop_with_flushes(kvq_mod, oracle_mod):
                 assert_export_equal(g.debug_export(layer), o.export(layer), "step %d layer %d" % (step, layer))
 
 
-@pytest.mark.parametrize("variant", [1])
 @pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 64])
 def test_result_does_not_depend_on_splits(kvq_mod, oracle_mod, variant, splits):
     w = W.Workload("splits", 1, 1, 8, 2, 128, 32 * 40 + 45, [4], [4], seed=600, outlier_channels=3)
@@ -195,11 +201,11 @@ def test_result_does_not_depend_on_splits(kvq_mod, oracle_mod, variant, splits):
     assert torch.equal(out, out2)
 
 
-def test_biased_keys_gq7_mixed_layers(kvq_mod, oracle_mod):
+def test_biased_keys_gq7_mixed_layers(kvq_mod, oracle_mod, variant):
     """Shape of the Qwen configuration in small: g_q = 7, keys with a large per-channel offset, K8V2 / K4V2 layers."""
     w = W.config4(batch=2, context=32 * 20 + 32)
     w.n_layers, w.kbits, w.vbits = 2, [8, 4], [2, 2]
-    g, o = _pair(kvq_mod, oracle_mod, w, 1024)
+    g, o = _pair(kvq_mod, oracle_mod, w, 1024, variant=variant)
     for layer in range(2):
         K, V = W.kv_tokens(w, layer, 0, w.context)
         g.quantize_append(layer, K.cuda(), V.cuda())
@@ -227,9 +233,9 @@ def test_tie_heavy_keys_are_coded_identically(kvq_mod, oracle_mod):
         assert_export_equal(g.debug_export(0), o.export(0), "ties K%dV%d" % (kb, vb))
 
 
-def test_sixteen_bit_mode_equals_exact_attention(kvq_mod, oracle_mod):
+def test_sixteen_bit_mode_equals_exact_attention(kvq_mod, oracle_mod, variant):
     w = W.Workload("fp16", 1, 2, 8, 2, 128, 300, [16], [16], seed=700)
-    g, _ = _pair(kvq_mod, oracle_mod, w, 512)
+    g, _ = _pair(kvq_mod, oracle_mod, w, 512, variant=variant)
     K, V = W.kv_tokens(w, 0, 0, 300)
     q = W.query(w, 0)
     g.quantize_append(0, K.cuda(), V.cuda())
