@@ -38,7 +38,7 @@ bool config_ok(const kvq_config *c)
 }
 
 struct LayerPlan {
-    size_t kcode, kmeta, vcode, vmeta, kres, vres;   // byte offsets into the workspace
+    size_t kcode, kmeta, vcode, vmeta, bexp, kres, vres;   // byte offsets into the workspace
 };
 
 struct Plan {
@@ -62,6 +62,7 @@ Plan make_plan(const kvq_config *c)
         y.kmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(kb));
         y.vcode = off; off = align_up(off + BH * p.NB * kvq::block_code_bytes(vb));
         y.vmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(vb));
+        y.bexp = off; off = align_up(off + BH * p.NB * sizeof(uint32_t));
         y.kres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
         y.vres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
     }
@@ -101,6 +102,7 @@ kvq::LayerView view(const kvq_ctx *c, int l)
     v.kmeta = reinterpret_cast<float *>(c->ws + y.kmeta);
     v.vcode = c->ws + y.vcode;
     v.vmeta = reinterpret_cast<float *>(c->ws + y.vmeta);
+    v.bexp = reinterpret_cast<uint32_t *>(c->ws + y.bexp);
     v.kres = reinterpret_cast<uint16_t *>(c->ws + y.kres);
     v.vres = reinterpret_cast<uint16_t *>(c->ws + y.vres);
     v.kbits = c->kbits[l];

@@ -6,10 +6,10 @@
 //   scores   sum_d q_d (c_td s_d + z_d) = sum_d (q_d s_d) c_td + sum_d q_d z_d
 //   output   sum_t p_t (c_td s_tg + z_tg) = sum_t (p_t s_tg) c_td + sum_t p_t z_tg
 //
-// The integer codes are the B operand.  Masked into the low mantissa bits of an fp16 lane
-// they are subnormal halves worth c * 2^-24 (times a power of two that depends on the bit
-// position and is folded into the A operand), so "conversion" is one AND per two codes and
-// is exact.  The A operand carries q_d s_d (scores) or p_t s_tg (output); to keep fp32-class
+// The integer codes are the B operand.  Masked into the mantissa of an fp16 1.0 they read as
+// 1 + c * 2^-k exactly (k depends on the bit position; differences are folded into the A
+// operand), so "conversion" is about one AND-OR per two codes; the "1 +" part is measured by
+// one more MFMA of the same A tile against all-ones and subtracted.  The A operand carries q_d s_d (scores) or p_t s_tg (output); to keep fp32-class
 // accuracy it is split into a high and a low fp16 part held in rows j and 8 + j of the 16-row
 // tile (j = query head within the group, at most 8), and the two partial results are added
 // after the MFMA.  The zero-point terms: q . z is one more MFMA per 32 channels (q and z are
@@ -43,33 +43,43 @@ __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, ui
 __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
 
-// B operand of MFMA m (8 codes of this lane) straight from the packed dwords: element e of the
-// operand is worth code * 2^-24 / code_weight<BITS>(e).
+// B operand of MFMA m (8 codes of this lane) straight from the packed dwords.  Each code is
+// masked into the mantissa of an fp16 whose exponent field is forced to that of 1.0, so element
+// e of the operand is exactly 1 + code * 2^-kCodeShift<BITS> * code_weight<BITS>(e): a normal
+// number (the matrix core keeps about 24 bits below the largest *nominal* exponent of a sum, so
+// subnormal operands would lose precision).  The "1 +" is removed by one more MFMA of the same A
+// tile against an all-ones B tile.
+constexpr uint32_t kOne2 = 0x3C003C00u;      // two fp16 1.0
+
+template <int BITS> struct CodeShift { static constexpr int value = BITS == 8 ? 10 : 6; };
+
 template <int BITS>
 __device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m)
 {
     if constexpr (BITS == 8) {
+        // bytes (b0, b1), (b2, b3) -> halves 0x3C00 | b : 1 + b / 1024
         const uint32_t w0 = dw[2 * m], w1 = dw[2 * m + 1];
-        return as_half8(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u), __builtin_amdgcn_perm(0u, w0, 0x0C030C02u),
-                        __builtin_amdgcn_perm(0u, w1, 0x0C010C00u), __builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
+        return as_half8(__builtin_amdgcn_perm(kOne2, w0, 0x05010500u), __builtin_amdgcn_perm(kOne2, w0, 0x05030502u),
+                        __builtin_amdgcn_perm(kOne2, w1, 0x05010500u), __builtin_amdgcn_perm(kOne2, w1, 0x05030502u));
     } else if constexpr (BITS == 4) {
-        const uint32_t x = dw[m], y = x >> 8;
-        return as_half8(x & 0x000F000Fu, x & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
+        // nibbles (k, k + 4) moved to mantissa bits 7:4 of each half: 1 + c / 64
+        const uint32_t x = dw[m], msk = 0x00F000F0u;
+        return as_half8(((x << 4) & msk) | kOne2, (x & msk) | kOne2, ((x >> 4) & msk) | kOne2, ((x >> 8) & msk) | kOne2);
     } else {
-        const uint32_t x = dw[m >> 1] >> (8 * (m & 1));
-        return as_half8(x & 0x00030003u, x & 0x000C000Cu, x & 0x00300030u, x & 0x00C000C0u);
+        // 2-bit fields at mantissa bits 5:4 (1 + c / 64) or 7:6 (1 + c / 16), alternating
+        const uint32_t x = dw[m >> 1], lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
+        return as_half8((lo & 0x00300030u) | kOne2, (lo & 0x00C000C0u) | kOne2, (hi & 0x00300030u) | kOne2,
+                        (hi & 0x00C000C0u) | kOne2);
     }
 }
 
-// power of two by which the A operand must be divided for element e (the code sits at a
-// higher bit position inside its halfword)
+// power of two by which the A operand must be divided for element e (its code sits two bits
+// higher in the mantissa than the base position)
 template <int BITS>
 __device__ __forceinline__ float code_weight_inv(int e)
 {
-    if (BITS == 8) return 1.0f;
-    if (BITS == 4) return ((e >> 1) & 1) ? 0.0625f : 1.0f;
-    const int v = (e >> 1) & 3;
-    return v == 0 ? 1.0f : v == 1 ? 0.25f : v == 2 ? 0.0625f : 0.015625f;
+    if (BITS == 2) return ((e >> 1) & 1) ? 0.25f : 1.0f;
+    return 1.0f;
 }
 
 // split two fp32 values into fp16 high parts and (scaled by 2^11) fp16 low parts
@@ -86,11 +96,13 @@ struct BlockRegs {
     uint32_t kdw[KB < 16 ? 2 * KB : 1];
     uint32_t vdw[VB < 16 ? 2 * VB : 1];
     float2 ks, kz, vs, vz;
+    uint32_t bexp;               // exponents of the block's largest key scale (low half) and value scale (high half)
 };
 
 template <int KB, int VB>
 __device__ __forceinline__ void load_block(const DecodeArgs &a, size_t blk_index, int lane, BlockRegs<KB, VB> &r)
 {
+    r.bexp = a.lv.bexp[blk_index];
     if constexpr (KB < 16) {
         const uint8_t *blk = a.lv.kcode + blk_index * block_code_bytes(KB);
 #pragma unroll
@@ -115,11 +127,248 @@ __device__ __forceinline__ void load_block(const DecodeArgs &a, size_t blk_index
     }
 }
 
+// max over the 16 lanes of a DPP row (lanes that share lane >> 4), result in every lane
+__device__ __forceinline__ float row_max16(float x)
+{
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false)));   // quad_perm [1,0,3,2]
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false)));   // quad_perm [2,3,0,1]
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xf, 0xf, false)));  // row_half_mirror
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xf, 0xf, false)));  // row_mirror
+    return x;
+}
+
+__device__ __forceinline__ float row_sum16(float x)
+{
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xf, 0xf, false));
+    return x;
+}
+
+// lo = the value held by lanes 0..31, hi = the value held by lanes 32..63, both in every lane.
+// Written as inline assembly: the compiler builtin for this instruction returned its first
+// result twice with this toolchain.  The s_nop covers the VALU-write -> permlane read hazard.
+__device__ __forceinline__ void halves_of(float x, float &lo, float &hi)
+{
+    uint32_t a = __builtin_bit_cast(uint32_t, x), b = a;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    lo = __builtin_bit_cast(float, a);      // [x.lanes0-31, x.lanes0-31]
+    hi = __builtin_bit_cast(float, b);      // [x.lanes32-63, x.lanes32-63]
+}
+
+// LDS scratch of one wave
+template <int GQ>
+struct WaveLds {
+    _Float16 Ak[16][kD + 8];       // score A tiles [row][channel]: rows j = high parts, 8 + j = low parts
+    _Float16 Zk[kD];               // key zero-points as fp16 (exact)
+    float P[GQ][32];               // softmax numerators of the current block
+    _Float16 Av[4][16][32 + 8];    // output A tiles [channel group][row][token]
+};
+
+template <int GQ>
+struct WaveState {
+    float m[4], l[4];              // rows 4*rq + i of the 16-row tile: running max (log2 units), partial sum
+    float4v O[8];                  // un-normalised output tile per 16-channel block, scaled, "1 +" part included
+    float4v On[4];                 // per channel group: row sums of the A tiles (the "1 +" part of O)
+    float oF[GQ][2];               // fp16-row contributions, channels 2*lane, 2*lane+1
+    float accz[GQ];                // sum_t p_t z_tg for group rq, tokens 2n, 2n+1
+    int ev;                        // O is held times 2^(14 - ev - 24); ev = largest value-scale exponent so far
+};
+
+template <int GQ>
+struct QueryRegs {
+    float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
+    half8 Aq[4];                   // exact fp16 queries as A tiles (rows j and 8 + j)
+    float c, alpha_h, alpha_l;     // log2(e)/sqrt(D); weights of the high / low partial scores
+    float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
+};
+
+// scores of a quantized block: s[th][i] for rows 4*rq + i, tokens 16*th + n
+template <int KB, int VB, int GQ>
+__device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, const QueryRegs<GQ> &Q, WaveLds<GQ> &L,
+                                              int lane, float (&s)[2][4])
+{
+    const int n = lane & 15, rq = lane >> 4;
+    // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
+    const int ek = (int)(blk.bexp & 0xffffu) - 32768;
+    const float ks0 = ldexpf(blk.ks.x, 14 - ek), ks1 = ldexpf(blk.ks.y, 14 - ek);
+    const float ah = ldexpf(Q.alpha_h, ek - 14), al = ldexpf(Q.alpha_l, ek - 14);
+#pragma unroll
+    for (int j = 0; j < GQ; j++) {
+        uint32_t hi, lo;
+        split_pair(Q.q2[j][0] * ks0, Q.q2[j][1] * ks1, hi, lo);
+        *reinterpret_cast<uint32_t *>(&L.Ak[j][2 * lane]) = hi;
+        *reinterpret_cast<uint32_t *>(&L.Ak[8 + j][2 * lane]) = lo;
+    }
+    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.kz.x, blk.kz.y));
+    wave_lds_sync();
+    float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0, Dn = S0;
+    const half8 ones = as_half8(kOne2, kOne2, kOne2, kOne2);
+#pragma unroll
+    for (int cb = 0; cb < 4; cb++) {
+        const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
+        const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, cb), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, 4 + cb), S1, 0, 0, 0);
+        Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
+        Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], Bz, Z, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        float h0, l0, h1, l1;
+        halves_of(S0[i] - Dn[i], h0, l0);  // lanes 0..31 hold the high-part rows, 32..63 the low-part rows
+        halves_of(S1[i] - Dn[i], h1, l1);
+        const float zc = Q.c * Z[i];
+        s[0][i] = fmaf(ah, h0, fmaf(al, l0, zc));
+        s[1][i] = fmaf(ah, h1, fmaf(al, l1, zc));
+    }
+}
+
+// scores of up to 32 fp16 rows (16-bit region or window ring)
+template <int GQ>
+__device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t *row1, int nt, const QueryRegs<GQ> &Q,
+                                            int lane, float (&s)[2][4])
+{
+    const int n = lane & 15, rq = lane >> 4;
+    float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0;
+#pragma unroll
+    for (int cb = 0; cb < 4; cb++) {
+        uint4 x0 = make_uint4(0, 0, 0, 0), x1 = x0;
+        if (n < nt) x0 = *reinterpret_cast<const uint4 *>(row0 + 32 * cb + 8 * rq);
+        if (16 + n < nt) x1 = *reinterpret_cast<const uint4 *>(row1 + 32 * cb + 8 * rq);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], as_half8(x0.x, x0.y, x0.z, x0.w), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], as_half8(x1.x, x1.y, x1.z, x1.w), S1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        s[0][i] = n < nt ? Q.c * S0[i] : -INFINITY;
+        s[1][i] = 16 + n < nt ? Q.c * S1[i] : -INFINITY;
+    }
+}
+
+// online softmax over the block's 32 scores per row; leaves the numerators in L.P[j][token]
+template <int GQ>
+__device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState<GQ> &W, WaveLds<GQ> &L, int lane)
+{
+    const int n = lane & 15, rq = lane >> 4;
+    float mnew[4];
+    bool grew = false;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        mnew[i] = fmaxf(W.m[i], row_max16(fmaxf(s[0][i], s[1][i])));
+        grew = grew || (mnew[i] > W.m[i]);
+    }
+    if (__any(grew)) {
+        float alpha[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            alpha[i] = exp2f(W.m[i] - mnew[i]);
+            W.l[i] *= alpha[i];
+            W.m[i] = mnew[i];
+        }
+#pragma unroll
+        for (int cblk = 0; cblk < 8; cblk++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) W.O[cblk][i] *= alpha[i];
+#pragma unroll
+        for (int gd = 0; gd < 4; gd++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) W.On[gd][i] *= alpha[i];
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            const float aj = __shfl(alpha[j & 3], 16 * (j >> 2));
+            W.oF[j][0] *= aj; W.oF[j][1] *= aj; W.accz[j] *= aj;
+        }
+    }
+    float p[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        p[0][i] = exp2f(s[0][i] - W.m[i]);
+        p[1][i] = exp2f(s[1][i] - W.m[i]);
+        W.l[i] += p[0][i] + p[1][i];
+    }
+    if (rq < 2) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            if (4 * rq + i < GQ) {
+                L.P[(4 * rq + i) % GQ][n] = p[0][i];
+                L.P[(4 * rq + i) % GQ][16 + n] = p[1][i];
+            }
+        }
+    }
+    wave_lds_sync();
+}
+
+// output contribution of a quantized block
+template <int KB, int VB, int GQ>
+__device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, const QueryRegs<GQ> &Q, WaveState<GQ> &W,
+                                              WaveLds<GQ> &L, int lane)
+{
+    const int n = lane & 15, rq = lane >> 4;
+    // keep p*s at the top of the fp16 range; when a block brings a larger scale, re-base the accumulators (exact)
+    const int ev = (int)(blk.bexp >> 16) - 32768;
+    if (ev > W.ev) {
+#pragma unroll
+        for (int cblk = 0; cblk < 8; cblk++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) W.O[cblk][i] = ldexpf(W.O[cblk][i], W.ev - ev);
+#pragma unroll
+        for (int gd = 0; gd < 4; gd++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) W.On[gd][i] = ldexpf(W.On[gd][i], W.ev - ev);
+        W.ev = ev;
+    }
+    const float sv0 = ldexpf(blk.vs.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(blk.vs.y * Q.vw1, 14 - W.ev);
+#pragma unroll
+    for (int j = 0; j < GQ; j++) {
+        const float2 pp = *reinterpret_cast<const float2 *>(&L.P[j][2 * n]);
+        uint32_t hi, lo;
+        split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
+        *reinterpret_cast<uint32_t *>(&L.Av[rq][j][2 * n]) = hi;
+        *reinterpret_cast<uint32_t *>(&L.Av[rq][8 + j][2 * n]) = lo;
+        W.accz[j] = fmaf(pp.x, blk.vz.x, fmaf(pp.y, blk.vz.y, W.accz[j]));
+    }
+    wave_lds_sync();
+    half8 Aop[4];
+    const half8 ones = as_half8(kOne2, kOne2, kOne2, kOne2);
+#pragma unroll
+    for (int gd = 0; gd < 4; gd++) {
+        Aop[gd] = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
+        W.On[gd] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop[gd], ones, W.On[gd], 0, 0, 0);
+    }
+#pragma unroll
+    for (int cblk = 0; cblk < 8; cblk++)
+        W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop[cblk >> 1], codes_operand<VB>(blk.vdw, cblk), W.O[cblk], 0, 0, 0);
+    wave_lds_sync();
+}
+
+// output contribution of nt fp16 rows: lane owns channels 2*lane, 2*lane+1
+template <int GQ>
+__device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, WaveState<GQ> &W,
+                                            WaveLds<GQ> &L, int lane)
+{
+    for (int tt = 0; tt < nt; tt++) {
+        const int pos = pos0 + tt;
+        const uint16_t *row = base + (size_t)(ring ? pos % ring : pos) * kD;
+        const uint32_t x = *reinterpret_cast<const uint32_t *>(row + 2 * lane);
+        const float v0 = half_lo(x), v1 = half_hi(x);
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            const float pj = L.P[j][tt];
+            W.oF[j][0] = fmaf(pj, v0, W.oF[j][0]);
+            W.oF[j][1] = fmaf(pj, v1, W.oF[j][1]);
+        }
+    }
+    wave_lds_sync();
+}
+
 template <int KB, int VB, int GQ>
 __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows j and 8 + j of a 16-row tile");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform on purpose: block indices stay scalar
     const int n = lane & 15, rq = lane >> 4;
     const int split = blockIdx.x, bh = blockIdx.y;
     const int b = bh / a.Hkv, h = bh % a.Hkv;
@@ -128,247 +377,144 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
     const int nvalid = gq_total - head0 < GQ ? gq_total - head0 : GQ;
     const size_t qrow0 = (size_t)b * a.Hq + (size_t)h * gq_total + head0;
 
-    __shared__ __attribute__((aligned(16))) _Float16 Ak[4][16][kD + 8];   // score A tiles [row][channel]
-    __shared__ __attribute__((aligned(16))) _Float16 Zk[4][kD];           // key zero-points as fp16
-    __shared__ __attribute__((aligned(16))) float P[4][GQ][32];           // softmax numerators of the block
-    __shared__ __attribute__((aligned(16))) _Float16 Av[4][4][16][32 + 8];// output A tiles [group][row][token]
+    __shared__ __attribute__((aligned(16))) WaveLds<GQ> lds[4];
     __shared__ __attribute__((aligned(16))) float o_lds[4][GQ][kD];
     __shared__ float az_lds[4][GQ][4];
     __shared__ float ml_lds[4][GQ][2];
+    WaveLds<GQ> &L = lds[wave];
 
     // rows that are never written must read as zero
-    for (int i = tid; i < 4 * 16 * (kD + 8) / 2; i += 256) reinterpret_cast<uint32_t *>(&Ak[0][0][0])[i] = 0u;
-    for (int i = tid; i < 4 * 4 * 16 * (32 + 8) / 2; i += 256) reinterpret_cast<uint32_t *>(&Av[0][0][0][0])[i] = 0u;
+    for (int i = tid; i < (int)(sizeof(lds) / 4); i += 256) reinterpret_cast<uint32_t *>(&lds[0])[i] = 0u;
 
     // ---- query setup: exact fp16 tiles for the q.z and fp16-row MFMAs, scaled fp32 pairs for q*s
-    const float c = a.scale_log2e;
-    float qraw[GQ][2];
-    float qmax = 0.0f;
-#pragma unroll
-    for (int j = 0; j < GQ; j++) {
-        uint32_t w = 0;
-        if (j < nvalid) w = *reinterpret_cast<const uint32_t *>(a.q + (qrow0 + j) * kD + 2 * lane);
-        qraw[j][0] = half_lo(w) * c;
-        qraw[j][1] = half_hi(w) * c;
-        qmax = fmaxf(qmax, fmaxf(fabsf(qraw[j][0]), fabsf(qraw[j][1])));
-    }
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, s));
-    int qexp = 0;
-    if (qmax > 0.0f) (void)frexpf(qmax, &qexp);          // qmax = f * 2^qexp, f in [0.5, 1)
-    const float alpha_h = ldexpf(1.0f, 24 + qexp);        // undo 2^-24 of the codes and 2^-qexp of q
-    const float alpha_l = ldexpf(1.0f, 13 + qexp);
-    float q2[GQ][2];
-#pragma unroll
-    for (int j = 0; j < GQ; j++) {
-        q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
-        q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
-    }
-    half8 Aq[4];
+    QueryRegs<GQ> Q;
+    Q.c = a.scale_log2e;
     {
+        float qraw[GQ][2];
+        float qmax = 0.0f;
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            uint32_t w = 0;
+            if (j < nvalid) w = *reinterpret_cast<const uint32_t *>(a.q + (qrow0 + j) * kD + 2 * lane);
+            qraw[j][0] = half_lo(w) * Q.c;
+            qraw[j][1] = half_hi(w) * Q.c;
+            qmax = fmaxf(qmax, fmaxf(fabsf(qraw[j][0]), fabsf(qraw[j][1])));
+        }
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, sft));
+        int qexp = 0;
+        if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
+        Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
+        Q.alpha_l = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp - 11);
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
+            Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
+        }
         const int jr = n & 7;
 #pragma unroll
         for (int cb = 0; cb < 4; cb++) {
             uint4 x = make_uint4(0, 0, 0, 0);
             if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 32 * cb + 8 * rq);
-            Aq[cb] = as_half8(x.x, x.y, x.z, x.w);
+            Q.Aq[cb] = as_half8(x.x, x.y, x.z, x.w);
         }
+        Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
+        Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
     }
-    const float vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7), vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
     __syncthreads();
 
-    float m[4], l[4];
-    float4v O[8];
-    float oF[GQ][2], accz[GQ];
+    WaveState<GQ> W;
 #pragma unroll
-    for (int i = 0; i < 4; i++) { m[i] = -INFINITY; l[i] = 0.0f; }
+    for (int i = 0; i < 4; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
 #pragma unroll
-    for (int cblk = 0; cblk < 8; cblk++) O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int j = 0; j < GQ; j++) { oF[j][0] = oF[j][1] = 0.0f; accz[j] = 0.0f; }
+    for (int gd = 0; gd < 4; gd++) W.On[gd] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int j = 0; j < GQ; j++) { W.oF[j][0] = W.oF[j][1] = 0.0f; W.accz[j] = 0.0f; }
+    W.ev = -100;
 
     const int units = a.n_blocks + (a.n_res + 31) / 32;
     const int u0 = split * a.units_per_split;
     const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
+    int u = u0 + wave;
 
-    BlockRegs<KB, VB> cur, nxt;
-    if (u0 + wave < u1 && u0 + wave < a.n_blocks) load_block<KB, VB>(a, (size_t)bh * a.NB + u0 + wave, lane, cur);
+    // ---- hot loop: fully quantized blocks, the next block's loads always in flight.  The prefetch is
+    // unconditional (the index is clamped) so that the wait counters stay exact.
+    if constexpr (KB < 16 && VB < 16) {
+        const int ub = u1 < a.n_blocks ? u1 : a.n_blocks;
+        if (u < ub) {
+            const size_t base = (size_t)bh * a.NB;
+            BlockRegs<KB, VB> r0, r1;
+            load_block<KB, VB>(a, base + u, lane, r0);
+            float s[2][4];
+            while (true) {
+                load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r1);
+                scores_packed<KB, VB, GQ>(r0, Q, L, lane, s);
+                softmax_update<GQ>(s, W, L, lane);
+                output_packed<KB, VB, GQ>(r0, Q, W, L, lane);
+                u += 4;
+                if (u >= ub) break;
+                load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r0);
+                scores_packed<KB, VB, GQ>(r1, Q, L, lane, s);
+                softmax_update<GQ>(s, W, L, lane);
+                output_packed<KB, VB, GQ>(r1, Q, W, L, lane);
+                u += 4;
+                if (u >= ub) break;
+            }
+        }
+    }
 
-    for (int u = u0 + wave; u < u1; u += 4) {
+    // ---- everything else: fp16 window chunks, and blocks of layers that keep K or V in fp16
+    for (; u < u1; u += 4) {
         const bool packed = u < a.n_blocks;
         const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
         const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
-        if (u + 4 < u1 && u + 4 < a.n_blocks) load_block<KB, VB>(a, (size_t)bh * a.NB + u + 4, lane, nxt);
-
-        // ------------------------------------------------ scores
+        BlockRegs<KB, VB> r;
+        if (packed) load_block<KB, VB>(a, (size_t)bh * a.NB + u, lane, r);
         float s[2][4];
         bool k_rows = true;
         if constexpr (KB < 16) if (packed) {
             k_rows = false;
-#pragma unroll
-            for (int j = 0; j < GQ; j++) {
-                uint32_t hi, lo;
-                split_pair(q2[j][0] * cur.ks.x, q2[j][1] * cur.ks.y, hi, lo);
-                *reinterpret_cast<uint32_t *>(&Ak[wave][j][2 * lane]) = hi;
-                *reinterpret_cast<uint32_t *>(&Ak[wave][8 + j][2 * lane]) = lo;
-            }
-            *reinterpret_cast<uint32_t *>(&Zk[wave][2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(cur.kz.x, cur.kz.y));
-            wave_lds_sync();
-            float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0;
-#pragma unroll
-            for (int cb = 0; cb < 4; cb++) {
-                const half8 Aop = *reinterpret_cast<const half8 *>(&Ak[wave][n][32 * cb + 8 * rq]);
-                const half8 Bz = *reinterpret_cast<const half8 *>(&Zk[wave][32 * cb + 8 * rq]);
-                S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(cur.kdw, cb), S0, 0, 0, 0);
-                S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(cur.kdw, 4 + cb), S1, 0, 0, 0);
-                Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aq[cb], Bz, Z, 0, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const float o0 = __shfl_xor(S0[i], 32), o1 = __shfl_xor(S1[i], 32);
-                const float h0 = rq < 2 ? S0[i] : o0, l0 = rq < 2 ? o0 : S0[i];
-                const float h1 = rq < 2 ? S1[i] : o1, l1 = rq < 2 ? o1 : S1[i];
-                s[0][i] = fmaf(alpha_h, h0, fmaf(alpha_l, l0, c * Z[i]));
-                s[1][i] = fmaf(alpha_h, h1, fmaf(alpha_l, l1, c * Z[i]));
-            }
+            scores_packed<KB, VB, GQ>(r, Q, L, lane, s);
         }
         if (k_rows) {
-            float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0;
-            const uint16_t *row0, *row1;
-            {
-                const int p0 = pos0 + n, p1 = pos0 + 16 + n;
-                row0 = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + ((size_t)bh * a.NB * kG + p0) * kD
-                              : a.lv.kres + ((size_t)bh * a.RC + p0 % a.RC) * kD;
-                row1 = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + ((size_t)bh * a.NB * kG + p1) * kD
-                              : a.lv.kres + ((size_t)bh * a.RC + p1 % a.RC) * kD;
-            }
-#pragma unroll
-            for (int cb = 0; cb < 4; cb++) {
-                uint4 x0 = make_uint4(0, 0, 0, 0), x1 = x0;
-                if (n < nt) x0 = *reinterpret_cast<const uint4 *>(row0 + 32 * cb + 8 * rq);
-                if (16 + n < nt) x1 = *reinterpret_cast<const uint4 *>(row1 + 32 * cb + 8 * rq);
-                S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aq[cb], as_half8(x0.x, x0.y, x0.z, x0.w), S0, 0, 0, 0);
-                S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aq[cb], as_half8(x1.x, x1.y, x1.z, x1.w), S1, 0, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                s[0][i] = n < nt ? c * S0[i] : -INFINITY;
-                s[1][i] = 16 + n < nt ? c * S1[i] : -INFINITY;
-            }
+            const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
+                                           : a.lv.kres + (size_t)bh * a.RC * kD;
+            const int p0 = pos0 + n, p1 = pos0 + 16 + n;
+            scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
         }
-
-        // ------------------------------------------------ online softmax (log2 domain), rows 4*rq + i
-        float mnew[4];
-        bool grew = false;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            float mb = fmaxf(s[0][i], s[1][i]);
-            mb = fmaxf(mb, __shfl_xor(mb, 1));
-            mb = fmaxf(mb, __shfl_xor(mb, 2));
-            mb = fmaxf(mb, __shfl_xor(mb, 4));
-            mb = fmaxf(mb, __shfl_xor(mb, 8));
-            mnew[i] = fmaxf(m[i], mb);
-            grew = grew || (mnew[i] > m[i]);
-        }
-        if (__any(grew)) {
-            float alpha[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                alpha[i] = exp2f(m[i] - mnew[i]);
-                l[i] *= alpha[i];
-                m[i] = mnew[i];
-            }
-#pragma unroll
-            for (int cblk = 0; cblk < 8; cblk++)
-#pragma unroll
-                for (int i = 0; i < 4; i++) O[cblk][i] *= alpha[i];
-#pragma unroll
-            for (int j = 0; j < GQ; j++) {
-                const float aj = __shfl(alpha[j & 3], 16 * (j >> 2));
-                oF[j][0] *= aj; oF[j][1] *= aj; accz[j] *= aj;
-            }
-        }
-        float p[2][4];
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            p[0][i] = exp2f(s[0][i] - m[i]);
-            p[1][i] = exp2f(s[1][i] - m[i]);
-            l[i] += p[0][i] + p[1][i];
-        }
-        if (rq < 2) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                if (4 * rq + i < GQ) {
-                    P[wave][(4 * rq + i) % GQ][n] = p[0][i];
-                    P[wave][(4 * rq + i) % GQ][16 + n] = p[1][i];
-                }
-            }
-        }
-        wave_lds_sync();
-
-        // ------------------------------------------------ output
+        softmax_update<GQ>(s, W, L, lane);
         bool v_rows = true;
         if constexpr (VB < 16) if (packed) {
             v_rows = false;
-            const float sv0 = cur.vs.x * vw0, sv1 = cur.vs.y * vw1;
-#pragma unroll
-            for (int j = 0; j < GQ; j++) {
-                const float2 pp = *reinterpret_cast<const float2 *>(&P[wave][j][2 * n]);
-                uint32_t hi, lo;
-                split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
-                *reinterpret_cast<uint32_t *>(&Av[wave][rq][j][2 * n]) = hi;
-                *reinterpret_cast<uint32_t *>(&Av[wave][rq][8 + j][2 * n]) = lo;
-                accz[j] = fmaf(pp.x, cur.vz.x, fmaf(pp.y, cur.vz.y, accz[j]));
-            }
-            wave_lds_sync();
-            half8 Aop[4];
-#pragma unroll
-            for (int gd = 0; gd < 4; gd++) Aop[gd] = *reinterpret_cast<const half8 *>(&Av[wave][gd][n][8 * rq]);
-#pragma unroll
-            for (int cblk = 0; cblk < 8; cblk++)
-                O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop[cblk >> 1], codes_operand<VB>(cur.vdw, cblk), O[cblk], 0, 0, 0);
+            output_packed<KB, VB, GQ>(r, Q, W, L, lane);
         }
         if (v_rows) {
-            // fp16 rows (the 16-bit region or the window ring): lane owns channels 2*lane, 2*lane+1
-            for (int tt = 0; tt < nt; tt++) {
-                const int pos = pos0 + tt;
-                const uint16_t *row = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + ((size_t)bh * a.NB * kG + pos) * kD
-                                             : a.lv.vres + ((size_t)bh * a.RC + pos % a.RC) * kD;
-                const uint32_t x = *reinterpret_cast<const uint32_t *>(row + 2 * lane);
-                const float v0 = half_lo(x), v1 = half_hi(x);
-#pragma unroll
-                for (int j = 0; j < GQ; j++) {
-                    const float pj = P[wave][j][tt];
-                    oF[j][0] = fmaf(pj, v0, oF[j][0]);
-                    oF[j][1] = fmaf(pj, v1, oF[j][1]);
-                }
-            }
+            const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
+                                           : a.lv.vres + (size_t)bh * a.RC * kD;
+            output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, lane);
         }
-        wave_lds_sync();
-        cur = nxt;
     }
 
     // ---------------------------------------------------- wave results -> LDS
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        l[i] += __shfl_xor(l[i], 1); l[i] += __shfl_xor(l[i], 2);
-        l[i] += __shfl_xor(l[i], 4); l[i] += __shfl_xor(l[i], 8);
-    }
+    for (int i = 0; i < 4; i++) W.l[i] = row_sum16(W.l[i]);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
-        accz[j] += __shfl_xor(accz[j], 1); accz[j] += __shfl_xor(accz[j], 2);
-        accz[j] += __shfl_xor(accz[j], 4); accz[j] += __shfl_xor(accz[j], 8);
-        if (n == 0) az_lds[wave][j][rq] = accz[j];
+        W.accz[j] = row_sum16(W.accz[j]);
+        if (n == 0) az_lds[wave][j][rq] = W.accz[j];
     }
-    const float two24 = 16777216.0f, two13 = 8192.0f;
+    constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
+    const float two24 = ldexpf(1.0f, vshift + W.ev - 14), two13 = ldexpf(1.0f, vshift - 11 + W.ev - 14);
     if (rq < 2) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             if (4 * rq + i < GQ) {
                 const int j = (4 * rq + i) % GQ;
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] = two24 * O[cblk][i];
-                if (n == 0) { ml_lds[wave][j][0] = m[i]; ml_lds[wave][j][1] = l[i]; }
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] = two24 * (W.O[cblk][i] - W.On[cblk >> 1][i]);
+                if (n == 0) { ml_lds[wave][j][0] = W.m[i]; ml_lds[wave][j][1] = W.l[i]; }
             }
         }
     }
@@ -379,15 +525,15 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             if (4 * (rq - 2) + i < GQ) {
                 const int j = (4 * (rq - 2) + i) % GQ;
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] += two13 * O[cblk][i];
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] += two13 * (W.O[cblk][i] - W.On[cblk >> 1][i]);
             }
         }
     }
     wave_lds_sync();
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
-        o_lds[wave][j][2 * lane] += oF[j][0];
-        o_lds[wave][j][2 * lane + 1] += oF[j][1];
+        o_lds[wave][j][2 * lane] += W.oF[j][0];
+        o_lds[wave][j][2 * lane + 1] += W.oF[j][1];
     }
     __syncthreads();
 
@@ -397,17 +543,17 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
         float M = -INFINITY;
 #pragma unroll
         for (int w = 0; w < 4; w++) M = fmaxf(M, ml_lds[w][j][0]);
-        float L = 0.0f, Osum = 0.0f;
+        float Lsum = 0.0f, Osum = 0.0f;
 #pragma unroll
         for (int w = 0; w < 4; w++) {
             const float mw = ml_lds[w][j][0];
             const float f = mw == -INFINITY ? 0.0f : exp2f(mw - M);
-            L = fmaf(ml_lds[w][j][1], f, L);
+            Lsum = fmaf(ml_lds[w][j][1], f, Lsum);
             Osum = fmaf(o_lds[w][j][d] + az_lds[w][j][d >> 5], f, Osum);
         }
         const size_t prow = (qrow0 + j) * a.splits + split;
         a.part_o[prow * kD + d] = Osum;
-        if (d == 0) { a.part_ml[prow * 2] = M; a.part_ml[prow * 2 + 1] = L; }
+        if (d == 0) { a.part_ml[prow * 2] = M; a.part_ml[prow * 2 + 1] = Lsum; }
     }
 }
 

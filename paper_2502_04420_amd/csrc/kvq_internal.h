@@ -13,6 +13,7 @@ struct LayerView {
     float *kmeta;         // [BH][NB][256] (absent when kbits == 16)
     uint8_t *vcode;       // [BH][NB] blocks of block_code_bytes(vbits)
     float *vmeta;         // [BH][NB][256] (absent when vbits == 16)
+    uint32_t *bexp;       // [BH][NB] binary exponents of the block's largest key / value scale (lo / hi half)
     uint16_t *kres;       // [BH][RC][128] fp16 ring, slot = position % RC
     uint16_t *vres;
     int kbits, vbits;

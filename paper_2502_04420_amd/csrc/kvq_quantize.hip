@@ -65,6 +65,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
         vx[i][0] = vv.x; vx[i][1] = vv.y; vx[i][2] = vv.z; vx[i][3] = vv.w;
     }
     const size_t blk_index = (size_t)bh * a.NB + blk;
+    float ks_max = 0.0f, vs_max = 0.0f;     // largest scale of the block, for the matrix-core kernel's operand scaling
 
     // ---- keys
     if constexpr (KB == 16) {
@@ -91,10 +92,11 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
         }
         float *meta = a.lv.kmeta + blk_index * 256;
-        if (r == 0) {
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const float s = scale_of(mn[e], mx[e], KB);
+        for (int e = 0; e < 8; e++) {
+            const float s = scale_of(mn[e], mx[e], KB);
+            ks_max = fmaxf(ks_max, s);
+            if (r == 0) {
                 ks[8 * c16 + e] = s; kz[8 * c16 + e] = mn[e];
                 meta[8 * c16 + e] = s; meta[kD + 8 * c16 + e] = mn[e];
             }
@@ -127,12 +129,26 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             // the 4 lanes c16 = 4*gd .. 4*gd+3 hold the 32 channels of group gd
             mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
             mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
+            const float s = scale_of(mn, mx, VB);
+            vs_max = fmaxf(vs_max, s);
             if ((c16 & 3) == 0) {
                 const int gd = c16 >> 2;
-                const float s = scale_of(mn, mx, VB);
                 vs[32 * gd + t] = s; vz[32 * gd + t] = mn;
                 meta[32 * gd + t] = s; meta[kD + 32 * gd + t] = mn;
             }
+        }
+    }
+    if constexpr (KB < 16 || VB < 16) {
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) {
+            ks_max = fmaxf(ks_max, __shfl_xor(ks_max, sft));
+            vs_max = fmaxf(vs_max, __shfl_xor(vs_max, sft));
+        }
+        if (lane == 0) {
+            int ek = 0, ev = 0;                       // max = f * 2^e with f in [0.5, 1); 0 for an all-constant block
+            if (ks_max > 0.0f) (void)frexpf(ks_max, &ek);
+            if (vs_max > 0.0f) (void)frexpf(vs_max, &ev);
+            a.lv.bexp[blk_index] = ((uint32_t)(ek + 32768) & 0xffffu) | ((uint32_t)(ev + 32768) << 16);
         }
     }
     __syncthreads();
