@@ -50,6 +50,7 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_b
 // subnormal operands would lose precision).  The "1 +" is removed by one more MFMA of the same A
 // tile against an all-ones B tile.
 constexpr uint32_t kOne2 = 0x3C003C00u;      // two fp16 1.0
+constexpr uint32_t kMinusOne2 = 0xBC00BC00u; // two fp16 -1.0
 
 template <int BITS> struct CodeShift { static constexpr int value = BITS == 8 ? 10 : 6; };
 
@@ -169,8 +170,7 @@ struct WaveLds {
 template <int GQ>
 struct WaveState {
     float m[4], l[4];              // rows 4*rq + i of the 16-row tile: running max (log2 units), partial sum
-    float4v O[8];                  // un-normalised output tile per 16-channel block, scaled, "1 +" part included
-    float4v On[4];                 // per channel group: row sums of the A tiles (the "1 +" part of O)
+    float4v O[8];                  // un-normalised output tile per 16-channel block (scaled by 2^(14 - ev - shift))
     float oF[GQ][2];               // fp16-row contributions, channels 2*lane, 2*lane+1
     float accz[GQ];                // sum_t p_t z_tg for group rq, tokens 2n, 2n+1
     int ev;                        // O is held times 2^(14 - ev - 24); ev = largest value-scale exponent so far
@@ -179,7 +179,7 @@ struct WaveState {
 template <int GQ>
 struct QueryRegs {
     float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
-    half8 Aq[4];                   // exact fp16 queries as A tiles (rows j and 8 + j)
+    const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows j and 8 + j)
     float c, alpha_h, alpha_l;     // log2(e)/sqrt(D); weights of the high / low partial scores
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
 };
@@ -212,7 +212,7 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
         S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, cb), S0, 0, 0, 0);
         S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, 4 + cb), S1, 0, 0, 0);
         Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
-        Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], Bz, Z, 0, 0, 0);
+        Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -237,8 +237,9 @@ __device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t
         uint4 x0 = make_uint4(0, 0, 0, 0), x1 = x0;
         if (n < nt) x0 = *reinterpret_cast<const uint4 *>(row0 + 32 * cb + 8 * rq);
         if (16 + n < nt) x1 = *reinterpret_cast<const uint4 *>(row1 + 32 * cb + 8 * rq);
-        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], as_half8(x0.x, x0.y, x0.z, x0.w), S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Q.Aq[cb], as_half8(x1.x, x1.y, x1.z, x1.w), S1, 0, 0, 0);
+        const half8 Aop = *reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, as_half8(x0.x, x0.y, x0.z, x0.w), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, as_half8(x1.x, x1.y, x1.z, x1.w), S1, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -248,7 +249,7 @@ __device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t
 }
 
 // online softmax over the block's 32 scores per row; leaves the numerators in L.P[j][token]
-template <int GQ>
+template <int GQ, bool ROWS_SEEN>
 __device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState<GQ> &W, WaveLds<GQ> &L, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
@@ -272,13 +273,10 @@ __device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState
 #pragma unroll
             for (int i = 0; i < 4; i++) W.O[cblk][i] *= alpha[i];
 #pragma unroll
-        for (int gd = 0; gd < 4; gd++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) W.On[gd][i] *= alpha[i];
-#pragma unroll
         for (int j = 0; j < GQ; j++) {
             const float aj = __shfl(alpha[j & 3], 16 * (j >> 2));
-            W.oF[j][0] *= aj; W.oF[j][1] *= aj; W.accz[j] *= aj;
+            if (ROWS_SEEN) { W.oF[j][0] *= aj; W.oF[j][1] *= aj; }   // still zero while only quantized blocks were seen
+            W.accz[j] *= aj;
         }
     }
     float p[2][4];
@@ -313,10 +311,6 @@ __device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, cons
         for (int cblk = 0; cblk < 8; cblk++)
 #pragma unroll
             for (int i = 0; i < 4; i++) W.O[cblk][i] = ldexpf(W.O[cblk][i], W.ev - ev);
-#pragma unroll
-        for (int gd = 0; gd < 4; gd++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) W.On[gd][i] = ldexpf(W.On[gd][i], W.ev - ev);
         W.ev = ev;
     }
     const float sv0 = ldexpf(blk.vs.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(blk.vs.y * Q.vw1, 14 - W.ev);
@@ -330,16 +324,18 @@ __device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, cons
         W.accz[j] = fmaf(pp.x, blk.vz.x, fmaf(pp.y, blk.vz.y, W.accz[j]));
     }
     wave_lds_sync();
-    half8 Aop[4];
-    const half8 ones = as_half8(kOne2, kOne2, kOne2, kOne2);
+    // each code operand reads 1 + c * 2^-k: the second MFMA against minus-ones removes the "1 +" part at once
+    const half8 minus_ones = as_half8(kMinusOne2, kMinusOne2, kMinusOne2, kMinusOne2);
 #pragma unroll
     for (int gd = 0; gd < 4; gd++) {
-        Aop[gd] = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
-        W.On[gd] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop[gd], ones, W.On[gd], 0, 0, 0);
-    }
+        const half8 Aop = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
 #pragma unroll
-    for (int cblk = 0; cblk < 8; cblk++)
-        W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop[cblk >> 1], codes_operand<VB>(blk.vdw, cblk), W.O[cblk], 0, 0, 0);
+        for (int c2 = 0; c2 < 2; c2++) {
+            const int cblk = 2 * gd + c2;
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.vdw, cblk), W.O[cblk], 0, 0, 0);
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, minus_ones, W.O[cblk], 0, 0, 0);
+        }
+    }
     wave_lds_sync();
 }
 
@@ -364,7 +360,7 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
 }
 
 template <int KB, int VB, int GQ>
-__global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
+__global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows j and 8 + j of a 16-row tile");
     const int tid = threadIdx.x, lane = tid & 63;
@@ -378,6 +374,7 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
     const size_t qrow0 = (size_t)b * a.Hq + (size_t)h * gq_total + head0;
 
     __shared__ __attribute__((aligned(16))) WaveLds<GQ> lds[4];
+    __shared__ __attribute__((aligned(16))) _Float16 aq_lds[16][kD + 8];
     __shared__ __attribute__((aligned(16))) float o_lds[4][GQ][kD];
     __shared__ float az_lds[4][GQ][4];
     __shared__ float ml_lds[4][GQ][2];
@@ -411,13 +408,14 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
             Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
         }
-        const int jr = n & 7;
-#pragma unroll
-        for (int cb = 0; cb < 4; cb++) {
+        // rows j and 8 + j of the shared query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
+        {
+            const int row = tid >> 4, jr = row & 7;
             uint4 x = make_uint4(0, 0, 0, 0);
-            if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 32 * cb + 8 * rq);
-            Q.Aq[cb] = as_half8(x.x, x.y, x.z, x.w);
+            if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * (tid & 15));
+            *reinterpret_cast<uint4 *>(&aq_lds[row][8 * (tid & 15)]) = x;
         }
+        Q.Aq = &aq_lds[0][0];
         Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
         Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
     }
@@ -428,8 +426,6 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
     for (int i = 0; i < 4; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
 #pragma unroll
     for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int gd = 0; gd < 4; gd++) W.On[gd] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int j = 0; j < GQ; j++) { W.oF[j][0] = W.oF[j][1] = 0.0f; W.accz[j] = 0.0f; }
     W.ev = -100;
@@ -451,13 +447,13 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             while (true) {
                 load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r1);
                 scores_packed<KB, VB, GQ>(r0, Q, L, lane, s);
-                softmax_update<GQ>(s, W, L, lane);
+                softmax_update<GQ, false>(s, W, L, lane);
                 output_packed<KB, VB, GQ>(r0, Q, W, L, lane);
                 u += 4;
                 if (u >= ub) break;
                 load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r0);
                 scores_packed<KB, VB, GQ>(r1, Q, L, lane, s);
-                softmax_update<GQ>(s, W, L, lane);
+                softmax_update<GQ, false>(s, W, L, lane);
                 output_packed<KB, VB, GQ>(r1, Q, W, L, lane);
                 u += 4;
                 if (u >= ub) break;
@@ -484,7 +480,7 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             const int p0 = pos0 + n, p1 = pos0 + 16 + n;
             scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
         }
-        softmax_update<GQ>(s, W, L, lane);
+        softmax_update<GQ, true>(s, W, L, lane);
         bool v_rows = true;
         if constexpr (VB < 16) if (packed) {
             v_rows = false;
@@ -513,7 +509,7 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             if (4 * rq + i < GQ) {
                 const int j = (4 * rq + i) % GQ;
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] = two24 * (W.O[cblk][i] - W.On[cblk >> 1][i]);
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] = two24 * W.O[cblk][i];
                 if (n == 0) { ml_lds[wave][j][0] = W.m[i]; ml_lds[wave][j][1] = W.l[i]; }
             }
         }
@@ -525,7 +521,7 @@ __global__ __launch_bounds__(256) void decode_mfma(DecodeArgs a)
             if (4 * (rq - 2) + i < GQ) {
                 const int j = (4 * (rq - 2) + i) % GQ;
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] += two13 * (W.O[cblk][i] - W.On[cblk >> 1][i]);
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] += two13 * W.O[cblk][i];
             }
         }
     }
