@@ -220,9 +220,11 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     const int units = a.n_blocks + (a.n_res + 31) / 32;
     int splits = c->splits;
     if (splits <= 0) {
+        // two 256-thread groups per compute unit fill the GPU (512 groups); more splits only add
+        // per-group set-up and merge work, so split no further than that and keep >= 8 units per group
         const int BH = a.B * a.Hkv;
-        splits = (1024 + BH - 1) / BH;           // about four 256-thread groups per compute unit
-        const int cap = (units + 3) / 4;         // at least four units per group
+        splits = (512 + BH - 1) / BH;
+        const int cap = (units + 7) / 8;
         if (splits > cap) splits = cap;
     }
     if (splits > kMaxSplits) splits = kMaxSplits;
@@ -230,7 +232,7 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     if (splits < 1) splits = 1;
     a.units_per_split = (units + splits - 1) / splits;
     a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
-    const int variant = c->variant == 0 ? 1 : c->variant;
+    const int variant = c->variant == 0 ? 2 : c->variant;     // the matrix-core kernel is the default
     hipError_t e = variant == 2 ? kvq::launch_decode_mfma(a, c->stream) : kvq::launch_decode_valu(a, c->stream);
     if (e != hipSuccess) return launch_failed("decode kernel", e);
     e = kvq::launch_combine(a, c->stream);

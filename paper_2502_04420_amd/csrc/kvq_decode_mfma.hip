@@ -50,44 +50,47 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_b
 // subnormal operands would lose precision).  The "1 +" is removed by one more MFMA of the same A
 // tile against an all-ones B tile.
 constexpr uint32_t kOne2 = 0x3C003C00u;      // two fp16 1.0
-constexpr uint32_t kMinusOne2 = 0xBC00BC00u; // two fp16 -1.0
 
-template <int BITS> struct CodeShift { static constexpr int value = BITS == 8 ? 10 : 6; };
+// log2 of the divisor of the code in the base position: operand element = 1 + code * 2^-CodeShift
+template <int BITS> struct CodeShift { static constexpr int value = BITS == 2 ? 6 : 10; };
 
+// `one` is kOne2 held in a vector register the compiler cannot see through, so that each
+// (x & mask) | one becomes a single v_and_or_b32.
 template <int BITS>
-__device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m)
+__device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m, uint32_t one)
 {
     if constexpr (BITS == 8) {
         // bytes (b0, b1), (b2, b3) -> halves 0x3C00 | b : 1 + b / 1024
         const uint32_t w0 = dw[2 * m], w1 = dw[2 * m + 1];
-        return as_half8(__builtin_amdgcn_perm(kOne2, w0, 0x05010500u), __builtin_amdgcn_perm(kOne2, w0, 0x05030502u),
-                        __builtin_amdgcn_perm(kOne2, w1, 0x05010500u), __builtin_amdgcn_perm(kOne2, w1, 0x05030502u));
+        return as_half8(__builtin_amdgcn_perm(one, w0, 0x05010500u), __builtin_amdgcn_perm(one, w0, 0x05030502u),
+                        __builtin_amdgcn_perm(one, w1, 0x05010500u), __builtin_amdgcn_perm(one, w1, 0x05030502u));
     } else if constexpr (BITS == 4) {
-        // nibbles (k, k + 4) moved to mantissa bits 7:4 of each half: 1 + c / 64
-        const uint32_t x = dw[m], msk = 0x00F000F0u;
-        return as_half8(((x << 4) & msk) | kOne2, (x & msk) | kOne2, ((x >> 4) & msk) | kOne2, ((x >> 8) & msk) | kOne2);
+        // nibbles (k, k + 4) of the dword form a pair; mantissa bits 3:0 read 1 + c / 1024, bits 7:4 read 1 + 16 c / 1024
+        const uint32_t x = dw[m], y = x >> 8;
+        return as_half8((x & 0x000F000Fu) | one, (x & 0x00F000F0u) | one, (y & 0x000F000Fu) | one, (y & 0x00F000F0u) | one);
     } else {
-        // 2-bit fields at mantissa bits 5:4 (1 + c / 64) or 7:6 (1 + c / 16), alternating
+        // 2-bit fields at mantissa bits 5:4 (1 + c / 64) or 7:6 (1 + 4 c / 64), alternating
         const uint32_t x = dw[m >> 1], lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
-        return as_half8((lo & 0x00300030u) | kOne2, (lo & 0x00C000C0u) | kOne2, (hi & 0x00300030u) | kOne2,
-                        (hi & 0x00C000C0u) | kOne2);
+        return as_half8((lo & 0x00300030u) | one, (lo & 0x00C000C0u) | one, (hi & 0x00300030u) | one, (hi & 0x00C000C0u) | one);
     }
 }
 
-// power of two by which the A operand must be divided for element e (its code sits two bits
-// higher in the mantissa than the base position)
+// power of two by which the A operand must be divided for element e (its code sits higher in
+// the mantissa than the base position)
 template <int BITS>
 __device__ __forceinline__ float code_weight_inv(int e)
 {
+    if (BITS == 4) return ((e >> 1) & 1) ? 0.0625f : 1.0f;
     if (BITS == 2) return ((e >> 1) & 1) ? 0.25f : 1.0f;
     return 1.0f;
 }
 
-// split two fp32 values into fp16 high parts and (scaled by 2^11) fp16 low parts
+// split two fp32 values into fp16 high parts and fp16 low parts (hi + lo = r to about 2^-21; the
+// operands are kept near the top of the fp16 range, so the low parts are normal numbers too)
 __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uint32_t &lo)
 {
     const half2v h = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(r0, r1));
-    const float d0 = (r0 - (float)h[0]) * 2048.0f, d1 = (r1 - (float)h[1]) * 2048.0f;
+    const float d0 = r0 - (float)h[0], d1 = r1 - (float)h[1];
     hi = __builtin_bit_cast(uint32_t, h);
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d0, d1));
 }
@@ -180,7 +183,8 @@ template <int GQ>
 struct QueryRegs {
     float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
     const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows j and 8 + j)
-    float c, alpha_h, alpha_l;     // log2(e)/sqrt(D); weights of the high / low partial scores
+    float c, alpha_h;              // log2(e)/sqrt(D); weight of the partial scores
+    uint32_t one;                  // two fp16 1.0 in a vector register
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
 };
 
@@ -193,7 +197,7 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
     const int ek = (int)(blk.bexp & 0xffffu) - 32768;
     const float ks0 = ldexpf(blk.ks.x, 14 - ek), ks1 = ldexpf(blk.ks.y, 14 - ek);
-    const float ah = ldexpf(Q.alpha_h, ek - 14), al = ldexpf(Q.alpha_l, ek - 14);
+    const float ah = ldexpf(Q.alpha_h, ek - 14);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
         uint32_t hi, lo;
@@ -204,13 +208,13 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
     *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.kz.x, blk.kz.y));
     wave_lds_sync();
     float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0, Dn = S0;
-    const half8 ones = as_half8(kOne2, kOne2, kOne2, kOne2);
+    const half8 ones = as_half8(Q.one, Q.one, Q.one, Q.one);
 #pragma unroll
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
         const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
-        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, cb), S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, 4 + cb), S1, 0, 0, 0);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, cb, Q.one), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, 4 + cb, Q.one), S1, 0, 0, 0);
         Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
         Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
@@ -220,8 +224,8 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
         halves_of(S0[i] - Dn[i], h0, l0);  // lanes 0..31 hold the high-part rows, 32..63 the low-part rows
         halves_of(S1[i] - Dn[i], h1, l1);
         const float zc = Q.c * Z[i];
-        s[0][i] = fmaf(ah, h0, fmaf(al, l0, zc));
-        s[1][i] = fmaf(ah, h1, fmaf(al, l1, zc));
+        s[0][i] = fmaf(ah, h0 + l0, zc);
+        s[1][i] = fmaf(ah, h1 + l1, zc);
     }
 }
 
@@ -253,20 +257,20 @@ template <int GQ, bool ROWS_SEEN>
 __device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState<GQ> &W, WaveLds<GQ> &L, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
-    float mnew[4];
-    bool grew = false;
+    // The reference maximum only has to keep the numerators in range: it is refreshed (with an exact
+    // row maximum and a rescale of everything accumulated so far) when some score exceeds it by more
+    // than 1, so numerators stay <= 2 and the fp16 output operands cannot overflow.
+    bool over = false;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        mnew[i] = fmaxf(W.m[i], row_max16(fmaxf(s[0][i], s[1][i])));
-        grew = grew || (mnew[i] > W.m[i]);
-    }
-    if (__any(grew)) {
+    for (int i = 0; i < 4; i++) over = over || (fmaxf(s[0][i], s[1][i]) > W.m[i] + 1.0f);
+    if (__any(over)) {
         float alpha[4];
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            alpha[i] = exp2f(W.m[i] - mnew[i]);
+            const float mnew = fmaxf(W.m[i], row_max16(fmaxf(s[0][i], s[1][i])));
+            alpha[i] = exp2f(W.m[i] - mnew);
             W.l[i] *= alpha[i];
-            W.m[i] = mnew[i];
+            W.m[i] = mnew;
         }
 #pragma unroll
         for (int cblk = 0; cblk < 8; cblk++)
@@ -325,14 +329,15 @@ __device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, cons
     }
     wave_lds_sync();
     // each code operand reads 1 + c * 2^-k: the second MFMA against minus-ones removes the "1 +" part at once
-    const half8 minus_ones = as_half8(kMinusOne2, kMinusOne2, kMinusOne2, kMinusOne2);
+    const uint32_t mone = Q.one ^ 0x80008000u;
+    const half8 minus_ones = as_half8(mone, mone, mone, mone);
 #pragma unroll
     for (int gd = 0; gd < 4; gd++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
 #pragma unroll
         for (int c2 = 0; c2 < 2; c2++) {
             const int cblk = 2 * gd + c2;
-            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.vdw, cblk), W.O[cblk], 0, 0, 0);
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.vdw, cblk, Q.one), W.O[cblk], 0, 0, 0);
             W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, minus_ones, W.O[cblk], 0, 0, 0);
         }
     }
@@ -402,7 +407,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
         int qexp = 0;
         if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
         Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
-        Q.alpha_l = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp - 11);
+        Q.one = kOne2;
+        asm volatile("" : "+v"(Q.one));
 #pragma unroll
         for (int j = 0; j < GQ; j++) {
             Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
@@ -502,7 +508,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
         if (n == 0) az_lds[wave][j][rq] = W.accz[j];
     }
     constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
-    const float two24 = ldexpf(1.0f, vshift + W.ev - 14), two13 = ldexpf(1.0f, vshift - 11 + W.ev - 14);
+    const float two24 = ldexpf(1.0f, vshift + W.ev - 14), two13 = two24;   // high and low parts carry the same weight
     if (rq < 2) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
