@@ -1,0 +1,123 @@
+"""CPU-only checks of the product's host side: the C ABI loads and exports what include/kvq.h declares,
+argument validation returns the documented codes without touching a GPU, and the schedule helpers."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_04420_amd import binding
+
+    if not os.path.exists(binding.library_path()):
+        from paper_2502_04420_amd.build import build
+
+        build(verbose=False)
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert {"kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_workspace_bytes"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None, name
+    from paper_2502_04420_amd import binding
+
+    assert sorted(binding.EXPORTED) == names
+
+
+def _cfg(**over):
+    from paper_2502_04420_amd import binding
+
+    kw = dict(n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, max_tokens=256, kbits=[8, 4], vbits=[4, 2])
+    kw.update(over)
+    return binding.make_config(**kw)
+
+
+def test_workspace_bytes_and_config_validation(lib):
+    cfg, keep = _cfg()
+    need = lib.kvq_workspace_bytes(ctypes.byref(cfg))
+    assert need > 0 and need % 256 == 0
+    # codes + metadata of 8 blocks per (b, h) for both layers must fit
+    assert need >= 4 * 8 * ((4096 + 2048 + 2048) + (2048 + 1024 + 2048))
+    for bad in (dict(head_dim=64), dict(group=16), dict(n_q_heads=7), dict(kbits=[8, 3]), dict(vbits=[1, 2]),
+                dict(max_tokens=0), dict(batch=0), dict(residual=-1)):
+        c, k = _cfg(**bad)
+        assert lib.kvq_workspace_bytes(ctypes.byref(c)) == 0, bad
+        h = ctypes.c_void_p()
+        assert lib.kvq_configure(ctypes.byref(h), ctypes.byref(c), ctypes.c_void_p(256), 1 << 40, None) == -1, bad
+    assert lib.kvq_workspace_bytes(None) == 0
+
+
+def test_configure_and_call_errors_without_gpu(lib):
+    cfg, keep = _cfg()
+    need = lib.kvq_workspace_bytes(ctypes.byref(cfg))
+    h = ctypes.c_void_p()
+    assert lib.kvq_configure(ctypes.byref(h), ctypes.byref(cfg), None, need, None) == -4          # no workspace
+    assert lib.kvq_configure(ctypes.byref(h), ctypes.byref(cfg), ctypes.c_void_p(256 + 8), need, None) == -4   # misaligned
+    assert lib.kvq_configure(ctypes.byref(h), ctypes.byref(cfg), ctypes.c_void_p(256), need - 1, None) == -4   # too small
+    assert lib.kvq_configure(None, ctypes.byref(cfg), ctypes.c_void_p(256), need, None) == -1
+    # a fake (never dereferenced) workspace pointer is enough for the host-side checks below
+    assert lib.kvq_configure(ctypes.byref(h), ctypes.byref(cfg), ctypes.c_void_p(256), need, None) == 0
+    try:
+        fake = ctypes.c_void_p(4096)
+        assert lib.kvq_decode_attention(h, 0, fake, fake) == -3          # no token yet
+        assert lib.kvq_decode_attention(h, 2, fake, fake) == -1          # bad layer
+        assert lib.kvq_decode_attention(h, 0, None, fake) == -1
+        assert lib.kvq_quantize_append(h, -1, fake, fake, 1) == -1
+        assert lib.kvq_quantize_append(h, 0, fake, fake, 0) == -1
+        assert lib.kvq_quantize_append(h, 0, fake, None, 1) == -1
+        assert lib.kvq_quantize_append(h, 0, fake, fake, 257) == -2      # beyond max_tokens
+        a, b = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        assert lib.kvq_layer_tokens(h, 1, ctypes.byref(a), ctypes.byref(b)) == 0 and (a.value, b.value) == (0, 0)
+        assert lib.kvq_layer_tokens(h, 5, ctypes.byref(a), ctypes.byref(b)) == -1
+        assert lib.kvq_reset(h, -1) == 0 and lib.kvq_reset(h, 2) == -1
+        assert lib.kvq_set_decode_options(h, 3, 0) == -1 and lib.kvq_set_decode_options(h, 1, 65) == -1
+        assert lib.kvq_set_decode_options(h, 2, 8) == 0
+        assert lib.kvq_debug_export(h, 0, *([None] * 8)) == 0              # empty layer: nothing to do
+    finally:
+        lib.kvq_destroy(h)
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(lib.kvq_strerror(code)) > 0
+    assert lib.kvq_last_error() is not None
+
+
+def test_binding_refuses_cpu_device(lib):
+    import paper_2502_04420_amd as pkg
+
+    with pytest.raises(ValueError):
+        pkg.KVQ(1, 1, 4, 1, 128, 64, [8], [8], device="cpu")
+
+
+def test_equivalent_precision_matches_the_papers_printed_values():
+    import kvq_workloads as W
+    from paper_2502_04420_amd import bytes_per_token, equivalent_precision, parse_pairs
+
+    gold = {}
+    with open(os.path.join(ROOT, "tests", "golden", "equivalent_precision.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, val = [p.strip() for p in line.split("|")]
+                gold[name] = float(val)
+    for name, printed in gold.items():
+        kb, vb = getattr(W, name)()
+        assert round(equivalent_precision(kb, vb), 2) in (printed, round(printed + 0.01, 2)), name   # 4.906 prints as 4.90 / 4.91
+    assert equivalent_precision(*W.llama_mix_325()) == 3.25
+    assert equivalent_precision(*W.qwen_mix_40()) == 4.0
+    assert equivalent_precision([4], [4]) == 4.0 and 16 / equivalent_precision([4], [2]) == pytest.approx(5.33, abs=0.01)
+    # bytes per token per kv head with fp32 metadata (head_dim 128, group 32)
+    assert [bytes_per_token(k, v) for k, v in ((8, 8), (8, 4), (8, 2), (4, 4), (4, 2), (2, 2), (16, 16))] == \
+        [320, 256, 224, 192, 160, 128, 512]
+    assert parse_pairs("K8V4, KV4,K4V2") == ([8, 4, 4], [4, 4, 2])
+    with pytest.raises(ValueError):
+        parse_pairs("K3V4")
