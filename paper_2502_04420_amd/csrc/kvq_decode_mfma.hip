@@ -15,8 +15,12 @@
 // after the MFMA.  The zero-point terms: q . z is one more MFMA per 32 channels (q and z are
 // exact in fp16), sum_t p_t z_tg is a handful of fp32 FMAs per block.
 //
-// A work-group owns one (batch, kv head, split); each of its 4 waves streams every 4th
-// 32-token block with the next block's loads in flight, and keeps an online-softmax state.
+// A work-group owns one (batch, kv head, split).  Its 4 waves form two pairs; in a pair one wave
+// (the key wave) streams the key blocks and produces the softmax numerators of each block, the
+// other (the value wave) consumes them one block later and accumulates the output.  The hand-off
+// goes through double-buffered LDS tiles and one work-group barrier per block, so score and
+// output work of neighbouring blocks overlap on different SIMDs and each wave carries only half
+// of the state (which is what lets 3 to 4 waves share a SIMD and hide the memory latency).
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -95,39 +99,29 @@ __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uin
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d0, d1));
 }
 
-template <int KB, int VB>
-struct BlockRegs {
-    uint32_t kdw[KB < 16 ? 2 * KB : 1];
-    uint32_t vdw[VB < 16 ? 2 * VB : 1];
-    float2 ks, kz, vs, vz;
-    uint32_t bexp;               // exponents of the block's largest key scale (low half) and value scale (high half)
+// one 32-token block of quantized keys / values as loaded by this lane
+template <int BITS>
+struct CodeRegs {
+    uint32_t dw[BITS < 16 ? 2 * BITS : 1];   // the lane's 64 codes
+    float2 s, z;                             // keys: channels 2*lane, +1; values: group lane>>4, tokens 2*(lane&15), +1
+    uint32_t bexp;                           // exponents of the block's largest key scale (low half) / value scale (high half)
 };
 
-template <int KB, int VB>
-__device__ __forceinline__ void load_block(const DecodeArgs &a, size_t blk_index, int lane, BlockRegs<KB, VB> &r)
+template <int BITS>
+__device__ __forceinline__ void load_codes(const uint8_t *code, const float *meta, const uint32_t *bexp, size_t blk_index,
+                                           int lane, CodeRegs<BITS> &r)
 {
-    r.bexp = a.lv.bexp[blk_index];
-    if constexpr (KB < 16) {
-        const uint8_t *blk = a.lv.kcode + blk_index * block_code_bytes(KB);
+    r.bexp = bexp[blk_index];
+    if constexpr (BITS < 16) {
+        const uint8_t *blk = code + blk_index * block_code_bytes(BITS);
 #pragma unroll
-        for (int c = 0; c < KB / 2; c++) {
+        for (int c = 0; c < BITS / 2; c++) {
             const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
-            r.kdw[4 * c] = x.x; r.kdw[4 * c + 1] = x.y; r.kdw[4 * c + 2] = x.z; r.kdw[4 * c + 3] = x.w;
+            r.dw[4 * c] = x.x; r.dw[4 * c + 1] = x.y; r.dw[4 * c + 2] = x.z; r.dw[4 * c + 3] = x.w;
         }
-        const float *meta = a.lv.kmeta + blk_index * 256;
-        r.ks = *reinterpret_cast<const float2 *>(meta + 2 * lane);
-        r.kz = *reinterpret_cast<const float2 *>(meta + kD + 2 * lane);
-    }
-    if constexpr (VB < 16) {
-        const uint8_t *blk = a.lv.vcode + blk_index * block_code_bytes(VB);
-#pragma unroll
-        for (int c = 0; c < VB / 2; c++) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
-            r.vdw[4 * c] = x.x; r.vdw[4 * c + 1] = x.y; r.vdw[4 * c + 2] = x.z; r.vdw[4 * c + 3] = x.w;
-        }
-        const float *meta = a.lv.vmeta + blk_index * 256;
-        r.vs = *reinterpret_cast<const float2 *>(meta + 2 * lane);          // group lane>>4, tokens 2*(lane&15), +1
-        r.vz = *reinterpret_cast<const float2 *>(meta + kD + 2 * lane);
+        const float *m = meta + blk_index * 256;
+        r.s = *reinterpret_cast<const float2 *>(m + 2 * lane);
+        r.z = *reinterpret_cast<const float2 *>(m + kD + 2 * lane);
     }
 }
 
@@ -161,22 +155,22 @@ __device__ __forceinline__ void halves_of(float x, float &lo, float &hi)
     hi = __builtin_bit_cast(float, b);      // [x.lanes32-63, x.lanes32-63]
 }
 
-// LDS scratch of one wave
-template <int GQ>
-struct WaveLds {
-    _Float16 Ak[16][kD + 8];       // score A tiles [row][channel]: rows j = high parts, 8 + j = low parts
-    _Float16 Zk[kD];               // key zero-points as fp16 (exact)
-    float P[GQ][32];               // softmax numerators of the current block
-    _Float16 Av[4][16][32 + 8];    // output A tiles [channel group][row][token]
-};
+// Work-group barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for
+// the global loads of the next block, which are meant to stay in flight across it.
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
+// LDS of one key-wave / value-wave pair
 template <int GQ>
-struct WaveState {
-    float m[4], l[4];              // rows 4*rq + i of the 16-row tile: running max (log2 units), partial sum
-    float4v O[8];                  // un-normalised output tile per 16-channel block (scaled by 2^(14 - ev - shift))
-    float oF[GQ][2];               // fp16-row contributions, channels 2*lane, 2*lane+1
-    float accz[GQ];                // sum_t p_t z_tg for group rq, tokens 2n, 2n+1
-    int ev;                        // O is held times 2^(14 - ev - 24); ev = largest value-scale exponent so far
+struct PairLds {
+    _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]: rows j = high parts, 8 + j = low parts
+    _Float16 Zk[kD];               // key wave: key zero-points as fp16 (exact)
+    _Float16 Av[4][16][32 + 8];    // value wave: output A tiles [channel group][row][token]
+    float P[2][GQ][32];            // hand-off: softmax numerators of a block, double-buffered
+    float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
+    int rescale[2];                // hand-off: non-zero when alpha is not all ones
 };
 
 template <int GQ>
@@ -188,15 +182,30 @@ struct QueryRegs {
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
 };
 
+template <int GQ>
+struct KeyState {
+    float m[4], l[4];              // rows 4*rq + i of the 16-row tile: reference max (log2 units), partial sum
+};
+
+template <int GQ>
+struct ValueState {
+    float4v O[8];                  // un-normalised output tile per 16-channel block (scaled by 2^(14 - ev - shift))
+    float oF[GQ][2];               // fp16-row contributions, channels 2*lane, 2*lane+1
+    float accz[GQ];                // sum_t p_t z_tg for group rq, tokens 2n, 2n+1
+    int ev;                        // largest value-scale exponent so far
+};
+
+// ------------------------------------------------------------------ key wave
+
 // scores of a quantized block: s[th][i] for rows 4*rq + i, tokens 16*th + n
-template <int KB, int VB, int GQ>
-__device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, const QueryRegs<GQ> &Q, WaveLds<GQ> &L,
-                                              int lane, float (&s)[2][4])
+template <int KB, int GQ>
+__device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
+                                              float (&s)[2][4])
 {
     const int n = lane & 15, rq = lane >> 4;
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
     const int ek = (int)(blk.bexp & 0xffffu) - 32768;
-    const float ks0 = ldexpf(blk.ks.x, 14 - ek), ks1 = ldexpf(blk.ks.y, 14 - ek);
+    const float ks0 = ldexpf(blk.s.x, 14 - ek), ks1 = ldexpf(blk.s.y, 14 - ek);
     const float ah = ldexpf(Q.alpha_h, ek - 14);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
@@ -205,7 +214,7 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
         *reinterpret_cast<uint32_t *>(&L.Ak[j][2 * lane]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Ak[8 + j][2 * lane]) = lo;
     }
-    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.kz.x, blk.kz.y));
+    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.z.x, blk.z.y));
     wave_lds_sync();
     float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0, Dn = S0;
     const half8 ones = as_half8(Q.one, Q.one, Q.one, Q.one);
@@ -213,8 +222,8 @@ __device__ __forceinline__ void scores_packed(const BlockRegs<KB, VB> &blk, cons
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
         const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
-        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, cb, Q.one), S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.kdw, 4 + cb, Q.one), S1, 0, 0, 0);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb, Q.one), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb, Q.one), S1, 0, 0, 0);
         Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
         Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
@@ -252,37 +261,31 @@ __device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t
     }
 }
 
-// online softmax over the block's 32 scores per row; leaves the numerators in L.P[j][token]
-template <int GQ, bool ROWS_SEEN>
-__device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState<GQ> &W, WaveLds<GQ> &L, int lane)
+// Online softmax over the block's 32 scores per row.  Publishes the numerators (L.P[buf]), and the factor
+// by which the value wave must shrink what it has accumulated (L.alpha[buf], L.rescale[buf]).
+// The reference maximum only has to keep the numerators in range: it is refreshed (exact row maximum)
+// when some score exceeds it by more than 1, so numerators stay <= 2 and the fp16 output operands
+// cannot overflow.  Rows of the tile that carry no head (row >= nrows) hold garbage and are ignored.
+template <int GQ>
+__device__ __forceinline__ void softmax_publish(const float (&s)[2][4], KeyState<GQ> &W, PairLds<GQ> &L, int buf, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
-    // The reference maximum only has to keep the numerators in range: it is refreshed (with an exact
-    // row maximum and a rescale of everything accumulated so far) when some score exceeds it by more
-    // than 1, so numerators stay <= 2 and the fp16 output operands cannot overflow.
     bool over = false;
 #pragma unroll
-    for (int i = 0; i < 4; i++) over = over || (fmaxf(s[0][i], s[1][i]) > W.m[i] + 1.0f);
-    if (__any(over)) {
-        float alpha[4];
+    for (int i = 0; i < 4; i++)
+        if (4 * (rq & 1) + i < GQ) over = over || (fmaxf(s[0][i], s[1][i]) > W.m[i] + 1.0f);
+    const bool grow = __any(over);
+    if (grow) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const float mnew = fmaxf(W.m[i], row_max16(fmaxf(s[0][i], s[1][i])));
-            alpha[i] = exp2f(W.m[i] - mnew);
-            W.l[i] *= alpha[i];
+            const float alpha = exp2f(W.m[i] - mnew);
+            W.l[i] *= alpha;
             W.m[i] = mnew;
-        }
-#pragma unroll
-        for (int cblk = 0; cblk < 8; cblk++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) W.O[cblk][i] *= alpha[i];
-#pragma unroll
-        for (int j = 0; j < GQ; j++) {
-            const float aj = __shfl(alpha[j & 3], 16 * (j >> 2));
-            if (ROWS_SEEN) { W.oF[j][0] *= aj; W.oF[j][1] *= aj; }   // still zero while only quantized blocks were seen
-            W.accz[j] *= aj;
+            if (n == 0 && rq < 2 && 4 * rq + i < GQ) L.alpha[buf][4 * rq + i] = alpha;
         }
     }
+    if (lane == 0) L.rescale[buf] = grow ? 1 : 0;
     float p[2][4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -294,18 +297,39 @@ __device__ __forceinline__ void softmax_update(const float (&s)[2][4], WaveState
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             if (4 * rq + i < GQ) {
-                L.P[(4 * rq + i) % GQ][n] = p[0][i];
-                L.P[(4 * rq + i) % GQ][16 + n] = p[1][i];
+                L.P[buf][(4 * rq + i) % GQ][n] = p[0][i];
+                L.P[buf][(4 * rq + i) % GQ][16 + n] = p[1][i];
             }
         }
     }
-    wave_lds_sync();
+}
+
+// ------------------------------------------------------------------ value wave
+
+// shrink everything accumulated so far if the key wave moved the reference maximum for this block
+template <int GQ>
+__device__ __forceinline__ void apply_rescale(ValueState<GQ> &W, const PairLds<GQ> &L, int buf, int lane)
+{
+    const int rq = lane >> 4;
+    if (__builtin_amdgcn_readfirstlane(L.rescale[buf])) {
+        const float4 al = *reinterpret_cast<const float4 *>(&L.alpha[buf][4 * (rq & 1)]);
+        const float alpha[4] = {al.x, al.y, al.z, al.w};
+#pragma unroll
+        for (int cblk = 0; cblk < 8; cblk++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) W.O[cblk][i] *= alpha[i];
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            const float aj = L.alpha[buf][j];
+            W.oF[j][0] *= aj; W.oF[j][1] *= aj; W.accz[j] *= aj;
+        }
+    }
 }
 
 // output contribution of a quantized block
-template <int KB, int VB, int GQ>
-__device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, const QueryRegs<GQ> &Q, WaveState<GQ> &W,
-                                              WaveLds<GQ> &L, int lane)
+template <int VB, int GQ>
+__device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const QueryRegs<GQ> &Q, ValueState<GQ> &W,
+                                              PairLds<GQ> &L, int buf, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
     // keep p*s at the top of the fp16 range; when a block brings a larger scale, re-base the accumulators (exact)
@@ -317,15 +341,15 @@ __device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, cons
             for (int i = 0; i < 4; i++) W.O[cblk][i] = ldexpf(W.O[cblk][i], W.ev - ev);
         W.ev = ev;
     }
-    const float sv0 = ldexpf(blk.vs.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(blk.vs.y * Q.vw1, 14 - W.ev);
+    const float sv0 = ldexpf(blk.s.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(blk.s.y * Q.vw1, 14 - W.ev);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
-        const float2 pp = *reinterpret_cast<const float2 *>(&L.P[j][2 * n]);
+        const float2 pp = *reinterpret_cast<const float2 *>(&L.P[buf][j][2 * n]);
         uint32_t hi, lo;
         split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
         *reinterpret_cast<uint32_t *>(&L.Av[rq][j][2 * n]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Av[rq][8 + j][2 * n]) = lo;
-        W.accz[j] = fmaf(pp.x, blk.vz.x, fmaf(pp.y, blk.vz.y, W.accz[j]));
+        W.accz[j] = fmaf(pp.x, blk.z.x, fmaf(pp.y, blk.z.y, W.accz[j]));
     }
     wave_lds_sync();
     // each code operand reads 1 + c * 2^-k: the second MFMA against minus-ones removes the "1 +" part at once
@@ -337,17 +361,16 @@ __device__ __forceinline__ void output_packed(const BlockRegs<KB, VB> &blk, cons
 #pragma unroll
         for (int c2 = 0; c2 < 2; c2++) {
             const int cblk = 2 * gd + c2;
-            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.vdw, cblk, Q.one), W.O[cblk], 0, 0, 0);
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.dw, cblk, Q.one), W.O[cblk], 0, 0, 0);
             W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, minus_ones, W.O[cblk], 0, 0, 0);
         }
     }
-    wave_lds_sync();
 }
 
 // output contribution of nt fp16 rows: lane owns channels 2*lane, 2*lane+1
 template <int GQ>
-__device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, WaveState<GQ> &W,
-                                            WaveLds<GQ> &L, int lane)
+__device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, ValueState<GQ> &W,
+                                            const PairLds<GQ> &L, int buf, int lane)
 {
     for (int tt = 0; tt < nt; tt++) {
         const int pos = pos0 + tt;
@@ -356,18 +379,20 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
         const float v0 = half_lo(x), v1 = half_hi(x);
 #pragma unroll
         for (int j = 0; j < GQ; j++) {
-            const float pj = L.P[j][tt];
+            const float pj = L.P[buf][j][tt];
             W.oF[j][0] = fmaf(pj, v0, W.oF[j][0]);
             W.oF[j][1] = fmaf(pj, v1, W.oF[j][1]);
         }
     }
-    wave_lds_sync();
 }
 
+// ------------------------------------------------------------------ kernel
+
 template <int KB, int VB, int GQ>
-__global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
+__global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows j and 8 + j of a 16-row tile");
+    constexpr bool kFast = KB < 16 && VB < 16;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform on purpose: block indices stay scalar
     const int n = lane & 15, rq = lane >> 4;
@@ -377,20 +402,23 @@ __global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
     const int head0 = blockIdx.z * GQ;
     const int nvalid = gq_total - head0 < GQ ? gq_total - head0 : GQ;
     const size_t qrow0 = (size_t)b * a.Hq + (size_t)h * gq_total + head0;
+    // waves 0,1 / 2,3 take the key / value role in even work-groups and the other way round in odd ones,
+    // so that both kinds of wave land on every SIMD
+    const int pair = wave & 1;
+    const bool key_wave = ((wave >> 1) ^ (split + bh)) & 1 ? false : true;
 
-    __shared__ __attribute__((aligned(16))) WaveLds<GQ> lds[4];
+    __shared__ __attribute__((aligned(16))) PairLds<GQ> pairs[2];
     __shared__ __attribute__((aligned(16))) _Float16 aq_lds[16][kD + 8];
-    __shared__ __attribute__((aligned(16))) float o_lds[4][GQ][kD];
-    __shared__ float az_lds[4][GQ][4];
-    __shared__ float ml_lds[4][GQ][2];
-    WaveLds<GQ> &L = lds[wave];
+    __shared__ __attribute__((aligned(16))) float o_lds[2][GQ][kD];
+    __shared__ float az_lds[2][GQ][4];
+    __shared__ float ml_lds[2][GQ][2];
+    PairLds<GQ> &L = pairs[pair];
 
-    // rows that are never written must read as zero
-    for (int i = tid; i < (int)(sizeof(lds) / 4); i += 256) reinterpret_cast<uint32_t *>(&lds[0])[i] = 0u;
-
-    // ---- query setup: exact fp16 tiles for the q.z and fp16-row MFMAs, scaled fp32 pairs for q*s
+    // ---- query setup
     QueryRegs<GQ> Q;
     Q.c = a.scale_log2e;
+    Q.one = kOne2;
+    asm volatile("" : "+v"(Q.one));
     {
         float qraw[GQ][2];
         float qmax = 0.0f;
@@ -407,152 +435,207 @@ __global__ __launch_bounds__(256, 2) void decode_mfma(DecodeArgs a)
         int qexp = 0;
         if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
         Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
-        Q.one = kOne2;
-        asm volatile("" : "+v"(Q.one));
 #pragma unroll
         for (int j = 0; j < GQ; j++) {
             Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
             Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
         }
-        // rows j and 8 + j of the shared query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
-        {
-            const int row = tid >> 4, jr = row & 7;
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * (tid & 15));
-            *reinterpret_cast<uint4 *>(&aq_lds[row][8 * (tid & 15)]) = x;
-        }
+        // rows j and 8 + j of the shared exact-fp16 query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
+        const int row = tid >> 4, jr = row & 7;
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * (tid & 15));
+        *reinterpret_cast<uint4 *>(&aq_lds[row][8 * (tid & 15)]) = x;
         Q.Aq = &aq_lds[0][0];
         Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
         Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
     }
     __syncthreads();
 
-    WaveState<GQ> W;
-#pragma unroll
-    for (int i = 0; i < 4; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
-#pragma unroll
-    for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int j = 0; j < GQ; j++) { W.oF[j][0] = W.oF[j][1] = 0.0f; W.accz[j] = 0.0f; }
-    W.ev = -100;
-
+    // ---- work of this group: units [u0, u1) = quantized blocks, then chunks of <= 32 fp16 window tokens.
+    // Phase 1 covers the fully quantized blocks (only when both tensors are quantized), phase 2 the rest.
+    // A pair takes every second unit of a phase; every wave executes the same number of barriers.
     const int units = a.n_blocks + (a.n_res + 31) / 32;
     const int u0 = split * a.units_per_split;
     const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
-    int u = u0 + wave;
+    const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
+    const int f1c = f1 > u0 ? f1 : u0;
+    const int np = f1c - u0 - pair > 0 ? (f1c - u0 - pair + 1) / 2 : 0;   // my pair's units in phase 1
+    const int nit1 = (f1c - u0 + 1) / 2;                                   // pair 0's count = iterations of phase 1
+    const int ng = u1 - f1c - pair > 0 ? (u1 - f1c - pair + 1) / 2 : 0;
+    const int nit2 = (u1 - f1c + 1) / 2;
+    const size_t blk0 = (size_t)bh * a.NB;
+    // block index of my pair's i-th phase-1 unit, clamped so that prefetches never leave the range
+    auto blk1 = [&](int i) {
+        const int last = np > 0 ? np - 1 : 0;
+        const int u = u0 + (np > 0 ? pair : 0) + 2 * (i < last ? i : last);
+        return blk0 + (size_t)u;
+    };
 
-    // ---- hot loop: fully quantized blocks, the next block's loads always in flight.  The prefetch is
-    // unconditional (the index is clamped) so that the wait counters stay exact.
-    if constexpr (KB < 16 && VB < 16) {
-        const int ub = u1 < a.n_blocks ? u1 : a.n_blocks;
-        if (u < ub) {
-            const size_t base = (size_t)bh * a.NB;
-            BlockRegs<KB, VB> r0, r1;
-            load_block<KB, VB>(a, base + u, lane, r0);
-            float s[2][4];
-            while (true) {
-                load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r1);
-                scores_packed<KB, VB, GQ>(r0, Q, L, lane, s);
-                softmax_update<GQ, false>(s, W, L, lane);
-                output_packed<KB, VB, GQ>(r0, Q, W, L, lane);
-                u += 4;
-                if (u >= ub) break;
-                load_block<KB, VB>(a, base + (u + 4 < ub ? u + 4 : ub - 1), lane, r0);
-                scores_packed<KB, VB, GQ>(r1, Q, L, lane, s);
-                softmax_update<GQ, false>(s, W, L, lane);
-                output_packed<KB, VB, GQ>(r1, Q, W, L, lane);
-                u += 4;
-                if (u >= ub) break;
-            }
-        }
-    }
-
-    // ---- everything else: fp16 window chunks, and blocks of layers that keep K or V in fp16
-    for (; u < u1; u += 4) {
-        const bool packed = u < a.n_blocks;
-        const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
-        const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
-        BlockRegs<KB, VB> r;
-        if (packed) load_block<KB, VB>(a, (size_t)bh * a.NB + u, lane, r);
+    if (key_wave) {
+        // =========================================================== key wave
+        KeyState<GQ> W;
+#pragma unroll
+        for (int i = 0; i < 4; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
         float s[2][4];
-        bool k_rows = true;
-        if constexpr (KB < 16) if (packed) {
-            k_rows = false;
-            scores_packed<KB, VB, GQ>(r, Q, L, lane, s);
-        }
-        if (k_rows) {
-            const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
-                                           : a.lv.kres + (size_t)bh * a.RC * kD;
-            const int p0 = pos0 + n, p1 = pos0 + 16 + n;
-            scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
-        }
-        softmax_update<GQ, true>(s, W, L, lane);
-        bool v_rows = true;
-        if constexpr (VB < 16) if (packed) {
-            v_rows = false;
-            output_packed<KB, VB, GQ>(r, Q, W, L, lane);
-        }
-        if (v_rows) {
-            const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
-                                           : a.lv.vres + (size_t)bh * a.RC * kD;
-            output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, lane);
-        }
-    }
-
-    // ---------------------------------------------------- wave results -> LDS
-#pragma unroll
-    for (int i = 0; i < 4; i++) W.l[i] = row_sum16(W.l[i]);
-#pragma unroll
-    for (int j = 0; j < GQ; j++) {
-        W.accz[j] = row_sum16(W.accz[j]);
-        if (n == 0) az_lds[wave][j][rq] = W.accz[j];
-    }
-    constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
-    const float two24 = ldexpf(1.0f, vshift + W.ev - 14), two13 = two24;   // high and low parts carry the same weight
-    if (rq < 2) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (4 * rq + i < GQ) {
-                const int j = (4 * rq + i) % GQ;
-#pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] = two24 * W.O[cblk][i];
-                if (n == 0) { ml_lds[wave][j][0] = W.m[i]; ml_lds[wave][j][1] = W.l[i]; }
+        if constexpr (kFast) {
+            if (nit1 > 0) {
+                CodeRegs<KB> k0, k1;
+                load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(0), lane, k0);
+                int i = 0;
+                while (true) {
+                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + 1), lane, k1);
+                    if (i < np) {
+                        scores_packed<KB, GQ>(k0, Q, L, lane, s);
+                        softmax_publish<GQ>(s, W, L, i & 1, lane);
+                    }
+                    wg_barrier();
+                    if (++i >= nit1) break;
+                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + 1), lane, k0);
+                    if (i < np) {
+                        scores_packed<KB, GQ>(k1, Q, L, lane, s);
+                        softmax_publish<GQ>(s, W, L, i & 1, lane);
+                    }
+                    wg_barrier();
+                    if (++i >= nit1) break;
+                }
             }
         }
-    }
-    wave_lds_sync();
-    if (rq >= 2) {
+        wg_barrier();                                   // the value waves finish the last unit of phase 1
+        for (int i = 0; i < nit2; i++) {
+            if (i < ng) {
+                const int u = f1c + pair + 2 * i;
+                const bool packed = u < a.n_blocks;
+                const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
+                const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
+                bool k_rows = true;
+                if constexpr (KB < 16) if (packed) {
+                    k_rows = false;
+                    CodeRegs<KB> r;
+                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
+                    scores_packed<KB, GQ>(r, Q, L, lane, s);
+                }
+                if (k_rows) {
+                    const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
+                                                   : a.lv.kres + (size_t)bh * a.RC * kD;
+                    const int p0 = pos0 + n, p1 = pos0 + 16 + n;
+                    scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
+                }
+                softmax_publish<GQ>(s, W, L, i & 1, lane);
+            }
+            wg_barrier();
+        }
+        wg_barrier();                                   // the value waves finish the last unit of phase 2
+        // ---- results of this pair: reference max and sum per head
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            if (4 * (rq - 2) + i < GQ) {
-                const int j = (4 * (rq - 2) + i) % GQ;
+            const float lsum = row_sum16(W.l[i]);
+            if (n == 0 && rq < 2 && 4 * rq + i < GQ) { ml_lds[pair][(4 * rq + i) % GQ][0] = W.m[i]; ml_lds[pair][(4 * rq + i) % GQ][1] = lsum; }
+        }
+    } else {
+        // =========================================================== value wave (one unit behind its key wave)
+        ValueState<GQ> W;
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[wave][j][16 * cblk + n] += two13 * W.O[cblk][i];
+        for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int j = 0; j < GQ; j++) { W.oF[j][0] = W.oF[j][1] = 0.0f; W.accz[j] = 0.0f; }
+        W.ev = -100;
+        if constexpr (kFast) {
+            if (nit1 > 0) {
+                CodeRegs<VB> v0, v1;
+                load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(0), lane, v0);
+                wg_barrier();                           // the key waves produce the first block
+                int i = 0;
+                while (true) {
+                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + 1), lane, v1);
+                    if (i < np) {
+                        apply_rescale<GQ>(W, L, i & 1, lane);
+                        output_packed<VB, GQ>(v0, Q, W, L, i & 1, lane);
+                    }
+                    wg_barrier();
+                    if (++i >= nit1) break;
+                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + 1), lane, v0);
+                    if (i < np) {
+                        apply_rescale<GQ>(W, L, i & 1, lane);
+                        output_packed<VB, GQ>(v1, Q, W, L, i & 1, lane);
+                    }
+                    wg_barrier();
+                    if (++i >= nit1) break;
+                }
+            } else {
+                wg_barrier();
+            }
+        } else {
+            wg_barrier();
+        }
+        wg_barrier();                                   // the key waves produce the first unit of phase 2
+        for (int i = 0; i < nit2; i++) {
+            if (i < ng) {
+                const int u = f1c + pair + 2 * i;
+                const bool packed = u < a.n_blocks;
+                const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
+                const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
+                apply_rescale<GQ>(W, L, i & 1, lane);
+                bool v_rows = true;
+                if constexpr (VB < 16) if (packed) {
+                    v_rows = false;
+                    CodeRegs<VB> r;
+                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
+                    output_packed<VB, GQ>(r, Q, W, L, i & 1, lane);
+                }
+                if (v_rows) {
+                    const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
+                                                   : a.lv.vres + (size_t)bh * a.RC * kD;
+                    output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, i & 1, lane);
+                }
+            }
+            wg_barrier();
+        }
+        // ---- results of this pair: un-normalised output per head and channel
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            W.accz[j] = row_sum16(W.accz[j]);
+            if (n == 0) az_lds[pair][j][rq] = W.accz[j];
+        }
+        constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
+        const float wO = ldexpf(1.0f, vshift + W.ev - 14);       // high and low parts carry the same weight
+        if (rq < 2) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                if (4 * rq + i < GQ) {
+                    const int j = (4 * rq + i) % GQ;
+#pragma unroll
+                    for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] = wO * W.O[cblk][i];
+                }
             }
         }
-    }
-    wave_lds_sync();
+        wave_lds_sync();
+        if (rq >= 2) {
 #pragma unroll
-    for (int j = 0; j < GQ; j++) {
-        o_lds[wave][j][2 * lane] += W.oF[j][0];
-        o_lds[wave][j][2 * lane + 1] += W.oF[j][1];
+            for (int i = 0; i < 4; i++) {
+                if (4 * (rq - 2) + i < GQ) {
+                    const int j = (4 * (rq - 2) + i) % GQ;
+#pragma unroll
+                    for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] += wO * W.O[cblk][i];
+                }
+            }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            o_lds[pair][j][2 * lane] += W.oF[j][0];
+            o_lds[pair][j][2 * lane + 1] += W.oF[j][1];
+        }
     }
     __syncthreads();
 
-    // ---------------------------------------------------- merge the 4 waves, write the split's partial
+    // ---------------------------------------------------- merge the 2 pairs, write the split's partial
     for (int i = tid; i < nvalid * kD; i += 256) {
         const int j = i / kD, d = i % kD;
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < 4; w++) M = fmaxf(M, ml_lds[w][j][0]);
-        float Lsum = 0.0f, Osum = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 4; w++) {
-            const float mw = ml_lds[w][j][0];
-            const float f = mw == -INFINITY ? 0.0f : exp2f(mw - M);
-            Lsum = fmaf(ml_lds[w][j][1], f, Lsum);
-            Osum = fmaf(o_lds[w][j][d] + az_lds[w][j][d >> 5], f, Osum);
-        }
+        const float m0 = ml_lds[0][j][0], m1 = ml_lds[1][j][0];
+        const float M = fmaxf(m0, m1);
+        const float f0 = m0 == -INFINITY ? 0.0f : exp2f(m0 - M), f1w = m1 == -INFINITY ? 0.0f : exp2f(m1 - M);
+        const float Lsum = ml_lds[0][j][1] * f0 + ml_lds[1][j][1] * f1w;
+        const float Osum = (o_lds[0][j][d] + az_lds[0][j][d >> 5]) * f0 + (o_lds[1][j][d] + az_lds[1][j][d >> 5]) * f1w;
         const size_t prow = (qrow0 + j) * a.splits + split;
         a.part_o[prow * kD + d] = Osum;
         if (d == 0) { a.part_ml[prow * 2] = M; a.part_ml[prow * 2 + 1] = Lsum; }
