@@ -220,10 +220,10 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     const int units = a.n_blocks + (a.n_res + 31) / 32;
     int splits = c->splits;
     if (splits <= 0) {
-        // two 256-thread groups per compute unit fill the GPU (512 groups); more splits only add
-        // per-group set-up and merge work, so split no further than that and keep >= 8 units per group
+        // four 256-thread groups per compute unit (1024 groups) keep 4 waves on every SIMD; more splits
+        // only add per-group set-up and merge work, so split no further and keep >= 8 units per group
         const int BH = a.B * a.Hkv;
-        splits = (512 + BH - 1) / BH;
+        splits = (1024 + BH - 1) / BH;
         const int cap = (units + 7) / 8;
         if (splits > cap) splits = cap;
     }

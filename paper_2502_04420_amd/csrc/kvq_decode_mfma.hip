@@ -10,9 +10,9 @@
 // 1 + c * 2^-k exactly (k depends on the bit position; differences are folded into the A
 // operand), so "conversion" is about one AND-OR per two codes; the "1 +" part is measured by
 // one more MFMA of the same A tile against all-ones and subtracted.  The A operand carries q_d s_d (scores) or p_t s_tg (output); to keep fp32-class
-// accuracy it is split into a high and a low fp16 part held in rows j and 8 + j of the 16-row
-// tile (j = query head within the group, at most 8), and the two partial results are added
-// after the MFMA.  The zero-point terms: q . z is one more MFMA per 32 channels (q and z are
+// accuracy it is split into a high and a low fp16 part held in rows 2j and 2j + 1 of the 16-row
+// tile (j = query head within the group, at most 8); a lane of the result tile holds both rows
+// of a head, so the two partial results are added in registers after the MFMA.  The zero-point terms: q . z is one more MFMA per 32 channels (q and z are
 // exact in fp16), sum_t p_t z_tg is a handful of fp32 FMAs per block.
 //
 // A work-group owns one (batch, kv head, split).  Its 4 waves form two pairs; in a pair one wave
@@ -162,21 +162,21 @@ __device__ __forceinline__ void wg_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// LDS of one key-wave / value-wave pair
+// LDS of one key-wave / value-wave pair.  A tiles: row 2j = high parts, row 2j + 1 = low parts of head j.
 template <int GQ>
-struct PairLds {
-    _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]: rows j = high parts, 8 + j = low parts
-    _Float16 Zk[kD];               // key wave: key zero-points as fp16 (exact)
+struct __attribute__((aligned(16))) PairLds {
+    _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]
     _Float16 Av[4][16][32 + 8];    // value wave: output A tiles [channel group][row][token]
-    float P[2][GQ][32];            // hand-off: softmax numerators of a block, double-buffered
+    _Float16 Zk[kD];               // key wave: key zero-points as fp16 (exact)
+    float P[2][8][32];             // hand-off: softmax numerators of a block per head, double-buffered
     float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
-    int rescale[2];                // hand-off: non-zero when alpha is not all ones
+    int rescale[2][2];             // hand-off: non-zero when alpha is not all ones (padded to 16 bytes)
 };
 
 template <int GQ>
 struct QueryRegs {
     float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
-    const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows j and 8 + j)
+    const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows 2j and 2j + 1 = head j)
     float c, alpha_h;              // log2(e)/sqrt(D); weight of the partial scores
     uint32_t one;                  // two fp16 1.0 in a vector register
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
@@ -184,7 +184,7 @@ struct QueryRegs {
 
 template <int GQ>
 struct KeyState {
-    float m[4], l[4];              // rows 4*rq + i of the 16-row tile: reference max (log2 units), partial sum
+    float m[2], l[2];              // heads 2*rq, 2*rq + 1: reference max (log2 units), partial sum over this lane's tokens
 };
 
 template <int GQ>
@@ -197,10 +197,10 @@ struct ValueState {
 
 // ------------------------------------------------------------------ key wave
 
-// scores of a quantized block: s[th][i] for rows 4*rq + i, tokens 16*th + n
+// scores of a quantized block: s[th][hh] for head 2*rq + hh, tokens 16*th + n
 template <int KB, int GQ>
 __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
-                                              float (&s)[2][4])
+                                              float (&s)[2][2])
 {
     const int n = lane & 15, rq = lane >> 4;
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
@@ -211,8 +211,8 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
     for (int j = 0; j < GQ; j++) {
         uint32_t hi, lo;
         split_pair(Q.q2[j][0] * ks0, Q.q2[j][1] * ks1, hi, lo);
-        *reinterpret_cast<uint32_t *>(&L.Ak[j][2 * lane]) = hi;
-        *reinterpret_cast<uint32_t *>(&L.Ak[8 + j][2 * lane]) = lo;
+        *reinterpret_cast<uint32_t *>(&L.Ak[2 * j][2 * lane]) = hi;
+        *reinterpret_cast<uint32_t *>(&L.Ak[2 * j + 1][2 * lane]) = lo;
     }
     *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.z.x, blk.z.y));
     wave_lds_sync();
@@ -227,21 +227,20 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
         Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
         Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
+    // this lane holds rows 4*rq + i: (high, low) of head 2*rq and (high, low) of head 2*rq + 1
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        float h0, l0, h1, l1;
-        halves_of(S0[i] - Dn[i], h0, l0);  // lanes 0..31 hold the high-part rows, 32..63 the low-part rows
-        halves_of(S1[i] - Dn[i], h1, l1);
-        const float zc = Q.c * Z[i];
-        s[0][i] = fmaf(ah, h0 + l0, zc);
-        s[1][i] = fmaf(ah, h1 + l1, zc);
+    for (int hh = 0; hh < 2; hh++) {
+        const float d = Dn[2 * hh] + Dn[2 * hh + 1];
+        const float zc = Q.c * Z[2 * hh];
+        s[0][hh] = fmaf(ah, (S0[2 * hh] + S0[2 * hh + 1]) - d, zc);
+        s[1][hh] = fmaf(ah, (S1[2 * hh] + S1[2 * hh + 1]) - d, zc);
     }
 }
 
-// scores of up to 32 fp16 rows (16-bit region or window ring)
+// scores of up to 32 fp16 rows (16-bit region or window ring); rows 2j and 2j + 1 of the query tile are equal
 template <int GQ>
 __device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t *row1, int nt, const QueryRegs<GQ> &Q,
-                                            int lane, float (&s)[2][4])
+                                            int lane, float (&s)[2][2])
 {
     const int n = lane & 15, rq = lane >> 4;
     float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0;
@@ -255,52 +254,38 @@ __device__ __forceinline__ void scores_rows(const uint16_t *row0, const uint16_t
         S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, as_half8(x1.x, x1.y, x1.z, x1.w), S1, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        s[0][i] = n < nt ? Q.c * S0[i] : -INFINITY;
-        s[1][i] = 16 + n < nt ? Q.c * S1[i] : -INFINITY;
+    for (int hh = 0; hh < 2; hh++) {
+        s[0][hh] = n < nt ? Q.c * S0[2 * hh] : -INFINITY;
+        s[1][hh] = 16 + n < nt ? Q.c * S1[2 * hh] : -INFINITY;
     }
 }
 
-// Online softmax over the block's 32 scores per row.  Publishes the numerators (L.P[buf]), and the factor
+// Online softmax over the block's 32 scores per head.  Publishes the numerators (L.P[buf]) and the factor
 // by which the value wave must shrink what it has accumulated (L.alpha[buf], L.rescale[buf]).
-// The reference maximum only has to keep the numerators in range: it is refreshed (exact row maximum)
-// when some score exceeds it by more than 1, so numerators stay <= 2 and the fp16 output operands
-// cannot overflow.  Rows of the tile that carry no head (row >= nrows) hold garbage and are ignored.
+// The reference maximum only has to keep the numerators in range: it is refreshed (exact maximum over
+// the block) when some score exceeds it by more than 1, so numerators stay <= 2 and the fp16 output
+// operands cannot overflow.  Heads that do not exist see all-zero operands, hence finite values.
 template <int GQ>
-__device__ __forceinline__ void softmax_publish(const float (&s)[2][4], KeyState<GQ> &W, PairLds<GQ> &L, int buf, int lane)
+__device__ __forceinline__ void softmax_publish(const float (&s)[2][2], KeyState<GQ> &W, PairLds<GQ> &L, int buf, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
-    bool over = false;
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-        if (4 * (rq & 1) + i < GQ) over = over || (fmaxf(s[0][i], s[1][i]) > W.m[i] + 1.0f);
-    const bool grow = __any(over);
+    const float mx0 = fmaxf(s[0][0], s[1][0]), mx1 = fmaxf(s[0][1], s[1][1]);
+    const bool grow = __any((mx0 > W.m[0] + 1.0f) || (mx1 > W.m[1] + 1.0f));
     if (grow) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const float mnew = fmaxf(W.m[i], row_max16(fmaxf(s[0][i], s[1][i])));
-            const float alpha = exp2f(W.m[i] - mnew);
-            W.l[i] *= alpha;
-            W.m[i] = mnew;
-            if (n == 0 && rq < 2 && 4 * rq + i < GQ) L.alpha[buf][4 * rq + i] = alpha;
-        }
+        const float mn0 = fmaxf(W.m[0], row_max16(mx0)), mn1 = fmaxf(W.m[1], row_max16(mx1));
+        const float a0 = __builtin_amdgcn_exp2f(W.m[0] - mn0), a1 = __builtin_amdgcn_exp2f(W.m[1] - mn1);
+        W.l[0] *= a0; W.l[1] *= a1;
+        W.m[0] = mn0; W.m[1] = mn1;
+        L.alpha[buf][2 * rq] = a0;            // the 16 lanes of a row write the same value
+        L.alpha[buf][2 * rq + 1] = a1;
     }
-    if (lane == 0) L.rescale[buf] = grow ? 1 : 0;
-    float p[2][4];
+    if (lane == 0) L.rescale[buf][0] = grow ? 1 : 0;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        p[0][i] = exp2f(s[0][i] - W.m[i]);
-        p[1][i] = exp2f(s[1][i] - W.m[i]);
-        W.l[i] += p[0][i] + p[1][i];
-    }
-    if (rq < 2) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (4 * rq + i < GQ) {
-                L.P[buf][(4 * rq + i) % GQ][n] = p[0][i];
-                L.P[buf][(4 * rq + i) % GQ][16 + n] = p[1][i];
-            }
-        }
+    for (int hh = 0; hh < 2; hh++) {
+        const float p0 = __builtin_amdgcn_exp2f(s[0][hh] - W.m[hh]), p1 = __builtin_amdgcn_exp2f(s[1][hh] - W.m[hh]);
+        W.l[hh] += p0 + p1;
+        L.P[buf][2 * rq + hh][n] = p0;
+        L.P[buf][2 * rq + hh][16 + n] = p1;
     }
 }
 
@@ -311,13 +296,13 @@ template <int GQ>
 __device__ __forceinline__ void apply_rescale(ValueState<GQ> &W, const PairLds<GQ> &L, int buf, int lane)
 {
     const int rq = lane >> 4;
-    if (__builtin_amdgcn_readfirstlane(L.rescale[buf])) {
-        const float4 al = *reinterpret_cast<const float4 *>(&L.alpha[buf][4 * (rq & 1)]);
-        const float alpha[4] = {al.x, al.y, al.z, al.w};
+    if (__builtin_amdgcn_readfirstlane(L.rescale[buf][0])) {
+        const float2 al = *reinterpret_cast<const float2 *>(&L.alpha[buf][2 * rq]);
 #pragma unroll
-        for (int cblk = 0; cblk < 8; cblk++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) W.O[cblk][i] *= alpha[i];
+        for (int cblk = 0; cblk < 8; cblk++) {
+            W.O[cblk][0] *= al.x; W.O[cblk][1] *= al.x;
+            W.O[cblk][2] *= al.y; W.O[cblk][3] *= al.y;
+        }
 #pragma unroll
         for (int j = 0; j < GQ; j++) {
             const float aj = L.alpha[buf][j];
@@ -347,8 +332,8 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
         const float2 pp = *reinterpret_cast<const float2 *>(&L.P[buf][j][2 * n]);
         uint32_t hi, lo;
         split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
-        *reinterpret_cast<uint32_t *>(&L.Av[rq][j][2 * n]) = hi;
-        *reinterpret_cast<uint32_t *>(&L.Av[rq][8 + j][2 * n]) = lo;
+        *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j][2 * n]) = hi;
+        *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j + 1][2 * n]) = lo;
         W.accz[j] = fmaf(pp.x, blk.z.x, fmaf(pp.y, blk.z.y, W.accz[j]));
     }
     wave_lds_sync();
@@ -440,14 +425,26 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
             Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
             Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
         }
-        // rows j and 8 + j of the shared exact-fp16 query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
-        const int row = tid >> 4, jr = row & 7;
+        // rows 2j and 2j + 1 of the shared exact-fp16 query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
+        const int row = tid >> 4, jr = row >> 1;
         uint4 x = make_uint4(0, 0, 0, 0);
         if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * (tid & 15));
         *reinterpret_cast<uint4 *>(&aq_lds[row][8 * (tid & 15)]) = x;
         Q.Aq = &aq_lds[0][0];
         Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
         Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
+    }
+    if constexpr (GQ < 8) {
+        // A-tile rows of heads that do not exist are never written: they must read as zero
+        for (int i = tid; i < 2 * (16 - 2 * GQ) * (kD + 8) / 2; i += 256) {
+            const int pr = i / ((16 - 2 * GQ) * (kD + 8) / 2), w = i % ((16 - 2 * GQ) * (kD + 8) / 2);
+            reinterpret_cast<uint32_t *>(&pairs[pr].Ak[2 * GQ][0])[w] = 0u;
+        }
+        for (int i = tid; i < 2 * 4 * (16 - 2 * GQ) * (32 + 8) / 2; i += 256) {
+            const int per = (16 - 2 * GQ) * (32 + 8) / 2;
+            const int pr = i / (4 * per), gd = (i / per) % 4, w = i % per;
+            reinterpret_cast<uint32_t *>(&pairs[pr].Av[gd][2 * GQ][0])[w] = 0u;
+        }
     }
     __syncthreads();
 
@@ -475,8 +472,8 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
         // =========================================================== key wave
         KeyState<GQ> W;
 #pragma unroll
-        for (int i = 0; i < 4; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
-        float s[2][4];
+        for (int i = 0; i < 2; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
+        float s[2][2];
         if constexpr (kFast) {
             if (nit1 > 0) {
                 CodeRegs<KB> k0, k1;
@@ -527,9 +524,9 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
         wg_barrier();                                   // the value waves finish the last unit of phase 2
         // ---- results of this pair: reference max and sum per head
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const float lsum = row_sum16(W.l[i]);
-            if (n == 0 && rq < 2 && 4 * rq + i < GQ) { ml_lds[pair][(4 * rq + i) % GQ][0] = W.m[i]; ml_lds[pair][(4 * rq + i) % GQ][1] = lsum; }
+        for (int hh = 0; hh < 2; hh++) {
+            const float lsum = row_sum16(W.l[hh]);
+            if (n == 0 && 2 * rq + hh < GQ) { ml_lds[pair][(2 * rq + hh) % GQ][0] = W.m[hh]; ml_lds[pair][(2 * rq + hh) % GQ][1] = lsum; }
         }
     } else {
         // =========================================================== value wave (one unit behind its key wave)
@@ -598,25 +595,12 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
         }
         constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
         const float wO = ldexpf(1.0f, vshift + W.ev - 14);       // high and low parts carry the same weight
-        if (rq < 2) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                if (4 * rq + i < GQ) {
-                    const int j = (4 * rq + i) % GQ;
+        for (int hh = 0; hh < 2; hh++) {
+            if (2 * rq + hh < GQ) {
+                const int j = (2 * rq + hh) % GQ;
 #pragma unroll
-                    for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] = wO * W.O[cblk][i];
-                }
-            }
-        }
-        wave_lds_sync();
-        if (rq >= 2) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                if (4 * (rq - 2) + i < GQ) {
-                    const int j = (4 * (rq - 2) + i) % GQ;
-#pragma unroll
-                    for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] += wO * W.O[cblk][i];
-                }
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] = wO * (W.O[cblk][2 * hh] + W.O[cblk][2 * hh + 1]);
             }
         }
         wave_lds_sync();
