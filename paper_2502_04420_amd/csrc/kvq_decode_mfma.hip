@@ -399,8 +399,29 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
     __shared__ float ml_lds[2][GQ][2];
     PairLds<GQ> &L = pairs[pair];
 
-    // ---- query setup
+    // ---- work of this group: units [u0, u1) = quantized blocks, then chunks of <= 32 fp16 window tokens.
+    // Phase 1 covers the fully quantized blocks (only when both tensors are quantized), phase 2 the rest.
+    // A pair takes every second unit of a phase; every wave executes the same number of barriers.
+    const int units = a.n_blocks + (a.n_res + 31) / 32;
+    const int u0 = split * a.units_per_split;
+    const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
+    const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
+    const int f1c = f1 > u0 ? f1 : u0;
+    const int np = f1c - u0 - pair > 0 ? (f1c - u0 - pair + 1) / 2 : 0;   // my pair's units in phase 1
+    const int nit1 = (f1c - u0 + 1) / 2;                                   // pair 0's count = iterations of phase 1
+    const int ng = u1 - f1c - pair > 0 ? (u1 - f1c - pair + 1) / 2 : 0;
+    const int nit2 = (u1 - f1c + 1) / 2;
+    const size_t blk0 = (size_t)bh * a.NB;
+    // block index of my pair's i-th phase-1 unit, clamped so that prefetches never leave the range
+    auto blk1 = [&](int i) {
+        const int last = np > 0 ? np - 1 : 0;
+        const int u = u0 + (np > 0 ? pair : 0) + 2 * (i < last ? i : last);
+        return blk0 + (size_t)u;
+    };
+
+    // ---- query set-up (run by every wave, inside its role branch, after its first loads have been issued)
     QueryRegs<GQ> Q;
+    auto setup_query = [&]() {
     Q.c = a.scale_log2e;
     Q.one = kOne2;
     asm volatile("" : "+v"(Q.one));
@@ -448,36 +469,21 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
     }
     __syncthreads();
 
-    // ---- work of this group: units [u0, u1) = quantized blocks, then chunks of <= 32 fp16 window tokens.
-    // Phase 1 covers the fully quantized blocks (only when both tensors are quantized), phase 2 the rest.
-    // A pair takes every second unit of a phase; every wave executes the same number of barriers.
-    const int units = a.n_blocks + (a.n_res + 31) / 32;
-    const int u0 = split * a.units_per_split;
-    const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
-    const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
-    const int f1c = f1 > u0 ? f1 : u0;
-    const int np = f1c - u0 - pair > 0 ? (f1c - u0 - pair + 1) / 2 : 0;   // my pair's units in phase 1
-    const int nit1 = (f1c - u0 + 1) / 2;                                   // pair 0's count = iterations of phase 1
-    const int ng = u1 - f1c - pair > 0 ? (u1 - f1c - pair + 1) / 2 : 0;
-    const int nit2 = (u1 - f1c + 1) / 2;
-    const size_t blk0 = (size_t)bh * a.NB;
-    // block index of my pair's i-th phase-1 unit, clamped so that prefetches never leave the range
-    auto blk1 = [&](int i) {
-        const int last = np > 0 ? np - 1 : 0;
-        const int u = u0 + (np > 0 ? pair : 0) + 2 * (i < last ? i : last);
-        return blk0 + (size_t)u;
     };
 
     if (key_wave) {
         // =========================================================== key wave
+        CodeRegs<KB> k0, k1;
+        if constexpr (kFast) {
+            if (nit1 > 0) load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(0), lane, k0);
+        }
+        setup_query();
         KeyState<GQ> W;
 #pragma unroll
         for (int i = 0; i < 2; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
         float s[2][2];
         if constexpr (kFast) {
             if (nit1 > 0) {
-                CodeRegs<KB> k0, k1;
-                load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(0), lane, k0);
                 int i = 0;
                 while (true) {
                     load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + 1), lane, k1);
@@ -530,6 +536,11 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
         }
     } else {
         // =========================================================== value wave (one unit behind its key wave)
+        CodeRegs<VB> v0, v1;
+        if constexpr (kFast) {
+            if (nit1 > 0) load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(0), lane, v0);
+        }
+        setup_query();
         ValueState<GQ> W;
 #pragma unroll
         for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
@@ -538,8 +549,6 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
         W.ev = -100;
         if constexpr (kFast) {
             if (nit1 > 0) {
-                CodeRegs<VB> v0, v1;
-                load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(0), lane, v0);
                 wg_barrier();                           // the key waves produce the first block
                 int i = 0;
                 while (true) {

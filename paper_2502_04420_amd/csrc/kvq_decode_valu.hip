@@ -278,17 +278,36 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
 }
 
 // Merge the splits of one (batch, query head) by log-sum-exp and store fp16 (round to nearest even).
+// The partial records are fetched eight at a time with independent loads: a plain loop would pay one
+// memory latency per split.
 __global__ __launch_bounds__(128) void combine_splits(DecodeArgs a)
 {
     const size_t row = blockIdx.x;
     const int d = threadIdx.x;
-    float M = -INFINITY;
-    for (int s = 0; s < a.splits; s++) M = fmaxf(M, a.part_ml[(row * a.splits + s) * 2]);
-    float L = 0.0f, O = 0.0f;
-    for (int s = 0; s < a.splits; s++) {
-        const float f = exp2f(a.part_ml[(row * a.splits + s) * 2] - M);
-        L = fmaf(a.part_ml[(row * a.splits + s) * 2 + 1], f, L);
-        O = fmaf(a.part_o[(row * a.splits + s) * kD + d], f, O);
+    const float *ml = a.part_ml + row * a.splits * 2;
+    const float *po = a.part_o + row * a.splits * kD + d;
+    float M = -INFINITY, L = 0.0f, O = 0.0f;
+    for (int s0 = 0; s0 < a.splits; s0 += 8) {
+        float m8[8], l8[8], o8[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const bool ok = s0 + k < a.splits;
+            m8[k] = ok ? ml[(s0 + k) * 2] : -INFINITY;
+            l8[k] = ok ? ml[(s0 + k) * 2 + 1] : 0.0f;
+            o8[k] = ok ? po[(size_t)(s0 + k) * kD] : 0.0f;
+        }
+        float Mn = M;
+#pragma unroll
+        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, m8[k]);
+        const float fo = exp2f(M - Mn);          // M = -inf on the first pass: factor 0 on empty sums
+        L *= fo; O *= fo;
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const float f = exp2f(m8[k] - Mn);
+            L = fmaf(l8[k], f, L);
+            O = fmaf(o8[k], f, O);
+        }
+        M = Mn;
     }
     a.out[row * kD + d] = __builtin_bit_cast(uint16_t, (_Float16)(O / L));
 }
