@@ -121,7 +121,8 @@ int kvq_debug_export(kvq_ctx *ctx, int32_t layer, void *k_codes, void *k_scale, 
 /*
  * Tuning knobs (optional).  variant: 0 = choose automatically, 1 = vector-ALU kernel,
  * 2 = matrix-core kernel.  splits: 0 = automatic, else the number of token-range splits
- * per (batch, kv head) used to fill the GPU.  Returns KVQ_EINVAL for unknown values.
+ * per (batch, kv head) used to fill the GPU (at most 128).  Returns KVQ_EINVAL for unknown
+ * values.
  */
 int kvq_set_decode_options(kvq_ctx *ctx, int32_t variant, int32_t splits);
 

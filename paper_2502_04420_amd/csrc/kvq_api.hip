@@ -15,7 +15,7 @@
 
 namespace {
 
-constexpr int kMaxSplits = 64;
+constexpr int kMaxSplits = 128;
 constexpr size_t kAlign = 256;
 
 thread_local char g_last_error[256] = "";
@@ -218,13 +218,16 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     a.RC = c->plan.RC;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
     const int units = a.n_blocks + (a.n_res + 31) / 32;
+    const int variant = c->variant == 0 ? 2 : c->variant;     // the matrix-core kernel is the default
     int splits = c->splits;
     if (splits <= 0) {
-        // four 256-thread groups per compute unit (1024 groups) keep 4 waves on every SIMD; more splits
-        // only add per-group set-up and merge work, so split no further and keep >= 8 units per group
+        // 16 waves per compute unit (4 on every SIMD) over 256 compute units: 2048 two-wave groups of the
+        // matrix-core kernel or 1024 four-wave groups of the vector kernel.  More splits only add per-group
+        // set-up and merge work, so split no further and keep at least 4 (8) units per group.
         const int BH = a.B * a.Hkv;
-        splits = (1024 + BH - 1) / BH;
-        const int cap = (units + 7) / 8;
+        const int groups = variant == 2 ? 2048 : 1024, min_units = variant == 2 ? 4 : 8;
+        splits = (groups + BH - 1) / BH;
+        const int cap = (units + min_units - 1) / min_units;
         if (splits > cap) splits = cap;
     }
     if (splits > kMaxSplits) splits = kMaxSplits;
@@ -232,7 +235,6 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     if (splits < 1) splits = 1;
     a.units_per_split = (units + splits - 1) / splits;
     a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
-    const int variant = c->variant == 0 ? 2 : c->variant;     // the matrix-core kernel is the default
     hipError_t e = variant == 2 ? kvq::launch_decode_mfma(a, c->stream) : kvq::launch_decode_valu(a, c->stream);
     if (e != hipSuccess) return launch_failed("decode kernel", e);
     e = kvq::launch_combine(a, c->stream);

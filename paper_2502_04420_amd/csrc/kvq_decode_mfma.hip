@@ -6,21 +6,22 @@
 //   scores   sum_d q_d (c_td s_d + z_d) = sum_d (q_d s_d) c_td + sum_d q_d z_d
 //   output   sum_t p_t (c_td s_tg + z_tg) = sum_t (p_t s_tg) c_td + sum_t p_t z_tg
 //
-// The integer codes are the B operand.  Masked into the mantissa of an fp16 1.0 they read as
-// 1 + c * 2^-k exactly (k depends on the bit position; differences are folded into the A
-// operand), so "conversion" is about one AND-OR per two codes; the "1 +" part is measured by
-// one more MFMA of the same A tile against all-ones and subtracted.  The A operand carries q_d s_d (scores) or p_t s_tg (output); to keep fp32-class
-// accuracy it is split into a high and a low fp16 part held in rows 2j and 2j + 1 of the 16-row
-// tile (j = query head within the group, at most 8); a lane of the result tile holds both rows
-// of a head, so the two partial results are added in registers after the MFMA.  The zero-point terms: q . z is one more MFMA per 32 channels (q and z are
-// exact in fp16), sum_t p_t z_tg is a handful of fp32 FMAs per block.
+// The integer codes are the B operand.  Masked into the mantissa of an fp16 with a zero
+// exponent field they read as c * 2^-k exactly (k depends on the bit position; differences are
+// folded into the A operand), so "conversion" is about one AND per two codes.  The A operand
+// carries q_d s_d (scores) or p_t s_tg (output); to keep fp32-class accuracy it is split into a
+// high and a low fp16 part held in rows 2j and 2j + 1 of the 16-row tile (j = query head within
+// the group, at most 8); a lane of the result tile holds both rows of a head, so the two partial
+// results are added in registers after the MFMA.  The zero-point terms: q . z is one more MFMA
+// per 32 channels (q and z are exact in fp16), sum_t p_t z_tg is a handful of fp32 FMAs per block.
 //
-// A work-group owns one (batch, kv head, split).  Its 4 waves form two pairs; in a pair one wave
-// (the key wave) streams the key blocks and produces the softmax numerators of each block, the
-// other (the value wave) consumes them one block later and accumulates the output.  The hand-off
-// goes through double-buffered LDS tiles and one work-group barrier per block, so score and
-// output work of neighbouring blocks overlap on different SIMDs and each wave carries only half
-// of the state (which is what lets 3 to 4 waves share a SIMD and hide the memory latency).
+// A work-group owns one (batch, kv head, split) and has two waves: one (the key wave) streams the
+// key blocks and produces the softmax numerators of each block, the other (the value wave)
+// consumes them one block later and accumulates the output.  The hand-off goes through
+// double-buffered LDS tiles and one work-group barrier per block, so score and output work of
+// neighbouring blocks overlap on different SIMDs and each wave carries only half of the state
+// (which is what lets 4 waves share a SIMD and hide the memory latency).  Each wave writes its
+// part of the split's partial result itself; the splits are merged by combine_splits.
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -48,34 +49,31 @@ __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_b
 __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
 
 // B operand of MFMA m (8 codes of this lane) straight from the packed dwords.  Each code is
-// masked into the mantissa of an fp16 whose exponent field is forced to that of 1.0, so element
-// e of the operand is exactly 1 + code * 2^-kCodeShift<BITS> * code_weight<BITS>(e): a normal
-// number (the matrix core keeps about 24 bits below the largest *nominal* exponent of a sum, so
-// subnormal operands would lose precision).  The "1 +" is removed by one more MFMA of the same A
-// tile against an all-ones B tile.
-constexpr uint32_t kOne2 = 0x3C003C00u;      // two fp16 1.0
+// masked into the mantissa of an fp16 whose exponent field is zero: a subnormal number, which
+// the matrix core takes at face value, so element e of the operand is exactly
+// code * 2^-CodeShift<BITS> * code_weight<BITS>(e) and "conversion" costs about one AND per two
+// codes.  (The sum of a tile is aligned to the largest nominal exponent and keeps about 24 bits
+// below it, the same as for a normal operand 1 + code * 2^-10, without a "1 +" to remove.)
 
-// log2 of the divisor of the code in the base position: operand element = 1 + code * 2^-CodeShift
-template <int BITS> struct CodeShift { static constexpr int value = BITS == 2 ? 6 : 10; };
+// log2 of the divisor of the code in the base position: operand element = code * 2^-CodeShift
+template <int BITS> struct CodeShift { static constexpr int value = BITS == 2 ? 20 : 24; };
 
-// `one` is kOne2 held in a vector register the compiler cannot see through, so that each
-// (x & mask) | one becomes a single v_and_or_b32.
 template <int BITS>
-__device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m, uint32_t one)
+__device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m)
 {
     if constexpr (BITS == 8) {
-        // bytes (b0, b1), (b2, b3) -> halves 0x3C00 | b : 1 + b / 1024
+        // bytes (b0, b1), (b2, b3) -> halves 0x0000 | b : b * 2^-24
         const uint32_t w0 = dw[2 * m], w1 = dw[2 * m + 1];
-        return as_half8(__builtin_amdgcn_perm(one, w0, 0x05010500u), __builtin_amdgcn_perm(one, w0, 0x05030502u),
-                        __builtin_amdgcn_perm(one, w1, 0x05010500u), __builtin_amdgcn_perm(one, w1, 0x05030502u));
+        return as_half8(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u), __builtin_amdgcn_perm(0u, w0, 0x0C030C02u),
+                        __builtin_amdgcn_perm(0u, w1, 0x0C010C00u), __builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
     } else if constexpr (BITS == 4) {
-        // nibbles (k, k + 4) of the dword form a pair; mantissa bits 3:0 read 1 + c / 1024, bits 7:4 read 1 + 16 c / 1024
+        // nibbles (k, k + 4) of the dword form a pair; mantissa bits 3:0 read c * 2^-24, bits 7:4 read 16 c * 2^-24
         const uint32_t x = dw[m], y = x >> 8;
-        return as_half8((x & 0x000F000Fu) | one, (x & 0x00F000F0u) | one, (y & 0x000F000Fu) | one, (y & 0x00F000F0u) | one);
+        return as_half8(x & 0x000F000Fu, x & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
     } else {
-        // 2-bit fields at mantissa bits 5:4 (1 + c / 64) or 7:6 (1 + 4 c / 64), alternating
+        // 2-bit fields at mantissa bits 5:4 (c * 2^-20) or 7:6 (4 c * 2^-20), alternating
         const uint32_t x = dw[m >> 1], lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
-        return as_half8((lo & 0x00300030u) | one, (lo & 0x00C000C0u) | one, (hi & 0x00300030u) | one, (hi & 0x00C000C0u) | one);
+        return as_half8(lo & 0x00300030u, lo & 0x00C000C0u, hi & 0x00300030u, hi & 0x00C000C0u);
     }
 }
 
@@ -178,7 +176,6 @@ struct QueryRegs {
     float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
     const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows 2j and 2j + 1 = head j)
     float c, alpha_h;              // log2(e)/sqrt(D); weight of the partial scores
-    uint32_t one;                  // two fp16 1.0 in a vector register
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
 };
 
@@ -216,24 +213,21 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
     }
     *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.z.x, blk.z.y));
     wave_lds_sync();
-    float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0, Dn = S0;
-    const half8 ones = as_half8(Q.one, Q.one, Q.one, Q.one);
+    float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0;
 #pragma unroll
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
         const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
-        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb, Q.one), S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb, Q.one), S1, 0, 0, 0);
-        Dn = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, ones, Dn, 0, 0, 0);          // row sums of A: the "1 +" part
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb), S1, 0, 0, 0);
         Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
     // this lane holds rows 4*rq + i: (high, low) of head 2*rq and (high, low) of head 2*rq + 1
 #pragma unroll
     for (int hh = 0; hh < 2; hh++) {
-        const float d = Dn[2 * hh] + Dn[2 * hh + 1];
         const float zc = Q.c * Z[2 * hh];
-        s[0][hh] = fmaf(ah, (S0[2 * hh] + S0[2 * hh + 1]) - d, zc);
-        s[1][hh] = fmaf(ah, (S1[2 * hh] + S1[2 * hh + 1]) - d, zc);
+        s[0][hh] = fmaf(ah, S0[2 * hh] + S0[2 * hh + 1], zc);
+        s[1][hh] = fmaf(ah, S1[2 * hh] + S1[2 * hh + 1], zc);
     }
 }
 
@@ -337,17 +331,13 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
         W.accz[j] = fmaf(pp.x, blk.z.x, fmaf(pp.y, blk.z.y, W.accz[j]));
     }
     wave_lds_sync();
-    // each code operand reads 1 + c * 2^-k: the second MFMA against minus-ones removes the "1 +" part at once
-    const uint32_t mone = Q.one ^ 0x80008000u;
-    const half8 minus_ones = as_half8(mone, mone, mone, mone);
 #pragma unroll
     for (int gd = 0; gd < 4; gd++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
 #pragma unroll
         for (int c2 = 0; c2 < 2; c2++) {
             const int cblk = 2 * gd + c2;
-            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.dw, cblk, Q.one), W.O[cblk], 0, 0, 0);
-            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, minus_ones, W.O[cblk], 0, 0, 0);
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.dw, cblk), W.O[cblk], 0, 0, 0);
         }
     }
 }
@@ -374,12 +364,15 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
 // ------------------------------------------------------------------ kernel
 
 template <int KB, int VB, int GQ>
-__global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
+__global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 {
-    static_assert(GQ == 4 || GQ == 8, "rows j and 8 + j of a 16-row tile");
+    static_assert(GQ == 4 || GQ == 8, "rows 2j and 2j + 1 of a 16-row tile");
     constexpr bool kFast = KB < 16 && VB < 16;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform on purpose: block indices stay scalar
+    // register stages of the phase-1 pipelines (units in flight per wave = stages - 1)
+    constexpr int DK = KB <= 4 ? 3 : 2;
+    constexpr int DV = VB <= 4 ? 3 : 2;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform on purpose: block indices stay scalar
     const int n = lane & 15, rq = lane >> 4;
     const int split = blockIdx.x, bh = blockIdx.y;
     const int b = bh / a.Hkv, h = bh % a.Hkv;
@@ -387,251 +380,242 @@ __global__ __launch_bounds__(256, 3) void decode_mfma(DecodeArgs a)
     const int head0 = blockIdx.z * GQ;
     const int nvalid = gq_total - head0 < GQ ? gq_total - head0 : GQ;
     const size_t qrow0 = (size_t)b * a.Hq + (size_t)h * gq_total + head0;
-    // waves 0,1 / 2,3 take the key / value role in even work-groups and the other way round in odd ones,
+    // wave 0 / wave 1 take the key / value role in even work-groups and the other way round in odd ones,
     // so that both kinds of wave land on every SIMD
-    const int pair = wave & 1;
-    const bool key_wave = ((wave >> 1) ^ (split + bh)) & 1 ? false : true;
+    const bool key_wave = ((wave ^ (split + bh)) & 1) == 0;
 
-    __shared__ __attribute__((aligned(16))) PairLds<GQ> pairs[2];
+    __shared__ PairLds<GQ> L;
     __shared__ __attribute__((aligned(16))) _Float16 aq_lds[16][kD + 8];
-    __shared__ __attribute__((aligned(16))) float o_lds[2][GQ][kD];
-    __shared__ float az_lds[2][GQ][4];
-    __shared__ float ml_lds[2][GQ][2];
-    PairLds<GQ> &L = pairs[pair];
 
     // ---- work of this group: units [u0, u1) = quantized blocks, then chunks of <= 32 fp16 window tokens.
     // Phase 1 covers the fully quantized blocks (only when both tensors are quantized), phase 2 the rest.
-    // A pair takes every second unit of a phase; every wave executes the same number of barriers.
+    // Unit number it (counted from u0) is handed over through buffer it & 1.
     const int units = a.n_blocks + (a.n_res + 31) / 32;
     const int u0 = split * a.units_per_split;
     const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
     const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
     const int f1c = f1 > u0 ? f1 : u0;
-    const int np = f1c - u0 - pair > 0 ? (f1c - u0 - pair + 1) / 2 : 0;   // my pair's units in phase 1
-    const int nit1 = (f1c - u0 + 1) / 2;                                   // pair 0's count = iterations of phase 1
-    const int ng = u1 - f1c - pair > 0 ? (u1 - f1c - pair + 1) / 2 : 0;
-    const int nit2 = (u1 - f1c + 1) / 2;
+    const int n1 = f1c - u0, n2 = u1 - f1c;
     const size_t blk0 = (size_t)bh * a.NB;
-    // block index of my pair's i-th phase-1 unit, clamped so that prefetches never leave the range
+    // block index of the i-th phase-1 unit, clamped so that prefetches never leave the range
+    // Every group starts its sweep at a different place of its range and wraps around: groups advance at the
+    // same pace, and with equal phases their addresses would keep falling on the same memory channels.
+    const int rot = n1 > 0 ? (int)(((uint32_t)bh * 40503u + (uint32_t)split * 9973u) % (uint32_t)n1) : 0;
     auto blk1 = [&](int i) {
-        const int last = np > 0 ? np - 1 : 0;
-        const int u = u0 + (np > 0 ? pair : 0) + 2 * (i < last ? i : last);
-        return blk0 + (size_t)u;
+        const int last = n1 > 0 ? n1 - 1 : 0;
+        const int r = (i < last ? i : last) + rot;
+        return blk0 + (size_t)(u0 + (r < n1 ? r : r - n1));
     };
 
-    // ---- query set-up (run by every wave, inside its role branch, after its first loads have been issued)
     QueryRegs<GQ> Q;
-    auto setup_query = [&]() {
     Q.c = a.scale_log2e;
-    Q.one = kOne2;
-    asm volatile("" : "+v"(Q.one));
-    {
-        float qraw[GQ][2];
-        float qmax = 0.0f;
-#pragma unroll
-        for (int j = 0; j < GQ; j++) {
-            uint32_t w = 0;
-            if (j < nvalid) w = *reinterpret_cast<const uint32_t *>(a.q + (qrow0 + j) * kD + 2 * lane);
-            qraw[j][0] = half_lo(w) * Q.c;
-            qraw[j][1] = half_hi(w) * Q.c;
-            qmax = fmaxf(qmax, fmaxf(fabsf(qraw[j][0]), fabsf(qraw[j][1])));
-        }
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, sft));
-        int qexp = 0;
-        if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
-        Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
-#pragma unroll
-        for (int j = 0; j < GQ; j++) {
-            Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
-            Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
-        }
-        // rows 2j and 2j + 1 of the shared exact-fp16 query tile (256 threads x 16 bytes = 16 rows x 256 bytes)
-        const int row = tid >> 4, jr = row >> 1;
-        uint4 x = make_uint4(0, 0, 0, 0);
-        if (jr < nvalid) x = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * (tid & 15));
-        *reinterpret_cast<uint4 *>(&aq_lds[row][8 * (tid & 15)]) = x;
-        Q.Aq = &aq_lds[0][0];
-        Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
-        Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
-    }
-    if constexpr (GQ < 8) {
-        // A-tile rows of heads that do not exist are never written: they must read as zero
-        for (int i = tid; i < 2 * (16 - 2 * GQ) * (kD + 8) / 2; i += 256) {
-            const int pr = i / ((16 - 2 * GQ) * (kD + 8) / 2), w = i % ((16 - 2 * GQ) * (kD + 8) / 2);
-            reinterpret_cast<uint32_t *>(&pairs[pr].Ak[2 * GQ][0])[w] = 0u;
-        }
-        for (int i = tid; i < 2 * 4 * (16 - 2 * GQ) * (32 + 8) / 2; i += 256) {
-            const int per = (16 - 2 * GQ) * (32 + 8) / 2;
-            const int pr = i / (4 * per), gd = (i / per) % 4, w = i % per;
-            reinterpret_cast<uint32_t *>(&pairs[pr].Av[gd][2 * GQ][0])[w] = 0u;
-        }
-    }
-    __syncthreads();
-
-    };
+    Q.Aq = &aq_lds[0][0];
 
     if (key_wave) {
         // =========================================================== key wave
-        CodeRegs<KB> k0, k1;
-        if constexpr (kFast) {
-            if (nit1 > 0) load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(0), lane, k0);
+        // the loads are issued in the order in which their results are needed: queries, then the first blocks
+        uint32_t qw[GQ];
+#pragma unroll
+        for (int j = 0; j < GQ; j++) {
+            qw[j] = 0;
+            if (j < nvalid) qw[j] = *reinterpret_cast<const uint32_t *>(a.q + (qrow0 + j) * kD + 2 * lane);
         }
-        setup_query();
+        CodeRegs<KB> kr[DK];
+        if constexpr (kFast) {
+            if (n1 > 0) {
+#pragma unroll
+                for (int d = 0; d < DK - 1; d++) load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(d), lane, kr[d]);
+            }
+        }
+        {
+            // scaled queries for the q * s operand: divided by a power of two that brings the largest to [0.5, 1)
+            float qraw[GQ][2];
+            float qmax = 0.0f;
+#pragma unroll
+            for (int j = 0; j < GQ; j++) {
+                const uint32_t w = qw[j];
+                qraw[j][0] = half_lo(w) * Q.c;
+                qraw[j][1] = half_hi(w) * Q.c;
+                qmax = fmaxf(qmax, fmaxf(fabsf(qraw[j][0]), fabsf(qraw[j][1])));
+            }
+            // maximum over the wave: 16-lane rows by DPP, the 4 rows as unsigned integers (the values are >= 0)
+            const int qrow = __builtin_bit_cast(int, row_max16(qmax));
+            uint32_t qbits = (uint32_t)__builtin_amdgcn_readlane(qrow, 0);
+#pragma unroll
+            for (int r = 1; r < 4; r++) {
+                const uint32_t o = (uint32_t)__builtin_amdgcn_readlane(qrow, 16 * r);
+                qbits = o > qbits ? o : qbits;
+            }
+            qmax = __builtin_bit_cast(float, qbits);
+            int qexp = 0;
+            if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
+            Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
+#pragma unroll
+            for (int j = 0; j < GQ; j++) {
+                Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
+                Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
+            }
+            if constexpr (GQ < 8) {
+                // A-tile rows of heads that do not exist are never written: they must read as zero
+                for (int i = lane; i < (16 - 2 * GQ) * (kD + 8) / 8; i += 64)
+                    reinterpret_cast<uint4 *>(&L.Ak[2 * GQ][0])[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
+        wg_barrier();                                   // the value wave has written the exact-fp16 query tile
         KeyState<GQ> W;
 #pragma unroll
         for (int i = 0; i < 2; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
         float s[2][2];
         if constexpr (kFast) {
-            if (nit1 > 0) {
-                int i = 0;
-                while (true) {
-                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + 1), lane, k1);
-                    if (i < np) {
-                        scores_packed<KB, GQ>(k0, Q, L, lane, s);
+            // DK register stages in rotation: stage d is consumed while the loads of the next DK - 1 units are in
+            // flight.  Every stage is loaded unconditionally (the index is clamped), so the wait counts stay exact.
+            bool more = n1 > 0;
+            for (int i = 0; more;) {
+#pragma unroll
+                for (int d = 0; d < DK; d++) {
+                    if (more) {
+                        load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + DK - 1), lane, kr[(d + DK - 1) % DK]);
+                        scores_packed<KB, GQ>(kr[d], Q, L, lane, s);
                         softmax_publish<GQ>(s, W, L, i & 1, lane);
+                        wg_barrier();
+                        more = ++i < n1;
                     }
-                    wg_barrier();
-                    if (++i >= nit1) break;
-                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + 1), lane, k0);
-                    if (i < np) {
-                        scores_packed<KB, GQ>(k1, Q, L, lane, s);
-                        softmax_publish<GQ>(s, W, L, i & 1, lane);
-                    }
-                    wg_barrier();
-                    if (++i >= nit1) break;
                 }
             }
         }
-        wg_barrier();                                   // the value waves finish the last unit of phase 1
-        for (int i = 0; i < nit2; i++) {
-            if (i < ng) {
-                const int u = f1c + pair + 2 * i;
-                const bool packed = u < a.n_blocks;
-                const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
-                const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
-                bool k_rows = true;
-                if constexpr (KB < 16) if (packed) {
-                    k_rows = false;
-                    CodeRegs<KB> r;
-                    load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
-                    scores_packed<KB, GQ>(r, Q, L, lane, s);
-                }
-                if (k_rows) {
-                    const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
-                                                   : a.lv.kres + (size_t)bh * a.RC * kD;
-                    const int p0 = pos0 + n, p1 = pos0 + 16 + n;
-                    scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
-                }
-                softmax_publish<GQ>(s, W, L, i & 1, lane);
+        for (int i = 0; i < n2; i++) {
+            const int u = f1c + i;
+            const bool packed = u < a.n_blocks;
+            const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
+            const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
+            bool k_rows = true;
+            if constexpr (KB < 16) if (packed) {
+                k_rows = false;
+                CodeRegs<KB> r;
+                load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
+                scores_packed<KB, GQ>(r, Q, L, lane, s);
             }
+            if (k_rows) {
+                const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
+                                               : a.lv.kres + (size_t)bh * a.RC * kD;
+                const int p0 = pos0 + n, p1 = pos0 + 16 + n;
+                scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
+            }
+            softmax_publish<GQ>(s, W, L, (n1 + i) & 1, lane);
             wg_barrier();
         }
-        wg_barrier();                                   // the value waves finish the last unit of phase 2
-        // ---- results of this pair: reference max and sum per head
+        wg_barrier();                                   // the value wave consumes the last unit
+        // ---- result of the key wave: reference max and sum per head
 #pragma unroll
         for (int hh = 0; hh < 2; hh++) {
             const float lsum = row_sum16(W.l[hh]);
-            if (n == 0 && 2 * rq + hh < GQ) { ml_lds[pair][(2 * rq + hh) % GQ][0] = W.m[hh]; ml_lds[pair][(2 * rq + hh) % GQ][1] = lsum; }
+            const int j = 2 * rq + hh;
+            if (n == 0 && j < nvalid) {
+                const size_t prow = (qrow0 + j) * a.splits + split;
+                *reinterpret_cast<float2 *>(a.part_ml + prow * 2) = make_float2(W.m[hh], lsum);
+            }
         }
     } else {
-        // =========================================================== value wave (one unit behind its key wave)
-        CodeRegs<VB> v0, v1;
-        if constexpr (kFast) {
-            if (nit1 > 0) load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(0), lane, v0);
+        // =========================================================== value wave (one unit behind the key wave)
+        // rows 2j and 2j + 1 of the exact-fp16 query tile (16 rows x 256 bytes); rows of absent heads are zero.
+        // The loads are issued in the order in which their results are needed: queries, then the first blocks.
+        uint4 qx[4];
+#pragma unroll
+        for (int pass = 0; pass < 4; pass++) {
+            const int jr = (4 * pass + rq) >> 1;
+            qx[pass] = make_uint4(0, 0, 0, 0);
+            if (jr < nvalid) qx[pass] = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * n);
         }
-        setup_query();
+        CodeRegs<VB> vr[DV];
+        if constexpr (kFast) {
+            if (n1 > 0) {
+#pragma unroll
+                for (int d = 0; d < DV - 1; d++) load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(d), lane, vr[d]);
+            }
+        }
+#pragma unroll
+        for (int pass = 0; pass < 4; pass++) *reinterpret_cast<uint4 *>(&aq_lds[4 * pass + rq][8 * n]) = qx[pass];
+        if constexpr (GQ < 8) {
+            constexpr int per = (16 - 2 * GQ) * (32 + 8) / 8;        // 16-byte pieces of the unused rows per channel group
+            for (int i = lane; i < 4 * per; i += 64)
+                reinterpret_cast<uint4 *>(&L.Av[i / per][2 * GQ][0])[i % per] = make_uint4(0, 0, 0, 0);
+        }
+        Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
+        Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
+        wg_barrier();                                   // query tile handed to the key wave
         ValueState<GQ> W;
 #pragma unroll
         for (int cblk = 0; cblk < 8; cblk++) W.O[cblk] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int j = 0; j < GQ; j++) { W.oF[j][0] = W.oF[j][1] = 0.0f; W.accz[j] = 0.0f; }
         W.ev = -100;
+        wg_barrier();                                   // the key wave has produced the first unit
         if constexpr (kFast) {
-            if (nit1 > 0) {
-                wg_barrier();                           // the key waves produce the first block
-                int i = 0;
-                while (true) {
-                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + 1), lane, v1);
-                    if (i < np) {
-                        apply_rescale<GQ>(W, L, i & 1, lane);
-                        output_packed<VB, GQ>(v0, Q, W, L, i & 1, lane);
-                    }
-                    wg_barrier();
-                    if (++i >= nit1) break;
-                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + 1), lane, v0);
-                    if (i < np) {
-                        apply_rescale<GQ>(W, L, i & 1, lane);
-                        output_packed<VB, GQ>(v1, Q, W, L, i & 1, lane);
-                    }
-                    wg_barrier();
-                    if (++i >= nit1) break;
-                }
-            } else {
-                wg_barrier();
-            }
-        } else {
-            wg_barrier();
-        }
-        wg_barrier();                                   // the key waves produce the first unit of phase 2
-        for (int i = 0; i < nit2; i++) {
-            if (i < ng) {
-                const int u = f1c + pair + 2 * i;
-                const bool packed = u < a.n_blocks;
-                const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
-                const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
-                apply_rescale<GQ>(W, L, i & 1, lane);
-                bool v_rows = true;
-                if constexpr (VB < 16) if (packed) {
-                    v_rows = false;
-                    CodeRegs<VB> r;
-                    load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
-                    output_packed<VB, GQ>(r, Q, W, L, i & 1, lane);
-                }
-                if (v_rows) {
-                    const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
-                                                   : a.lv.vres + (size_t)bh * a.RC * kD;
-                    output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, i & 1, lane);
-                }
-            }
-            wg_barrier();
-        }
-        // ---- results of this pair: un-normalised output per head and channel
+            bool more = n1 > 0;
+            for (int i = 0; more;) {
 #pragma unroll
-        for (int j = 0; j < GQ; j++) {
-            W.accz[j] = row_sum16(W.accz[j]);
-            if (n == 0) az_lds[pair][j][rq] = W.accz[j];
+                for (int d = 0; d < DV; d++) {
+                    if (more) {
+                        load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + DV - 1), lane, vr[(d + DV - 1) % DV]);
+                        // (always true here; as a run-time test it keeps the rarely taken re-base and rescale
+                        // paths out of line, without it the register count of the loop grows by half)
+                        if (i < n1) {
+                            apply_rescale<GQ>(W, L, i & 1, lane);
+                            output_packed<VB, GQ>(vr[d], Q, W, L, i & 1, lane);
+                        }
+                        wg_barrier();
+                        more = ++i < n1;
+                    }
+                }
+            }
         }
+        for (int i = 0; i < n2; i++) {
+            const int u = f1c + i, buf = (n1 + i) & 1;
+            const bool packed = u < a.n_blocks;
+            const int pos0 = packed ? u * kG : a.n_blocks * kG + (u - a.n_blocks) * 32;
+            const int nt = packed ? 32 : (a.n_res - (u - a.n_blocks) * 32 < 32 ? a.n_res - (u - a.n_blocks) * 32 : 32);
+            apply_rescale<GQ>(W, L, buf, lane);
+            bool v_rows = true;
+            if constexpr (VB < 16) if (packed) {
+                v_rows = false;
+                CodeRegs<VB> r;
+                load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
+                output_packed<VB, GQ>(r, Q, W, L, buf, lane);
+            }
+            if (v_rows) {
+                const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
+                                               : a.lv.vres + (size_t)bh * a.RC * kD;
+                output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, buf, lane);
+            }
+            wg_barrier();
+        }
+        // ---- result of the value wave: un-normalised output per head and channel.  The tile layout (lane =
+        // channel 16 cblk + n, rows of heads 2 rq, 2 rq + 1) is turned into (lane = channels 2 lane, 2 lane + 1,
+        // all heads) through the A-tile memory, which is no longer needed.
+        static_assert(sizeof(L.Av) >= GQ * kD * sizeof(float), "output staging fits the A tiles");
+        float *o_lds = reinterpret_cast<float *>(&L.Av[0][0][0]);
         constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
         const float wO = ldexpf(1.0f, vshift + W.ev - 14);       // high and low parts carry the same weight
+        wave_lds_sync();
 #pragma unroll
         for (int hh = 0; hh < 2; hh++) {
-            if (2 * rq + hh < GQ) {
-                const int j = (2 * rq + hh) % GQ;
+            const int j = 2 * rq + hh;
+            if (j < GQ) {
 #pragma unroll
-                for (int cblk = 0; cblk < 8; cblk++) o_lds[pair][j][16 * cblk + n] = wO * (W.O[cblk][2 * hh] + W.O[cblk][2 * hh + 1]);
+                for (int cblk = 0; cblk < 8; cblk++) o_lds[j * kD + 16 * cblk + n] = wO * (W.O[cblk][2 * hh] + W.O[cblk][2 * hh + 1]);
             }
         }
         wave_lds_sync();
 #pragma unroll
         for (int j = 0; j < GQ; j++) {
-            o_lds[pair][j][2 * lane] += W.oF[j][0];
-            o_lds[pair][j][2 * lane + 1] += W.oF[j][1];
+            // sum_t p_t z_tg of this lane's channel group (lane >> 4), over the 16 lanes that hold its tokens
+            const float az = row_sum16(W.accz[j]);
+            if (j < nvalid) {
+                const float2 t = *reinterpret_cast<const float2 *>(&o_lds[j * kD + 2 * lane]);
+                const size_t prow = (qrow0 + j) * a.splits + split;
+                *reinterpret_cast<float2 *>(a.part_o + prow * kD + 2 * lane) = make_float2(t.x + W.oF[j][0] + az, t.y + W.oF[j][1] + az);
+            }
         }
-    }
-    __syncthreads();
-
-    // ---------------------------------------------------- merge the 2 pairs, write the split's partial
-    for (int i = tid; i < nvalid * kD; i += 256) {
-        const int j = i / kD, d = i % kD;
-        const float m0 = ml_lds[0][j][0], m1 = ml_lds[1][j][0];
-        const float M = fmaxf(m0, m1);
-        const float f0 = m0 == -INFINITY ? 0.0f : exp2f(m0 - M), f1w = m1 == -INFINITY ? 0.0f : exp2f(m1 - M);
-        const float Lsum = ml_lds[0][j][1] * f0 + ml_lds[1][j][1] * f1w;
-        const float Osum = (o_lds[0][j][d] + az_lds[0][j][d >> 5]) * f0 + (o_lds[1][j][d] + az_lds[1][j][d >> 5]) * f1w;
-        const size_t prow = (qrow0 + j) * a.splits + split;
-        a.part_o[prow * kD + d] = Osum;
-        if (d == 0) { a.part_ml[prow * 2] = M; a.part_ml[prow * 2 + 1] = Lsum; }
     }
 }
 
@@ -640,7 +624,7 @@ hipError_t launch_gq(const DecodeArgs &a, hipStream_t s)
 {
     const int gq = a.Hq / a.Hkv;
     const int BH = a.B * a.Hkv;
-    const dim3 block(256);
+    const dim3 block(128);
     if (gq <= 4) {
         hipLaunchKernelGGL((decode_mfma<KB, VB, 4>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else {

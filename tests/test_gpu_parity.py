@@ -184,7 +184,7 @@ def test_decode_loop_with_flushes(kvq_mod, oracle_mod, variant):
                 assert_export_equal(g.debug_export(layer), o.export(layer), "step %d layer %d" % (step, layer))
 
 
-@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 64])
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 64, 128])
 def test_result_does_not_depend_on_splits(kvq_mod, oracle_mod, variant, splits):
     w = W.Workload("splits", 1, 1, 8, 2, 128, 32 * 40 + 45, [4], [4], seed=600, outlier_channels=3)
     g, o = _pair(kvq_mod, oracle_mod, w, 2048)

@@ -82,7 +82,7 @@ def test_configure_and_call_errors_without_gpu(lib):
         assert lib.kvq_layer_tokens(h, 1, ctypes.byref(a), ctypes.byref(b)) == 0 and (a.value, b.value) == (0, 0)
         assert lib.kvq_layer_tokens(h, 5, ctypes.byref(a), ctypes.byref(b)) == -1
         assert lib.kvq_reset(h, -1) == 0 and lib.kvq_reset(h, 2) == -1
-        assert lib.kvq_set_decode_options(h, 3, 0) == -1 and lib.kvq_set_decode_options(h, 1, 65) == -1
+        assert lib.kvq_set_decode_options(h, 3, 0) == -1 and lib.kvq_set_decode_options(h, 1, 129) == -1
         assert lib.kvq_set_decode_options(h, 2, 8) == 0
         assert lib.kvq_debug_export(h, 0, *([None] * 8)) == 0              # empty layer: nothing to do
     finally:
