@@ -27,11 +27,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
-def layer_bytes(w, kb, vb, n_packed, n_res, meta_bytes=4):
+def layer_bytes(w, kb, vb, n_packed, n_res):
     """Algorithmic HBM bytes of one decode_attention launch on one layer."""
     from paper_2502_04420_amd import bytes_per_token
 
-    per_tok = bytes_per_token(kb, vb, w.head_dim, w.group, meta_bytes)
+    per_tok = bytes_per_token(kb, vb, w.head_dim, w.group)
     bh = w.batch * w.n_kv_heads
     return bh * (n_packed * per_tok + n_res * 4 * w.head_dim) + 2 * w.batch * w.n_q_heads * w.head_dim * 2
 

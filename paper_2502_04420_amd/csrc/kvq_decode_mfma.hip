@@ -101,7 +101,8 @@ __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uin
 template <int BITS>
 struct CodeRegs {
     uint32_t dw[BITS < 16 ? 2 * BITS : 1];   // the lane's 64 codes
-    float2 s, z;                             // keys: channels 2*lane, +1; values: group lane>>4, tokens 2*(lane&15), +1
+    float2 s;                                // scales. keys: channels 2*lane, +1; values: group lane>>4, tokens 2*(lane&15), +1
+    uint32_t z;                              // zero-points of the same two elements, fp16 pair
     uint32_t bexp;                           // exponents of the block's largest key scale (low half) / value scale (high half)
 };
 
@@ -117,9 +118,9 @@ __device__ __forceinline__ void load_codes(const uint8_t *code, const float *met
             const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
             r.dw[4 * c] = x.x; r.dw[4 * c + 1] = x.y; r.dw[4 * c + 2] = x.z; r.dw[4 * c + 3] = x.w;
         }
-        const float *m = meta + blk_index * 256;
+        const float *m = meta + blk_index * kMetaWords;
         r.s = *reinterpret_cast<const float2 *>(m + 2 * lane);
-        r.z = *reinterpret_cast<const float2 *>(m + kD + 2 * lane);
+        r.z = *reinterpret_cast<const uint32_t *>(meta_zeros(m) + 2 * lane);
     }
 }
 
@@ -165,7 +166,7 @@ template <int GQ>
 struct __attribute__((aligned(16))) PairLds {
     _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]
     _Float16 Av[4][16][32 + 8];    // value wave: output A tiles [channel group][row][token]
-    _Float16 Zk[kD];               // key wave: key zero-points as fp16 (exact)
+    _Float16 Zk[kD];               // key wave: key zero-points (fp16 as stored)
     float P[2][8][32];             // hand-off: softmax numerators of a block per head, double-buffered
     float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
     int rescale[2][2];             // hand-off: non-zero when alpha is not all ones (padded to 16 bytes)
@@ -211,7 +212,7 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j][2 * lane]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j + 1][2 * lane]) = lo;
     }
-    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(blk.z.x, blk.z.y));
+    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = blk.z;
     wave_lds_sync();
     float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0;
 #pragma unroll
@@ -328,7 +329,7 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
         split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
         *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j][2 * n]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j + 1][2 * n]) = lo;
-        W.accz[j] = fmaf(pp.x, blk.z.x, fmaf(pp.y, blk.z.y, W.accz[j]));
+        W.accz[j] = fmaf(pp.x, half_lo(blk.z), fmaf(pp.y, half_hi(blk.z), W.accz[j]));
     }
     wave_lds_sync();
 #pragma unroll

@@ -22,6 +22,17 @@ __device__ __forceinline__ void wave_lds_sync()
 __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
 
+// a block's metadata (128 fp32 scales, 128 fp16 zero-points) into an LDS tile of 256 floats, one wave
+__device__ __forceinline__ void stage_meta(const float *meta, float *tile, int lane)
+{
+    if (lane < 32) {
+        *reinterpret_cast<float4 *>(&tile[4 * lane]) = *reinterpret_cast<const float4 *>(meta + 4 * lane);
+    } else {
+        const uint2 z = *reinterpret_cast<const uint2 *>(meta_zeros(meta) + 4 * (lane - 32));
+        *reinterpret_cast<float4 *>(&tile[kD + 4 * (lane - 32)]) = make_float4(half_lo(z.x), half_hi(z.x), half_lo(z.y), half_hi(z.y));
+    }
+}
+
 template <int BITS>
 __device__ __forceinline__ float code_as_float(const uint32_t *dw, int ci)
 {
@@ -87,8 +98,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
                 dw[4 * c] = x.x; dw[4 * c + 1] = x.y; dw[4 * c + 2] = x.z; dw[4 * c + 3] = x.w;
             }
-            *reinterpret_cast<float4 *>(&kmeta_lds[wave][4 * lane]) =
-                *reinterpret_cast<const float4 *>(a.lv.kmeta + blk_index * 256 + 4 * lane);
+            stage_meta(a.lv.kmeta + blk_index * kMetaWords, kmeta_lds[wave], lane);
             wave_lds_sync();
 #pragma unroll
             for (int cb = 0; cb < 4; cb++) {
@@ -187,8 +197,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
                 dw[4 * c] = x.x; dw[4 * c + 1] = x.y; dw[4 * c + 2] = x.z; dw[4 * c + 3] = x.w;
             }
-            *reinterpret_cast<float4 *>(&vmeta_lds[wave][4 * lane]) =
-                *reinterpret_cast<const float4 *>(a.lv.vmeta + blk_index * 256 + 4 * lane);
+            stage_meta(a.lv.vmeta + blk_index * kMetaWords, vmeta_lds[wave], lane);
             wave_lds_sync();
             float sv[4][8], zv[4][8];     // [channel group][token 8*kq + e]
 #pragma unroll

@@ -19,7 +19,8 @@
 //   4 bit : dword m, nibble (e>>1) + 4*(e&1)   (nibbles k and k+4 form an fp16 pair)
 //   2 bit : dword m/2, field 4*(m&1) + (e>>1) + 8*(e&1)
 //
-// Metadata of a block: 128 scales then 128 zero-points, fp32.
+// Metadata of a block: 128 fp32 scales, then 128 zero-points as fp16 (768 bytes).  A zero-point
+// is the minimum of a group of fp16 inputs, so it is an fp16 number and the narrow store is exact.
 //   keys  : index = channel              (per channel over the block's 32 tokens)
 //   values: index = 32*(channel/32) + token (per token over 32 channels)
 //
@@ -31,7 +32,8 @@ namespace kvq {
 
 constexpr int kD = 128;       // head dimension
 constexpr int kG = 32;        // group size: tokens per key group, channels per value group
-constexpr int kMetaBytes = 1024;
+constexpr int kMetaBytes = 768;
+constexpr int kMetaWords = kMetaBytes / 4;   // a block's metadata in dwords: scales at [0, 128), zero-points at [128, 192)
 
 __host__ __device__ constexpr int block_code_bytes(int bits) { return bits == 16 ? 32 * kD * 2 : 512 * bits; }
 __host__ __device__ constexpr int block_meta_bytes(int bits) { return bits == 16 ? 0 : kMetaBytes; }
@@ -63,5 +65,9 @@ __host__ __device__ constexpr int key_lane(int t, int d) { return 16 * ((d & 31)
 __host__ __device__ constexpr int key_ci(int t, int d) { return 8 * (4 * (t >> 4) + (d >> 5)) + (d & 7); }
 __host__ __device__ constexpr int val_lane(int t, int d) { return 16 * (t >> 3) + (d & 15); }
 __host__ __device__ constexpr int val_ci(int t, int d) { return 8 * (d >> 4) + (t & 7); }
+
+// zero-points of the metadata block that starts at `meta` (fp16 bit patterns)
+__host__ __device__ inline const uint16_t *meta_zeros(const float *meta) { return reinterpret_cast<const uint16_t *>(meta + kD); }
+__host__ __device__ inline uint16_t *meta_zeros(float *meta) { return reinterpret_cast<uint16_t *>(meta + kD); }
 
 }  // namespace kvq

@@ -17,6 +17,12 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h)
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
 }
 
+// bit pattern of a float that is known to be an fp16 number (a minimum of fp16 inputs): the narrowing is exact
+__device__ __forceinline__ uint16_t float_to_half_bits_exact(float x)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)x);
+}
+
 // fp16 row of the token at absolute position pos: the window ring for tokens that were
 // already held, the caller's tensor for tokens of this append.
 __device__ __forceinline__ const uint16_t *token_row(const uint16_t *in, const uint16_t *ring, int bh, int pos,
@@ -91,14 +97,14 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16));
             mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
         }
-        float *meta = a.lv.kmeta + blk_index * 256;
+        float *meta = a.lv.kmeta + blk_index * kMetaWords;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             const float s = scale_of(mn[e], mx[e], KB);
             ks_max = fmaxf(ks_max, s);
             if (r == 0) {
                 ks[8 * c16 + e] = s; kz[8 * c16 + e] = mn[e];
-                meta[8 * c16 + e] = s; meta[kD + 8 * c16 + e] = mn[e];
+                meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = float_to_half_bits_exact(mn[e]);
             }
         }
 #pragma unroll
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
         for (int i = 0; i < 8; i++)
             *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(vx[i][0], vx[i][1], vx[i][2], vx[i][3]);
     } else {
-        float *meta = a.lv.vmeta + blk_index * 256;
+        float *meta = a.lv.vmeta + blk_index * kMetaWords;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const int t = r + 4 * i;
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             if ((c16 & 3) == 0) {
                 const int gd = c16 >> 2;
                 vs[32 * gd + t] = s; vz[32 * gd + t] = mn;
-                meta[32 * gd + t] = s; meta[kD + 32 * gd + t] = mn;
+                meta[32 * gd + t] = s; meta_zeros(meta)[32 * gd + t] = float_to_half_bits_exact(mn);
             }
         }
     }
@@ -282,12 +288,12 @@ __global__ void export_meta(ExportArgs a, int which)   // 0 = keys, 1 = values
     const int within = (int)(idx % kD);
     const int g = (int)((idx / kD) % (a.n_packed / kG));
     const int bh = (int)(idx / ((long long)kD * (a.n_packed / kG)));
-    const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * 256;
+    const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * kMetaWords;
     float *so = which == 0 ? a.k_scale : a.v_scale, *zo = which == 0 ? a.k_zero : a.v_zero;
     // canonical value metadata is [token][group]; the device keeps [group][token]
     const int src = which == 0 ? within : 32 * (within & 3) + (within >> 2);
     if (so) so[idx] = meta[src];
-    if (zo) zo[idx] = meta[kD + src];
+    if (zo) zo[idx] = half_bits_to_float(meta_zeros(meta)[src]);
 }
 
 // fp16 tensors: rows [bh][token][128]; one thread per 16 bytes.  which: 0/1 = 16-bit keys / values of the

@@ -15,18 +15,21 @@ def equivalent_precision(kbits: Sequence[int], vbits: Sequence[int]) -> float:
     return (sum(kbits) + sum(vbits)) / (2.0 * len(kbits))
 
 
-def bytes_per_token(kbits: int, vbits: int, head_dim: int = 128, group: int = 32, meta_bytes: int = 4) -> int:
+def bytes_per_token(kbits: int, vbits: int, head_dim: int = 128, group: int = 32, scale_bytes: int = 4,
+                    zero_bytes: int = 2) -> int:
     """Bytes one cached token of one kv head occupies once quantized, metadata included.
 
     Codes: head_dim * bits / 8 per tensor.  Metadata: keys carry (s, z) per channel per group of
-    `group` tokens, values (s, z) per token per `group` channels -- 2 * head_dim / group scalars per
-    token for each tensor.  16 bits means fp16 with no metadata.
+    `group` tokens, values (s, z) per token per `group` channels -- head_dim / group pairs per token
+    for each tensor.  The library stores s as fp32 and z as fp16 (z is a minimum of fp16 inputs, so
+    the narrow store is exact); pass zero_bytes=4 for the all-fp32 figure.  16 bits means fp16 with
+    no metadata.
     """
     total = 0
     for bits in (kbits, vbits):
         total += head_dim * bits // 8
         if bits < 16:
-            total += 2 * (head_dim // group) * meta_bytes
+            total += (head_dim // group) * (scale_bytes + zero_bytes)
     return total
 
 

@@ -49,7 +49,7 @@ def test_workspace_bytes_and_config_validation(lib):
     need = lib.kvq_workspace_bytes(ctypes.byref(cfg))
     assert need > 0 and need % 256 == 0
     # codes + metadata of 8 blocks per (b, h) for both layers must fit
-    assert need >= 4 * 8 * ((4096 + 2048 + 2048) + (2048 + 1024 + 2048))
+    assert need >= 4 * 8 * ((4096 + 2048 + 2 * 768) + (2048 + 1024 + 2 * 768))
     for bad in (dict(head_dim=64), dict(group=16), dict(n_q_heads=7), dict(kbits=[8, 3]), dict(vbits=[1, 2]),
                 dict(max_tokens=0), dict(batch=0), dict(residual=-1)):
         c, k = _cfg(**bad)
@@ -115,9 +115,10 @@ def test_equivalent_precision_matches_the_papers_printed_values():
     assert equivalent_precision(*W.llama_mix_325()) == 3.25
     assert equivalent_precision(*W.qwen_mix_40()) == 4.0
     assert equivalent_precision([4], [4]) == 4.0 and 16 / equivalent_precision([4], [2]) == pytest.approx(5.33, abs=0.01)
-    # bytes per token per kv head with fp32 metadata (head_dim 128, group 32)
-    assert [bytes_per_token(k, v) for k, v in ((8, 8), (8, 4), (8, 2), (4, 4), (4, 2), (2, 2), (16, 16))] == \
-        [320, 256, 224, 192, 160, 128, 512]
+    # bytes per token per kv head (head_dim 128, group 32): as stored (fp32 scales, fp16 zero-points), all fp32
+    pairs = ((8, 8), (8, 4), (8, 2), (4, 4), (4, 2), (2, 2), (16, 16))
+    assert [bytes_per_token(k, v) for k, v in pairs] == [304, 240, 208, 176, 144, 112, 512]
+    assert [bytes_per_token(k, v, zero_bytes=4) for k, v in pairs] == [320, 256, 224, 192, 160, 128, 512]
     assert parse_pairs("K8V4, KV4,K4V2") == ([8, 4, 4], [4, 4, 2])
     with pytest.raises(ValueError):
         parse_pairs("K3V4")
