@@ -16,7 +16,8 @@ _lib = None
 
 EXPORTED = [
     "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_layer_tokens",
-    "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_destroy", "kvq_strerror", "kvq_last_error",
+    "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
+    "kvq_last_error",
 ]
 
 
@@ -61,6 +62,8 @@ def load_library():
     lib.kvq_debug_export.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
     lib.kvq_set_decode_options.restype = c_int32
     lib.kvq_set_decode_options.argtypes = [c_void_p, c_int32, c_int32]
+    lib.kvq_set_kernel_events.restype = c_int32
+    lib.kvq_set_kernel_events.argtypes = [c_void_p, c_void_p, c_void_p]
     lib.kvq_destroy.restype = None
     lib.kvq_destroy.argtypes = [c_void_p]
     lib.kvq_strerror.restype = c_char_p
@@ -177,6 +180,10 @@ class KVQ:
 
     def set_decode_options(self, variant: int = 0, splits: int = 0):
         _check(self._lib.kvq_set_decode_options(self._h, variant, splits))
+
+    def set_kernel_events(self, begin_event=None, end_event=None):
+        """Raw hipEvent_t handles (integers or c_void_p) recorded around the main decode kernel; None switches off."""
+        _check(self._lib.kvq_set_kernel_events(self._h, begin_event, end_event))
 
     def debug_export(self, layer: int) -> dict:
         """Canonical dump as device tensors (same keys and shapes as the documented export format)."""

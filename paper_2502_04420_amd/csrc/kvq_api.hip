@@ -84,6 +84,7 @@ struct kvq_ctx {
     hipStream_t stream;
     int variant;                    // 0 auto, 1 vector ALU, 2 matrix core
     int splits;                     // 0 auto
+    hipEvent_t ev_begin, ev_end;    // recorded around the main decode kernel when both are set
 };
 
 namespace {
@@ -148,6 +149,7 @@ int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, 
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->variant = 0;
     c->splits = 0;
+    c->ev_begin = c->ev_end = nullptr;
     *out = c;
     return KVQ_OK;
 }
@@ -235,8 +237,11 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     if (splits < 1) splits = 1;
     a.units_per_split = (units + splits - 1) / splits;
     a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
+    const bool timed = c->ev_begin && c->ev_end;
+    if (timed && hipEventRecord(c->ev_begin, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
     hipError_t e = variant == 2 ? kvq::launch_decode_mfma(a, c->stream) : kvq::launch_decode_valu(a, c->stream);
     if (e != hipSuccess) return launch_failed("decode kernel", e);
+    if (timed && hipEventRecord(c->ev_end, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
     e = kvq::launch_combine(a, c->stream);
     if (e != hipSuccess) return launch_failed("combine kernel", e);
     return KVQ_OK;
@@ -290,6 +295,14 @@ int kvq_set_decode_options(kvq_ctx *c, int32_t variant, int32_t splits)
     if (!c || variant < 0 || variant > 2 || splits < 0 || splits > kMaxSplits) return KVQ_EINVAL;
     c->variant = variant;
     c->splits = splits;
+    return KVQ_OK;
+}
+
+int kvq_set_kernel_events(kvq_ctx *c, void *begin_event, void *end_event)
+{
+    if (!c || (begin_event == nullptr) != (end_event == nullptr)) return KVQ_EINVAL;
+    c->ev_begin = static_cast<hipEvent_t>(begin_event);
+    c->ev_end = static_cast<hipEvent_t>(end_event);
     return KVQ_OK;
 }
 

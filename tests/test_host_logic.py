@@ -83,6 +83,8 @@ def test_configure_and_call_errors_without_gpu(lib):
         assert lib.kvq_layer_tokens(h, 5, ctypes.byref(a), ctypes.byref(b)) == -1
         assert lib.kvq_reset(h, -1) == 0 and lib.kvq_reset(h, 2) == -1
         assert lib.kvq_set_decode_options(h, 3, 0) == -1 and lib.kvq_set_decode_options(h, 1, 129) == -1
+        assert lib.kvq_set_kernel_events(h, ctypes.c_void_p(8), None) == -1     # exactly one event
+        assert lib.kvq_set_kernel_events(h, None, None) == 0
         assert lib.kvq_set_decode_options(h, 2, 8) == 0
         assert lib.kvq_debug_export(h, 0, *([None] * 8)) == 0              # empty layer: nothing to do
     finally:
