@@ -32,13 +32,39 @@ __device__ __forceinline__ const uint16_t *token_row(const uint16_t *in, const u
                        : in + ((size_t)bh * n_in + (pos - t_old)) * kD;
 }
 
+// Eq. 2 for one element, the defining sequence: one IEEE subtraction, one IEEE division, round half to even.
 template <int BITS>
-__device__ __forceinline__ uint32_t encode(float x, float s, float z)
+__device__ __forceinline__ uint32_t encode_exact(float d, float s)
 {
-    float t = s != 0.0f ? __fdiv_rn(x - z, s) : 0.0f;
-    float r = rintf(t);
+    float r = rintf(s != 0.0f ? __fdiv_rn(d, s) : 0.0f);
     r = fminf(fmaxf(r, 0.0f), (float)((1 << BITS) - 1));
     return (uint32_t)r;
+}
+
+// Eight elements at once.  d * (1 / s) with the hardware reciprocal (1 ulp) is within 2 ulp of the correctly
+// rounded quotient, so both round to the same integer unless the product lies within a few ulp of a tie;
+// if that happens for any lane of the wave (rare for real data, always for exact ties) the eight elements
+// are redone with the defining division.  rs is 0 where s is 0, which gives code 0 as required.
+constexpr float kTieMargin = 9.5367431640625e-07f;     // 2^-20 relative = 8 ulp
+
+template <int BITS>
+__device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s8)[8], const float (&z8)[8], const float (&r8)[8],
+                                        uint32_t (&c8)[8])
+{
+    float d[8];
+    bool unsure = false;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
+        const float t = d[e] * r8[e];
+        const float r = rintf(t);
+        unsure |= fabsf(fabsf(t - r) - 0.5f) <= t * kTieMargin;
+        c8[e] = (uint32_t)fminf(fmaxf(r, 0.0f), (float)((1 << BITS) - 1));
+    }
+    if (__any(unsure)) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) c8[e] = encode_exact<BITS>(d[e], s8[e]);
+    }
 }
 
 __device__ __forceinline__ float scale_of(float mn, float mx, int bits)
@@ -46,163 +72,180 @@ __device__ __forceinline__ float scale_of(float mn, float mx, int bits)
     return __fdiv_rn(mx - mn, (float)((1 << bits) - 1));
 }
 
-// One wave per (block of 32 tokens, (b, h)).  Lane = 16*r + c16 loads 8 channels
-// (8*c16 ..) of tokens r, r+4, .., r+28 for both tensors.
+__device__ __forceinline__ float recip_or_zero(float s) { return s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f; }
+
+__device__ __forceinline__ void load8(const float *p, float (&v)[8])
+{
+    *reinterpret_cast<float4 *>(&v[0]) = *reinterpret_cast<const float4 *>(p);
+    *reinterpret_cast<float4 *>(&v[4]) = *reinterpret_cast<const float4 *>(p + 4);
+}
+
+// 16-bit half of the block-exponent word: exponent e of max = f * 2^e, f in [0.5, 1), biased by 32768
+// (32768 itself for an all-constant block or an fp16 tensor)
+__device__ __forceinline__ uint16_t biased_exponent(float wave_max)
+{
+    int e = 0;
+    if (wave_max > 0.0f) (void)frexpf(wave_max, &e);
+    return (uint16_t)(e + 32768);
+}
+
+__device__ __forceinline__ float wave_max64(float x)
+{
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) x = fmaxf(x, __shfl_xor(x, sft));
+    return x;
+}
+
+// One wave per (tensor, block of 32 tokens, (b, h)); blockIdx.y = 0 keys, 1 values.  Lane = 16*r + c16
+// loads 8 channels (8*c16 ..) of tokens r, r+4, .., r+28; the statistics are taken in that arrangement,
+// the tile goes through LDS, and each lane encodes exactly the 64 codes it stores.
 template <int KB, int VB>
 __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
 {
     const int lane = threadIdx.x;
     const int bh = blockIdx.x / a.n_blocks;
     const int blk = a.first_block + blockIdx.x % a.n_blocks;
+    const bool values = blockIdx.y != 0;
     const int r = lane >> 4, c16 = lane & 15;
     const int n = lane & 15, kq = lane >> 4;
 
-    __shared__ __attribute__((aligned(16))) uint16_t tk[32][kD + 8];     // keys [token][channel]
-    __shared__ __attribute__((aligned(16))) uint16_t tvT[kD][32 + 8];    // values [channel][token]
-    __shared__ __attribute__((aligned(16))) float ks[kD], kz[kD], vs[kD], vz[kD];
+    // keys [token][channel] with rows of kD + 8 halves, or values [channel][token] with rows of 32 + 8 halves
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kD * (32 + 8)];
+    __shared__ __attribute__((aligned(16))) float sc[kD], zp[kD], rsc[kD];    // scale, zero-point, 1 / scale
+    static_assert(kD * (32 + 8) >= 32 * (kD + 8), "one buffer serves both arrangements");
 
-    uint32_t kx[8][4], vx[8][4];
+    const uint16_t *in = values ? a.v_in : a.k_in, *ring = values ? a.lv.vres : a.lv.kres;
+    uint32_t x[8][4];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         const int pos = blk * kG + r + 4 * i;
-        const uint4 kk = *reinterpret_cast<const uint4 *>(token_row(a.k_in, a.lv.kres, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
-        const uint4 vv = *reinterpret_cast<const uint4 *>(token_row(a.v_in, a.lv.vres, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
-        kx[i][0] = kk.x; kx[i][1] = kk.y; kx[i][2] = kk.z; kx[i][3] = kk.w;
-        vx[i][0] = vv.x; vx[i][1] = vv.y; vx[i][2] = vv.z; vx[i][3] = vv.w;
+        const uint4 w = *reinterpret_cast<const uint4 *>(token_row(in, ring, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
+        x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
     }
     const size_t blk_index = (size_t)bh * a.NB + blk;
-    float ks_max = 0.0f, vs_max = 0.0f;     // largest scale of the block, for the matrix-core kernel's operand scaling
+    uint16_t *bexp16 = reinterpret_cast<uint16_t *>(a.lv.bexp + blk_index);    // [0] keys, [1] values
 
-    // ---- keys
-    if constexpr (KB == 16) {
-        uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(16);
+    if (!values) {
+        // ================================================================= keys
+        if constexpr (KB == 16) {
+            uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(16);
 #pragma unroll
-        for (int i = 0; i < 8; i++)
-            *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(kx[i][0], kx[i][1], kx[i][2], kx[i][3]);
+            for (int i = 0; i < 8; i++)
+                *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            if (lane == 0) bexp16[0] = 32768;
+        } else {
+            // min / max per channel over the lane's 8 tokens, then across the 4 lane rows by shuffles
+            float mn[8], mx[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const float v = half_bits_to_float((x[i][e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                    mn[e] = fminf(mn[e], v);
+                    mx[e] = fmaxf(mx[e], v);
+                }
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16));
+                mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
+            }
+            float *meta = a.lv.kmeta + blk_index * kMetaWords;
+            float s_max = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const float s = scale_of(mn[e], mx[e], KB);
+                s_max = fmaxf(s_max, s);
+                if (r == 0) {
+                    sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn[e]; rsc[8 * c16 + e] = recip_or_zero(s);
+                    meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = float_to_half_bits_exact(mn[e]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+                *reinterpret_cast<uint4 *>(&tile[(r + 4 * i) * (kD + 8) + 8 * c16]) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            s_max = wave_max64(s_max);
+            if (lane == 0) bexp16[0] = biased_exponent(s_max);
+            __syncthreads();
+            // codes in the lane layout of kvq_layout.h
+            uint32_t dw[2 * KB];
+#pragma unroll
+            for (int i = 0; i < 2 * KB; i++) dw[i] = 0;
+#pragma unroll
+            for (int m = 0; m < 8; m++) {
+                const int token = 16 * (m >> 2) + n, ch0 = 32 * (m & 3) + 8 * kq;
+                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[token * (kD + 8) + ch0]);
+                const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
+                float s8[8], z8[8], r8[8];
+                load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
+                uint32_t c8[8];
+                encode8<KB>(xw, s8, z8, r8, c8);
+#pragma unroll
+                for (int e = 0; e < 8; e++) dw[code_dword<KB>(8 * m + e)] |= c8[e] << code_shift<KB>(8 * m + e);
+            }
+            uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
+#pragma unroll
+            for (int c = 0; c < KB / 2; c++)
+                *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
+        }
     } else {
-        // min / max per channel over the lane's 8 tokens, then across the 4 lane rows by shuffles
-        float mn[8], mx[8];
+        // ================================================================= values
+        if constexpr (VB == 16) {
+            uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(16);
 #pragma unroll
-        for (int e = 0; e < 8; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+            for (int i = 0; i < 8; i++)
+                *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
+            if (lane == 0) bexp16[1] = 32768;
+        } else {
+            float *meta = a.lv.vmeta + blk_index * kMetaWords;
+            float s_max = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; i++)
+            for (int i = 0; i < 8; i++) {
+                const int t = r + 4 * i;
+                float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const float x = half_bits_to_float((kx[i][e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                mn[e] = fminf(mn[e], x);
-                mx[e] = fmaxf(mx[e], x);
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t hb = (x[i][e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                    const float v = half_bits_to_float(hb);
+                    mn = fminf(mn, v);
+                    mx = fmaxf(mx, v);
+                    tile[(8 * c16 + e) * (32 + 8) + t] = (uint16_t)hb;
+                }
+                // the 4 lanes c16 = 4*gd .. 4*gd+3 hold the 32 channels of group gd
+                mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
+                mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
+                const float s = scale_of(mn, mx, VB);
+                s_max = fmaxf(s_max, s);
+                if ((c16 & 3) == 0) {
+                    const int gd = c16 >> 2;
+                    sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
+                    meta[32 * gd + t] = s; meta_zeros(meta)[32 * gd + t] = float_to_half_bits_exact(mn);
+                }
             }
+            s_max = wave_max64(s_max);
+            if (lane == 0) bexp16[1] = biased_exponent(s_max);
+            __syncthreads();
+            uint32_t dw[2 * VB];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16));
-            mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
-        }
-        float *meta = a.lv.kmeta + blk_index * kMetaWords;
+            for (int i = 0; i < 2 * VB; i++) dw[i] = 0;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const float s = scale_of(mn[e], mx[e], KB);
-            ks_max = fmaxf(ks_max, s);
-            if (r == 0) {
-                ks[8 * c16 + e] = s; kz[8 * c16 + e] = mn[e];
-                meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = float_to_half_bits_exact(mn[e]);
+            for (int m = 0; m < 8; m++) {
+                const int ch = 16 * m + n, gd = m >> 1;
+                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[ch * (32 + 8) + 8 * kq]);
+                const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
+                float s8[8], z8[8], r8[8];
+                load8(&sc[32 * gd + 8 * kq], s8); load8(&zp[32 * gd + 8 * kq], z8); load8(&rsc[32 * gd + 8 * kq], r8);
+                uint32_t c8[8];
+                encode8<VB>(xw, s8, z8, r8, c8);
+#pragma unroll
+                for (int e = 0; e < 8; e++) dw[code_dword<VB>(8 * m + e)] |= c8[e] << code_shift<VB>(8 * m + e);
             }
+            uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
+#pragma unroll
+            for (int c = 0; c < VB / 2; c++)
+                *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
         }
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-            *reinterpret_cast<uint4 *>(&tk[r + 4 * i][8 * c16]) = make_uint4(kx[i][0], kx[i][1], kx[i][2], kx[i][3]);
-    }
-
-    // ---- values
-    if constexpr (VB == 16) {
-        uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(16);
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-            *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(vx[i][0], vx[i][1], vx[i][2], vx[i][3]);
-    } else {
-        float *meta = a.lv.vmeta + blk_index * kMetaWords;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-            const int t = r + 4 * i;
-            float mn = INFINITY, mx = -INFINITY;
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const uint32_t hb = (vx[i][e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                const float x = half_bits_to_float(hb);
-                mn = fminf(mn, x);
-                mx = fmaxf(mx, x);
-                tvT[8 * c16 + e][t] = (uint16_t)hb;
-            }
-            // the 4 lanes c16 = 4*gd .. 4*gd+3 hold the 32 channels of group gd
-            mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
-            mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
-            const float s = scale_of(mn, mx, VB);
-            vs_max = fmaxf(vs_max, s);
-            if ((c16 & 3) == 0) {
-                const int gd = c16 >> 2;
-                vs[32 * gd + t] = s; vz[32 * gd + t] = mn;
-                meta[32 * gd + t] = s; meta_zeros(meta)[32 * gd + t] = float_to_half_bits_exact(mn);
-            }
-        }
-    }
-    if constexpr (KB < 16 || VB < 16) {
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) {
-            ks_max = fmaxf(ks_max, __shfl_xor(ks_max, sft));
-            vs_max = fmaxf(vs_max, __shfl_xor(vs_max, sft));
-        }
-        if (lane == 0) {
-            int ek = 0, ev = 0;                       // max = f * 2^e with f in [0.5, 1); 0 for an all-constant block
-            if (ks_max > 0.0f) (void)frexpf(ks_max, &ek);
-            if (vs_max > 0.0f) (void)frexpf(vs_max, &ev);
-            a.lv.bexp[blk_index] = ((uint32_t)(ek + 32768) & 0xffffu) | ((uint32_t)(ev + 32768) << 16);
-        }
-    }
-    __syncthreads();
-
-    // ---- key codes in the lane layout of kvq_layout.h
-    if constexpr (KB < 16) {
-        uint32_t dw[2 * KB];
-#pragma unroll
-        for (int i = 0; i < 2 * KB; i++) dw[i] = 0;
-#pragma unroll
-        for (int m = 0; m < 8; m++) {
-            const int token = 16 * (m >> 2) + n, ch0 = 32 * (m & 3) + 8 * kq;
-            const uint4 xx = *reinterpret_cast<const uint4 *>(&tk[token][ch0]);
-            const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const float x = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                const uint32_t c = encode<KB>(x, ks[ch0 + e], kz[ch0 + e]);
-                dw[code_dword<KB>(8 * m + e)] |= c << code_shift<KB>(8 * m + e);
-            }
-        }
-        uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
-#pragma unroll
-        for (int c = 0; c < KB / 2; c++)
-            *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
-    }
-    // ---- value codes
-    if constexpr (VB < 16) {
-        uint32_t dw[2 * VB];
-#pragma unroll
-        for (int i = 0; i < 2 * VB; i++) dw[i] = 0;
-#pragma unroll
-        for (int m = 0; m < 8; m++) {
-            const int ch = 16 * m + n, gd = m >> 1;
-            const uint4 xx = *reinterpret_cast<const uint4 *>(&tvT[ch][8 * kq]);
-            const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const int t = 8 * kq + e;
-                const float x = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                const uint32_t c = encode<VB>(x, vs[32 * gd + t], vz[32 * gd + t]);
-                dw[code_dword<VB>(8 * m + e)] |= c << code_shift<VB>(8 * m + e);
-            }
-        }
-        uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
-#pragma unroll
-        for (int c = 0; c < VB / 2; c++)
-            *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
     }
 }
 
@@ -324,7 +367,7 @@ __global__ void export_rows(ExportArgs a, int which)
 template <int KB>
 hipError_t launch_quantize_vb(const QuantArgs &a, hipStream_t s)
 {
-    const dim3 grid((unsigned)a.n_blocks * (unsigned)a.BH), block(64);
+    const dim3 grid((unsigned)a.n_blocks * (unsigned)a.BH, 2), block(64);
     switch (a.lv.vbits) {
     case 2: hipLaunchKernelGGL((quantize_blocks<KB, 2>), grid, block, 0, s, a); break;
     case 4: hipLaunchKernelGGL((quantize_blocks<KB, 4>), grid, block, 0, s, a); break;
