@@ -32,38 +32,81 @@ __device__ __forceinline__ const uint16_t *token_row(const uint16_t *in, const u
                        : in + ((size_t)bh * n_in + (pos - t_old)) * kD;
 }
 
-// Eq. 2 for one element, the defining sequence: one IEEE subtraction, one IEEE division, round half to even.
-template <int BITS>
-__device__ __forceinline__ uint32_t encode_exact(float d, float s)
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+// element-wise minimum / maximum of two fp16 pairs (exact; the statistics need no widening).  Written as
+// single instructions: the generic vector builtins add a quieting pass over every loaded operand.
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 {
-    float r = rintf(s != 0.0f ? __fdiv_rn(d, s) : 0.0f);
-    r = fminf(fmaxf(r, 0.0f), (float)((1 << BITS) - 1));
-    return (uint32_t)r;
+    uint32_t d;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
 }
 
-// Eight elements at once.  d * (1 / s) with the hardware reciprocal (1 ulp) is within 2 ulp of the correctly
-// rounded quotient, so both round to the same integer unless the product lies within a few ulp of a tie;
-// if that happens for any lane of the wave (rare for real data, always for exact ties) the eight elements
-// are redone with the defining division.  rs is 0 where s is 0, which gives code 0 as required.
-constexpr float kTieMargin = 9.5367431640625e-07f;     // 2^-20 relative = 8 ulp
+// Eq. 2 for one element, the defining sequence: (one IEEE subtraction, done by the caller,) one IEEE
+// division, round half to even, clamp.  Returns the code as a float.
+template <int BITS>
+__device__ __forceinline__ float round_exact(float d, float s)
+{
+    const float r = rintf(s != 0.0f ? __fdiv_rn(d, s) : 0.0f);
+    return fminf(fmaxf(r, 0.0f), (float)((1 << BITS) - 1));
+}
 
+// Eight elements at once, codes returned as floats.  d * (1 / s) with the hardware reciprocal (1 ulp) differs
+// from the correctly rounded quotient by less than 2^-22 of its value, so both round to the same integer
+// unless the product lies that close to a tie; the test below uses twice that distance.  If it fires for any
+// lane of the wave (rare for real data, always for exact ties) the eight elements are redone with the
+// defining division.  d >= 0 and rs >= 0 (rs is 0 where s is 0, giving code 0), so the fast result needs no clamp:
+// d / s <= (2^B - 1)(1 + 2^-23).
 template <int BITS>
 __device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s8)[8], const float (&z8)[8], const float (&r8)[8],
-                                        uint32_t (&c8)[8])
+                                        float (&c8)[8])
 {
-    float d[8];
-    bool unsure = false;
+    float d[8], u[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) {
         d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
         const float t = d[e] * r8[e];
-        const float r = rintf(t);
-        unsure |= fabsf(fabsf(t - r) - 0.5f) <= t * kTieMargin;
-        c8[e] = (uint32_t)fminf(fmaxf(r, 0.0f), (float)((1 << BITS) - 1));
+        c8[e] = rintf(t);
+        u[e] = fmaf(t, 4.76837158203125e-07f, -fabsf(__builtin_amdgcn_fractf(t) - 0.5f));    // 2^-21 t - |frac(t) - 1/2|
     }
-    if (__any(unsure)) {
+    // some element is within its margin of a tie <=> the largest u is >= 0
+    const float worst = fmaxf(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])), fmaxf(fmaxf(u[4], u[5]), fmaxf(u[6], u[7])));
+    if (__any(worst >= 0.0f)) {
 #pragma unroll
-        for (int e = 0; e < 8; e++) c8[e] = encode_exact<BITS>(d[e], s8[e]);
+        for (int e = 0; e < 8; e++) c8[e] = round_exact<BITS>(d[e], s8[e]);
+    }
+}
+
+// The lane's codes 8*m .. 8*m + 7 (as floats) into their dwords.  The fields of a dword are assembled in
+// floating point while the partial words stay below 2^24 (exact), then converted once.
+template <int BITS>
+__device__ __forceinline__ void pack8(const float (&c)[8], int m, uint32_t *dw)
+{
+    if constexpr (BITS == 8) {
+        // code e in byte e % 4 of dword 2*m + e / 4
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const float w = fmaf(c[4 * h + 2], 65536.0f, fmaf(c[4 * h + 1], 256.0f, c[4 * h]));
+            dw[2 * m + h] = (uint32_t)w | ((uint32_t)c[4 * h + 3] << 24);
+        }
+    } else if constexpr (BITS == 4) {
+        // nibble (e >> 1) + 4 * (e & 1) of dword m
+        const float lo = fmaf(c[6], 4096.0f, fmaf(c[4], 256.0f, fmaf(c[2], 16.0f, c[0])));
+        const float hi = fmaf(c[7], 4096.0f, fmaf(c[5], 256.0f, fmaf(c[3], 16.0f, c[1])));
+        dw[m] = (uint32_t)lo | ((uint32_t)hi << 16);
+    } else {
+        // field 4 * (m & 1) + (e >> 1) + 8 * (e & 1) of dword m / 2
+        const float lo = fmaf(c[6], 64.0f, fmaf(c[4], 16.0f, fmaf(c[2], 4.0f, c[0])));
+        const float hi = fmaf(c[7], 64.0f, fmaf(c[5], 16.0f, fmaf(c[3], 4.0f, c[1])));
+        const uint32_t w = (uint32_t)fmaf(hi, 65536.0f, lo);
+        if (m & 1) dw[m >> 1] |= w << 8; else dw[m >> 1] = w;
     }
 }
 
@@ -96,9 +139,15 @@ __device__ __forceinline__ float wave_max64(float x)
     return x;
 }
 
-// One wave per (tensor, block of 32 tokens, (b, h)); blockIdx.y = 0 keys, 1 values.  Lane = 16*r + c16
-// loads 8 channels (8*c16 ..) of tokens r, r+4, .., r+28; the statistics are taken in that arrangement,
-// the tile goes through LDS, and each lane encodes exactly the 64 codes it stores.
+// Row of channel ch in the transposed value tile.  Rows are 80 bytes (32 tokens + 16 bytes of padding); the
+// low four bits of the row number are mixed with bits 3..6 of the channel so that both the 16 lanes that
+// write one token chunk (channels 8*c16 + e) and the 16 lanes that read one (channels 16*m + n) fall on
+// 16 different 16-byte bank groups.
+__device__ __forceinline__ int value_row(int ch) { return (ch & 0x70) | ((ch ^ (ch >> 3)) & 15); }
+
+// One wave per (tensor, block of 32 tokens, (b, h)); blockIdx.y = 0 keys, 1 values.  The statistics are
+// taken in the arrangement the rows are loaded in (16 bytes = 8 channels of a token per lane), the tile
+// goes through LDS, and each lane encodes exactly the 64 codes it stores.
 template <int KB, int VB>
 __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
 {
@@ -109,16 +158,17 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
     const int r = lane >> 4, c16 = lane & 15;
     const int n = lane & 15, kq = lane >> 4;
 
-    // keys [token][channel] with rows of kD + 8 halves, or values [channel][token] with rows of 32 + 8 halves
+    // keys [token][channel] with rows of kD + 8 halves, or values [row of channel][token] with rows of 32 + 8 halves
     __shared__ __attribute__((aligned(16))) uint16_t tile[kD * (32 + 8)];
     __shared__ __attribute__((aligned(16))) float sc[kD], zp[kD], rsc[kD];    // scale, zero-point, 1 / scale
     static_assert(kD * (32 + 8) >= 32 * (kD + 8), "one buffer serves both arrangements");
 
+    // keys: lane = 16*r + c16 holds tokens r, r+4, .., r+28; values: tokens 8*r .. 8*r+7 (8 channels 8*c16.. each)
     const uint16_t *in = values ? a.v_in : a.k_in, *ring = values ? a.lv.vres : a.lv.kres;
     uint32_t x[8][4];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
-        const int pos = blk * kG + r + 4 * i;
+        const int pos = blk * kG + (values ? 8 * r + i : r + 4 * i);
         const uint4 w = *reinterpret_cast<const uint4 *>(token_row(in, ring, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
         x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
     }
@@ -135,31 +185,29 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             if (lane == 0) bexp16[0] = 32768;
         } else {
             // min / max per channel over the lane's 8 tokens, then across the 4 lane rows by shuffles
-            float mn[8], mx[8];
+            uint32_t mnp[4], mxp[4];
 #pragma unroll
-            for (int e = 0; e < 8; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+            for (int p = 0; p < 4; p++) { mnp[p] = x[0][p]; mxp[p] = x[0][p]; }
 #pragma unroll
-            for (int i = 0; i < 8; i++)
+            for (int i = 1; i < 8; i++)
 #pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    const float v = half_bits_to_float((x[i][e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                    mn[e] = fminf(mn[e], v);
-                    mx[e] = fmaxf(mx[e], v);
-                }
+                for (int p = 0; p < 4; p++) { mnp[p] = pk_min(mnp[p], x[i][p]); mxp[p] = pk_max(mxp[p], x[i][p]); }
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16));
-                mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
+            for (int p = 0; p < 4; p++) {
+                mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
+                mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
             }
             float *meta = a.lv.kmeta + blk_index * kMetaWords;
             float s_max = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                const float s = scale_of(mn[e], mx[e], KB);
+                const uint32_t mnb = (mnp[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mxp[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                const float s = scale_of(mn, mx, KB);
                 s_max = fmaxf(s_max, s);
                 if (r == 0) {
-                    sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn[e]; rsc[8 * c16 + e] = recip_or_zero(s);
-                    meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = float_to_half_bits_exact(mn[e]);
+                    sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn; rsc[8 * c16 + e] = recip_or_zero(s);
+                    meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = (uint16_t)mnb;
                 }
             }
 #pragma unroll
@@ -171,18 +219,14 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             // codes in the lane layout of kvq_layout.h
             uint32_t dw[2 * KB];
 #pragma unroll
-            for (int i = 0; i < 2 * KB; i++) dw[i] = 0;
-#pragma unroll
             for (int m = 0; m < 8; m++) {
                 const int token = 16 * (m >> 2) + n, ch0 = 32 * (m & 3) + 8 * kq;
                 const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[token * (kD + 8) + ch0]);
                 const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-                float s8[8], z8[8], r8[8];
+                float s8[8], z8[8], r8[8], c8[8];
                 load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
-                uint32_t c8[8];
                 encode8<KB>(xw, s8, z8, r8, c8);
-#pragma unroll
-                for (int e = 0; e < 8; e++) dw[code_dword<KB>(8 * m + e)] |= c8[e] << code_shift<KB>(8 * m + e);
+                pack8<KB>(c8, m, dw);
             }
             uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
 #pragma unroll
@@ -195,26 +239,21 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(16);
 #pragma unroll
             for (int i = 0; i < 8; i++)
-                *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
+                *reinterpret_cast<uint4 *>(dst + (8 * r + i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
             if (lane == 0) bexp16[1] = 32768;
         } else {
             float *meta = a.lv.vmeta + blk_index * kMetaWords;
             float s_max = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-                const int t = r + 4 * i;
-                float mn = INFINITY, mx = -INFINITY;
-#pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    const uint32_t hb = (x[i][e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                    const float v = half_bits_to_float(hb);
-                    mn = fminf(mn, v);
-                    mx = fmaxf(mx, v);
-                    tile[(8 * c16 + e) * (32 + 8) + t] = (uint16_t)hb;
-                }
-                // the 4 lanes c16 = 4*gd .. 4*gd+3 hold the 32 channels of group gd
-                mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
-                mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
+                const int t = 8 * r + i;
+                // min / max over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd
+                uint32_t mnp = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
+                uint32_t mxp = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
+                mnp = pk_min(mnp, __shfl_xor(mnp, 1)); mxp = pk_max(mxp, __shfl_xor(mxp, 1));
+                mnp = pk_min(mnp, __shfl_xor(mnp, 2)); mxp = pk_max(mxp, __shfl_xor(mxp, 2));
+                const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
+                const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
                 const float s = scale_of(mn, mx, VB);
                 s_max = fmaxf(s_max, s);
                 if ((c16 & 3) == 0) {
@@ -223,23 +262,30 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     meta[32 * gd + t] = s; meta_zeros(meta)[32 * gd + t] = float_to_half_bits_exact(mn);
                 }
             }
+            // 8 x 8 transpose in registers: channel 8*c16 + e gets its 8 tokens as one 16-byte chunk
+            const int krow = (c16 & 7) | (((c16 ^ (c16 >> 3)) & 1) << 3);      // value_row(8*c16 + e) = (c16 >> 1) << 4 | (krow ^ e)
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                const uint4 w = make_uint4(__builtin_amdgcn_perm(x[1][e >> 1], x[0][e >> 1], sel), __builtin_amdgcn_perm(x[3][e >> 1], x[2][e >> 1], sel),
+                                           __builtin_amdgcn_perm(x[5][e >> 1], x[4][e >> 1], sel), __builtin_amdgcn_perm(x[7][e >> 1], x[6][e >> 1], sel));
+                const int row = ((c16 >> 1) << 4) | (krow ^ e);
+                *reinterpret_cast<uint4 *>(&tile[row * (32 + 8) + 8 * r]) = w;
+            }
             s_max = wave_max64(s_max);
             if (lane == 0) bexp16[1] = biased_exponent(s_max);
             __syncthreads();
             uint32_t dw[2 * VB];
-#pragma unroll
-            for (int i = 0; i < 2 * VB; i++) dw[i] = 0;
+            const int nrow = (n ^ (n >> 3)) & 15;                               // value_row(16*m + n) = m << 4 | (nrow ^ 2*m)
 #pragma unroll
             for (int m = 0; m < 8; m++) {
-                const int ch = 16 * m + n, gd = m >> 1;
-                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[ch * (32 + 8) + 8 * kq]);
+                const int gd = m >> 1, row = (m << 4) | (nrow ^ ((2 * m) & 15));
+                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[row * (32 + 8) + 8 * kq]);
                 const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-                float s8[8], z8[8], r8[8];
+                float s8[8], z8[8], r8[8], c8[8];
                 load8(&sc[32 * gd + 8 * kq], s8); load8(&zp[32 * gd + 8 * kq], z8); load8(&rsc[32 * gd + 8 * kq], r8);
-                uint32_t c8[8];
                 encode8<VB>(xw, s8, z8, r8, c8);
-#pragma unroll
-                for (int e = 0; e < 8; e++) dw[code_dword<VB>(8 * m + e)] |= c8[e] << code_shift<VB>(8 * m + e);
+                pack8<VB>(c8, m, dw);
             }
             uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
 #pragma unroll

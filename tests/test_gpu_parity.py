@@ -233,6 +233,39 @@ def test_tie_heavy_keys_are_coded_identically(kvq_mod, oracle_mod):
         assert_export_equal(g.debug_export(0), o.export(0), "ties K%dV%d" % (kb, vb))
 
 
+def test_quotients_next_to_ties_are_coded_identically(kvq_mod, oracle_mod):
+    """Adversarial groups for the encoder: inputs whose quotient (x - z) / s lies within a few fp32 ulp of k + 1/2
+    without being a tie, found by search over fp16 values.  A rounding shortcut that is not exact fails here."""
+    rng = np.random.default_rng(11)
+    B, H, T, D = 1, 1, 64, 128
+    for bits in (8, 4, 2):
+        levels = (1 << bits) - 1
+        K = np.zeros((B, H, T, D), dtype=np.float16)
+        found = 0
+        for d in range(D):
+            # a channel = two key groups (tokens 0..31, 32..63) sharing min 0 and max R
+            R = np.float16(rng.uniform(0.5, 60.0))
+            s32 = np.float32(R) / np.float32(levels)
+            xs = np.arange(1, int(np.float16(R).view(np.uint16)), dtype=np.uint16).view(np.float16)   # all fp16 in (0, R)
+            q = xs.astype(np.float64) / np.float64(s32)
+            dist = np.abs(q - np.floor(q) - 0.5)
+            near = xs[(dist < 3e-5 * np.maximum(q, 1.0)) & (dist > 0)]
+            if len(near) == 0:
+                near = xs[np.argsort(dist)[:30]]
+            found += len(near)
+            col = rng.choice(near, size=T)
+            col[0] = col[32] = 0.0
+            col[1] = col[33] = R
+            K[0, 0, :, d] = col
+        assert found >= D
+        V = K.copy()          # value groups (32 channels of a token) see the same numbers grouped differently
+        w = W.Workload("near-ties", 1, B, 4, H, D, T, [bits], [bits], seed=1)
+        g, o = _pair(kvq_mod, oracle_mod, w, 128, residual=0)
+        g.quantize_append(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+        o.quantize_append(0, K, V)
+        assert_export_equal(g.debug_export(0), o.export(0), "near ties %d bit" % bits)
+
+
 def test_sixteen_bit_mode_equals_exact_attention(kvq_mod, oracle_mod, variant):
     w = W.Workload("fp16", 1, 2, 8, 2, 128, 300, [16], [16], seed=700)
     g, _ = _pair(kvq_mod, oracle_mod, w, 512, variant=variant)
