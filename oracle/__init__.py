@@ -51,6 +51,10 @@ def _load():
     lib.kvo_double_to_half.argtypes = [c_double]
     lib.kvo_quantize_group.restype = None
     lib.kvo_quantize_group.argtypes = [f32p, c_int, c_int, f32p, f32p, u8p]
+    lib.kvo_quantize_group_ex.restype = None
+    lib.kvo_quantize_group_ex.argtypes = [f32p, c_int, c_int, c_int, f32p, f32p, u8p]
+    lib.kvo_set_scale_fp16.restype = c_int
+    lib.kvo_set_scale_fp16.argtypes = [c_void_p, c_int]
     lib.kvo_create.restype = c_void_p
     lib.kvo_create.argtypes = [c_int] * 7 + [u8p, u8p]
     lib.kvo_destroy.restype = None
@@ -99,13 +103,19 @@ def double_to_half_bits(x: float) -> int:
     return int(_load().kvo_double_to_half(float(x)))
 
 
-def quantize_group(x, bits: int):
-    """Eq. 2 on one group.  x: 1-D float32.  Returns (scale, zero, codes[uint8])."""
+def quantize_group(x, bits: int, scale_fp16: bool = False):
+    """Eq. 2 on one group.  x: 1-D float32.  Returns (scale, zero, codes[uint8]).
+
+    scale_fp16: the narrow-metadata variant (scale rounded once to fp16 and used that way)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     s, z = c_float(), c_float()
     codes = np.zeros(x.size, dtype=np.uint8)
-    _load().kvo_quantize_group(_ptr(x, c_float), x.size, bits, ctypes.byref(s), ctypes.byref(z),
-                               _ptr(codes, c_uint8))
+    if scale_fp16:
+        _load().kvo_quantize_group_ex(_ptr(x, c_float), x.size, bits, 1, ctypes.byref(s), ctypes.byref(z),
+                                      _ptr(codes, c_uint8))
+    else:
+        _load().kvo_quantize_group(_ptr(x, c_float), x.size, bits, ctypes.byref(s), ctypes.byref(z),
+                                   _ptr(codes, c_uint8))
     return np.float32(s.value), np.float32(z.value), codes
 
 
@@ -128,7 +138,7 @@ class OracleCache:
     """The oracle's mirror of configure / quantize_append / decode_attention."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, kbits, vbits, group=32,
-                 residual=32):
+                 residual=32, scale_fp16=False):
         self.L, self.B, self.Hq, self.Hkv, self.D = n_layers, batch, n_q_heads, n_kv_heads, head_dim
         self.G, self.R = group, residual
         self.kbits = np.ascontiguousarray(kbits, dtype=np.uint8)
@@ -138,6 +148,8 @@ class OracleCache:
                                      _ptr(self.kbits, c_uint8), _ptr(self.vbits, c_uint8))
         if not self._h:
             raise ValueError("invalid oracle configuration")
+        if scale_fp16 and _load().kvo_set_scale_fp16(self._h, 1):
+            raise ValueError("could not select the fp16-scale variant")
 
     def close(self):
         if self._h:

@@ -27,6 +27,8 @@
  *     T - N_p (at least R once T >= R) stay in full precision.  Key groups are
  *     therefore aligned to absolute positions [32 g, 32 g + 32).
  *   - 16 "bits" means the fp16 values are kept as they are.
+ *   - metadata precision: s and z are fp32 by default.  A variant stores them as
+ *     fp16 (z exactly, s rounded once); it encodes and decodes with the rounded s.
  *
  * Precision: s, z and the codes are fp32 / integer exactly as above; everything
  * in the attention (dequantisation c * s + z, dot products, softmax, weighted
@@ -93,8 +95,16 @@ uint16_t kvo_double_to_half(double x) { return double_to_half(x); }
 /*
  * Eq. 2 on one group of n fp32 values with B = bits.  Writes the scale, the
  * zero-point (offset) and one code per element.
+ *
+ * scale_fp16 selects the narrow-metadata variant: the scale is rounded once to
+ * fp16 (round-half-to-even) and that rounded value, widened back to fp32, is the
+ * s used for encoding and decoding, so both sides agree.  The zero-point is the
+ * minimum of fp16 inputs and needs no rounding.  With the rounded scale the
+ * quotient can exceed 2^B - 1 (a scale that became subnormal in fp16 may be far
+ * too small), which is where the clamp acts; a scale that rounds to zero gives
+ * all codes 0 like a constant group.
  */
-void kvo_quantize_group(const float *x, int n, int bits, float *s_out, float *z_out, uint8_t *codes)
+void kvo_quantize_group_ex(const float *x, int n, int bits, int scale_fp16, float *s_out, float *z_out, uint8_t *codes)
 {
     float mn = x[0], mx = x[0];
     for (int i = 1; i < n; i++) {
@@ -104,7 +114,8 @@ void kvo_quantize_group(const float *x, int n, int bits, float *s_out, float *z_
     const int qmax = (1 << bits) - 1;
     const float z = mn;
     const float range = mx - mn;
-    const float s = range / (float)qmax;
+    float s = range / (float)qmax;
+    if (scale_fp16) s = kvo_half_to_float(double_to_half((double)s));
     for (int i = 0; i < n; i++) {
         long c = 0;
         if (s != 0.0f) {
@@ -117,6 +128,11 @@ void kvo_quantize_group(const float *x, int n, int bits, float *s_out, float *z_
     }
     *s_out = s;
     *z_out = z;
+}
+
+void kvo_quantize_group(const float *x, int n, int bits, float *s_out, float *z_out, uint8_t *codes)
+{
+    kvo_quantize_group_ex(x, n, bits, 0, s_out, z_out, codes);
 }
 
 /* X^ = Q(X) * s + z, evaluated in double. */
@@ -141,6 +157,7 @@ typedef struct {
 
 typedef struct kvo_cache {
     int L, B, Hq, Hkv, D, G, R;
+    int scale_fp16;     /* narrow-metadata variant: scales rounded to fp16 */
     kvo_layer *layer;
 } kvo_cache;
 
@@ -164,6 +181,15 @@ kvo_cache *kvo_create(int n_layers, int batch, int n_q_heads, int n_kv_heads, in
         c->layer[l].vbits = vbits[l];
     }
     return c;
+}
+
+/* Select the narrow-metadata variant (see kvo_quantize_group_ex).  Only while every layer is empty. */
+int kvo_set_scale_fp16(kvo_cache *c, int on)
+{
+    for (int l = 0; l < c->L; l++)
+        if (c->layer[l].T) return -1;
+    c->scale_fp16 = on ? 1 : 0;
+    return 0;
 }
 
 static void layer_free(kvo_layer *y)
@@ -235,7 +261,7 @@ static void flush_group(const kvo_cache *c, kvo_layer *y, size_t bh)
             for (int i = 0; i < G; i++)
                 buf[i] = kvo_half_to_float(y->raw_k[(bh * cap + t0 + i) * D + d]);
             float s, z;
-            kvo_quantize_group(buf, G, y->kbits, &s, &z, cbuf);
+            kvo_quantize_group_ex(buf, G, y->kbits, c->scale_fp16, &s, &z, cbuf);
             y->k_s[(bh * (cap / G) + g) * D + d] = s;
             y->k_z[(bh * (cap / G) + g) * D + d] = z;
             for (int i = 0; i < G; i++)
@@ -248,7 +274,7 @@ static void flush_group(const kvo_cache *c, kvo_layer *y, size_t bh)
                 for (int e = 0; e < G; e++)
                     buf[e] = kvo_half_to_float(y->raw_v[(bh * cap + t0 + i) * D + j * G + e]);
                 float s, z;
-                kvo_quantize_group(buf, G, y->vbits, &s, &z, cbuf);
+                kvo_quantize_group_ex(buf, G, y->vbits, c->scale_fp16, &s, &z, cbuf);
                 y->v_s[(bh * cap + t0 + i) * (D / G) + j] = s;
                 y->v_z[(bh * cap + t0 + i) * (D / G) + j] = z;
                 for (int e = 0; e < G; e++)

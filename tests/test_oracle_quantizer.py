@@ -201,3 +201,83 @@ def test_error_shrinks_with_bits_on_gaussian_groups(oracle_mod):
     assert means[8] < means[4] < means[2]
     for bits, expect in ((8, 4.1 / (4 * 255)), (4, 4.1 / (4 * 15)), (2, 4.1 / (4 * 3))):
         assert 0.75 * expect < means[bits] < 1.25 * expect
+
+
+# ---- narrow-metadata variant: scale rounded once to fp16, zero-point unchanged ----
+
+def _rne_f16(fr: Fraction) -> Fraction:
+    """Round a non-negative rational to the nearest IEEE binary16 value (ties to even), as a rational."""
+    if fr == 0:
+        return fr
+    e = fr.numerator.bit_length() - fr.denominator.bit_length()
+    if Fraction(2) ** e > fr:
+        e -= 1
+    e = max(e, -14)                       # subnormals share the quantum 2^-24
+    quantum = Fraction(2) ** (e - 10)
+    r = _rne_int(fr / quantum) * quantum
+    assert r < 65520
+    return r
+
+
+def _model_group_fp16_scale(halves, bits):
+    xs = [Fraction(float(h)) for h in halves]
+    qmax = (1 << bits) - 1
+    z = min(xs)
+    s = _rne_f16(_rne_f32(_rne_f32(max(xs) - z) / qmax))
+    codes = []
+    for x in xs:
+        if s == 0:
+            codes.append(0)
+            continue
+        t = _rne_f32(_rne_f32(x - z) / s)
+        codes.append(min(max(_rne_int(t), 0), qmax))
+    return s, z, codes
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_fp16_scale_variant_matches_rational_model_and_numpy_rounding(oracle_mod, bits):
+    rng = np.random.default_rng(700 + bits)
+    differs = 0
+    for trial in range(80):
+        scale = 10.0 ** rng.integers(-4, 3)
+        offset = rng.standard_normal() * 20.0 * (trial % 3)
+        halves = (rng.standard_normal(32) * scale + offset).astype(np.float16)
+        x = halves.astype(np.float32)
+        s32, z32, c32 = oracle_mod.quantize_group(x, bits)
+        s16, z16, c16 = oracle_mod.quantize_group(x, bits, scale_fp16=True)
+        # the stored scale is numpy's fp16 rounding of the fp32 scale; the zero-point is untouched and is an fp16 number
+        assert np.float32(np.float32(s32).astype(np.float16)) == s16
+        assert z16 == z32 and np.float32(np.float16(z16)) == z16
+        ms, mz, mc = _model_group_fp16_scale(halves, bits)
+        assert Fraction(float(s16)) == ms and Fraction(float(z16)) == mz and c16.tolist() == mc
+        differs += int(not np.array_equal(c16, c32))
+        # error bound: half a (rounded) step, plus the clamp's share where the code saturated
+        xhat = c16.astype(np.float64) * float(s16) + float(z16)
+        qmax = (1 << bits) - 1
+        slack = 0.5 * float(s16) * (1 + 2.0 ** -20) + 4 * np.spacing(np.float32(np.abs(x).max()))
+        bound = np.where(c16 == qmax, slack + qmax * abs(float(s32) - float(s16)), slack)
+        assert np.all(np.abs(xhat - x.astype(np.float64)) <= bound)
+    if bits == 8:
+        assert differs > 0      # with fine steps the rounded scale really gives a different encoding
+
+
+def test_fp16_scale_variant_special_cases(oracle_mod):
+    # a scale that is an fp16 number: the variant changes nothing
+    x = np.array([0.0, 3.0] + [1.5] * 30, dtype=np.float32)
+    assert all(np.array_equal(a, b) for a, b in zip(oracle_mod.quantize_group(x, 2), oracle_mod.quantize_group(x, 2, True)))
+    # a range so small that the scale rounds to zero in fp16: all codes 0, like a constant group
+    tiny = np.array([0.0, 2.0 ** -24] + [0.0] * 30, dtype=np.float32)          # two neighbouring fp16 subnormals
+    s, z, c = oracle_mod.quantize_group(tiny, 8, True)
+    assert s == 0.0 and z == 0.0 and not c.any()
+    s, z, c = oracle_mod.quantize_group(tiny, 8)
+    assert s > 0 and c[1] == 255
+    # a scale that becomes an fp16 subnormal loses most of its bits: the clamp is what keeps codes in range
+    x = np.zeros(32, dtype=np.float32)
+    x[1] = 2.0 ** -24 * 700                  # range 700 * 2^-24, s = 2.745 * 2^-24 -> fp16 subnormal 3 * 2^-24
+    x[2] = 2.0 ** -24 * 699
+    s, z, c = oracle_mod.quantize_group(x, 8, True)
+    assert s == np.float32(3 * 2.0 ** -24) and c[1] == 233 and c[2] == 233
+    x[1] = 2.0 ** -24 * 300                  # s = 1.18 * 2^-24 -> 1 * 2^-24: quotient 300 > 255 is clamped
+    x[2] = 2.0 ** -24 * 100
+    s, z, c = oracle_mod.quantize_group(x, 8, True)
+    assert s == np.float32(2.0 ** -24) and c[1] == 255 and c[2] == 100
