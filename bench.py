@@ -27,11 +27,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
+SCALE_BYTES = 4                 # 2 with --meta fp16 (scales stored and used as fp16)
+
+
 def layer_bytes(w, kb, vb, n_packed, n_res):
     """Algorithmic HBM bytes of one decode_attention launch on one layer."""
     from paper_2502_04420_amd import bytes_per_token
 
-    per_tok = bytes_per_token(kb, vb, w.head_dim, w.group)
+    per_tok = bytes_per_token(kb, vb, w.head_dim, w.group, scale_bytes=SCALE_BYTES)
     bh = w.batch * w.n_kv_heads
     return bh * (n_packed * per_tok + n_res * 4 * w.head_dim) + 2 * w.batch * w.n_q_heads * w.head_dim * 2
 
@@ -70,7 +73,8 @@ def build_cache(torch, pkg, W, w, extra_tokens, variant=0, splits=0):
     """Configure the library for workload w and prefill it layer by layer (inputs generated on the GPU)."""
     dev = "cuda:0"
     cache = pkg.KVQ(w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.context + extra_tokens, w.kbits,
-                    w.vbits, group=w.group, residual=w.residual, device=dev)
+                    w.vbits, group=w.group, residual=w.residual, device=dev,
+                    meta_dtype=pkg.META_FP16 if SCALE_BYTES == 2 else pkg.META_FP32)
     cache.set_decode_options(variant, splits)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     q_ms = 0.0
@@ -212,7 +216,8 @@ def cpu_baseline(W, w, budget_s=20.0):
     t_start = time.perf_counter()
     for (kb, vb), layers in pairs.items():
         layer = layers[0]
-        oc = oracle.OracleCache(1, b_s, w.n_q_heads, w.n_kv_heads, w.head_dim, [kb], [vb], group=w.group, residual=w.residual)
+        oc = oracle.OracleCache(1, b_s, w.n_q_heads, w.n_kv_heads, w.head_dim, [kb], [vb], group=w.group, residual=w.residual,
+                                scale_fp16=SCALE_BYTES == 2)
         K, V = W.kv_tokens(ws, layer, 0, w.context)
         oc.quantize_append(0, K.numpy(), V.numpy())
         kn, vn = W.kv_tokens(ws, layer, 0, 1, stream=1, total=1)
@@ -254,6 +259,8 @@ def main():
                     help="llama8b-B<batch>-T<context> (3.25-bit mix vs K8V8) or qwen7b-B<batch>-T<context> (4.0-bit mix vs K8V8)")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 vector-ALU kernel, 2 matrix-core kernel")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--meta", choices=["fp32", "fp16"], default="fp32",
+                    help="precision of the stored scales (fp16 = the narrow-metadata variant; zero-points are exact either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv8", action="store_true")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
@@ -271,6 +278,8 @@ def main():
     import kvq_workloads as W
     import paper_2502_04420_amd as pkg
 
+    global SCALE_BYTES
+    SCALE_BYTES = 2 if args.meta == "fp16" else 4
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
@@ -313,7 +322,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "decode_mfma<%s> (%d of %d layers)" % (dom, counts[dom], w_main.n_layers),
         "achieved": pk["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": pk["kernel_gbps"] / HBM_PEAK_GBPS,
-        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "traffic": read_traffic(w_main.name + ":" + dom),
+        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "")),
         "whole_call_ms": pk["call_ms"], "whole_call_frac": pk["call_gbps"] / HBM_PEAK_GBPS,
     }
     from paper_2502_04420_amd import equivalent_precision
@@ -325,6 +334,7 @@ def main():
         "config": {"workload": w_main.name, "layers": w_main.n_layers, "batch": w_main.batch, "q_heads": w_main.n_q_heads,
                    "kv_heads": w_main.n_kv_heads, "head_dim": w_main.head_dim, "context": w_main.context,
                    "equivalent_bits": equivalent_precision(w_main.kbits, w_main.vbits), "group": 32, "residual": 32,
+                   "scales": args.meta, "zero_points": "fp16 (exact)",
                    "step": "per layer: append 1 token (+ flush of 32 every 32 steps) + fused decode attention"},
         "hbm_gbps": main_res["algorithmic_gbps"], "hbm_frac_of_peak": main_res["algorithmic_gbps"] / HBM_PEAK_GBPS,
         "step_bytes": main_res["step_bytes"], "gpu_ms_per_step": main_res["gpu_ms_per_step"],

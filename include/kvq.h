@@ -47,6 +47,21 @@ typedef enum kvq_status {
 typedef struct kvq_ctx kvq_ctx;
 
 /*
+ * Precision in which a group's scale s of Eq. 2 is stored and used (the paper leaves it open;
+ * its equivalent-precision figure of Section 5.1 does not count metadata).  The zero-point z
+ * is the minimum of fp16 inputs and is always kept exactly.
+ *   KVQ_META_FP32: s is the fp32 quotient (max - min) / (2^B - 1).  The default.
+ *   KVQ_META_FP16: s is that quotient rounded once to fp16 (round half to even); encoder and
+ *     decoder both use the rounded value, codes are clamped to [0, 2^B - 1], and a scale that
+ *     rounds to zero encodes its group as all-zero codes.  Saves 8 bytes per token and tensor.
+ * kvq_debug_export returns fp32 scales in both cases (exactly the values in use).
+ */
+typedef enum kvq_meta_dtype {
+    KVQ_META_FP32 = 0,
+    KVQ_META_FP16 = 1
+} kvq_meta_dtype;
+
+/*
  * Shapes and the layer-wise precision table P (Section 5.1: one (P_k, P_v) per layer,
  * each in {2, 4, 8}; 16 keeps that tensor in fp16, the paper's half-precision baseline).
  */
@@ -61,6 +76,7 @@ typedef struct kvq_config {
     int32_t residual;      /* R >= 0: at least this many newest tokens stay fp16 once T >= R     */
     const uint8_t *kbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
     const uint8_t *vbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
+    int32_t meta_dtype;    /* a kvq_meta_dtype: precision of the stored scales (see there)       */
 } kvq_config;
 
 /* Bytes of device workspace kvq_configure needs for this configuration; 0 if it is invalid. */

@@ -34,6 +34,7 @@ bool config_ok(const kvq_config *c)
     if ((int64_t)c->batch * c->n_q_heads > (1 << 24)) return false;
     for (int l = 0; l < c->n_layers; l++)
         if (!bits_ok(c->kbits[l]) || !bits_ok(c->vbits[l])) return false;
+    if (c->meta_dtype != KVQ_META_FP32 && c->meta_dtype != KVQ_META_FP16) return false;
     return true;
 }
 
@@ -53,15 +54,16 @@ Plan make_plan(const kvq_config *c)
     const size_t BH = (size_t)c->batch * c->n_kv_heads;
     p.NB = c->max_tokens / kvq::kG;                 // N_p never exceeds G * floor(max_tokens / G)
     p.RC = c->residual + kvq::kG;                   // the fp16 window never holds R + G tokens or more
+    const bool narrow = c->meta_dtype == KVQ_META_FP16;
     size_t off = 0;
     p.layer.resize(c->n_layers);
     for (int l = 0; l < c->n_layers; l++) {
         LayerPlan &y = p.layer[l];
         const int kb = c->kbits[l], vb = c->vbits[l];
         y.kcode = off; off = align_up(off + BH * p.NB * kvq::block_code_bytes(kb));
-        y.kmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(kb));
+        y.kmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(kb, narrow));
         y.vcode = off; off = align_up(off + BH * p.NB * kvq::block_code_bytes(vb));
-        y.vmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(vb));
+        y.vmeta = off; off = align_up(off + BH * p.NB * kvq::block_meta_bytes(vb, narrow));
         y.bexp = off; off = align_up(off + BH * p.NB * sizeof(uint32_t));
         y.kres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
         y.vres = off; off = align_up(off + BH * p.RC * kvq::kD * 2);
@@ -108,6 +110,7 @@ kvq::LayerView view(const kvq_ctx *c, int l)
     v.vres = reinterpret_cast<uint16_t *>(c->ws + y.vres);
     v.kbits = c->kbits[l];
     v.vbits = c->vbits[l];
+    v.narrow = c->cfg.meta_dtype == KVQ_META_FP16 ? 1 : 0;
     return v;
 }
 

@@ -101,12 +101,14 @@ __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uin
 template <int BITS>
 struct CodeRegs {
     uint32_t dw[BITS < 16 ? 2 * BITS : 1];   // the lane's 64 codes
-    float2 s;                                // scales. keys: channels 2*lane, +1; values: group lane>>4, tokens 2*(lane&15), +1
+    uint2 sraw;                              // scales as loaded (two fp32, or one fp16 pair in .x). keys: channels 2*lane, +1;
+                                             // values: group lane>>4, tokens 2*(lane&15), +1
     uint32_t z;                              // zero-points of the same two elements, fp16 pair
     uint32_t bexp;                           // exponents of the block's largest key scale (low half) / value scale (high half)
 };
 
-template <int BITS>
+// NARROW: the block's scales are stored as fp16 (and were used that way by the encoder)
+template <int BITS, bool NARROW>
 __device__ __forceinline__ void load_codes(const uint8_t *code, const float *meta, const uint32_t *bexp, size_t blk_index,
                                            int lane, CodeRegs<BITS> &r)
 {
@@ -118,10 +120,19 @@ __device__ __forceinline__ void load_codes(const uint8_t *code, const float *met
             const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
             r.dw[4 * c] = x.x; r.dw[4 * c + 1] = x.y; r.dw[4 * c + 2] = x.z; r.dw[4 * c + 3] = x.w;
         }
-        const float *m = meta + blk_index * kMetaWords;
-        r.s = *reinterpret_cast<const float2 *>(m + 2 * lane);
-        r.z = *reinterpret_cast<const uint32_t *>(meta_zeros(m) + 2 * lane);
+        const float *m = meta + blk_index * meta_words(NARROW);
+        if constexpr (NARROW) r.sraw.x = *reinterpret_cast<const uint32_t *>(meta_scales16(m) + 2 * lane);
+        else r.sraw = *reinterpret_cast<const uint2 *>(m + 2 * lane);
+        r.z = *reinterpret_cast<const uint32_t *>(meta_zeros(m, NARROW) + 2 * lane);
     }
+}
+
+// the two scales of a loaded block as floats
+template <bool NARROW, int BITS>
+__device__ __forceinline__ float2 scales_of(const CodeRegs<BITS> &r)
+{
+    if constexpr (NARROW) return make_float2(half_lo(r.sraw.x), half_hi(r.sraw.x));
+    return make_float2(__builtin_bit_cast(float, r.sraw.x), __builtin_bit_cast(float, r.sraw.y));
 }
 
 // max over the 16 lanes of a DPP row (lanes that share lane >> 4), result in every lane
@@ -196,14 +207,15 @@ struct ValueState {
 // ------------------------------------------------------------------ key wave
 
 // scores of a quantized block: s[th][hh] for head 2*rq + hh, tokens 16*th + n
-template <int KB, int GQ>
+template <int KB, int GQ, bool NARROW>
 __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
                                               float (&s)[2][2])
 {
     const int n = lane & 15, rq = lane >> 4;
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
     const int ek = (int)(blk.bexp & 0xffffu) - 32768;
-    const float ks0 = ldexpf(blk.s.x, 14 - ek), ks1 = ldexpf(blk.s.y, 14 - ek);
+    const float2 sc = scales_of<NARROW>(blk);
+    const float ks0 = ldexpf(sc.x, 14 - ek), ks1 = ldexpf(sc.y, 14 - ek);
     const float ah = ldexpf(Q.alpha_h, ek - 14);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
@@ -307,7 +319,7 @@ __device__ __forceinline__ void apply_rescale(ValueState<GQ> &W, const PairLds<G
 }
 
 // output contribution of a quantized block
-template <int VB, int GQ>
+template <int VB, int GQ, bool NARROW>
 __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const QueryRegs<GQ> &Q, ValueState<GQ> &W,
                                               PairLds<GQ> &L, int buf, int lane)
 {
@@ -321,7 +333,8 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
             for (int i = 0; i < 4; i++) W.O[cblk][i] = ldexpf(W.O[cblk][i], W.ev - ev);
         W.ev = ev;
     }
-    const float sv0 = ldexpf(blk.s.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(blk.s.y * Q.vw1, 14 - W.ev);
+    const float2 sc = scales_of<NARROW>(blk);
+    const float sv0 = ldexpf(sc.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(sc.y * Q.vw1, 14 - W.ev);
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
         const float2 pp = *reinterpret_cast<const float2 *>(&L.P[buf][j][2 * n]);
@@ -364,7 +377,7 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
 
 // ------------------------------------------------------------------ kernel
 
-template <int KB, int VB, int GQ>
+template <int KB, int VB, int GQ, bool NARROW>
 __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows 2j and 2j + 1 of a 16-row tile");
@@ -425,7 +438,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         if constexpr (kFast) {
             if (n1 > 0) {
 #pragma unroll
-                for (int d = 0; d < DK - 1; d++) load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(d), lane, kr[d]);
+                for (int d = 0; d < DK - 1; d++) load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(d), lane, kr[d]);
             }
         }
         {
@@ -475,8 +488,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 #pragma unroll
                 for (int d = 0; d < DK; d++) {
                     if (more) {
-                        load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + DK - 1), lane, kr[(d + DK - 1) % DK]);
-                        scores_packed<KB, GQ>(kr[d], Q, L, lane, s);
+                        load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + DK - 1), lane, kr[(d + DK - 1) % DK]);
+                        scores_packed<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
                         softmax_publish<GQ>(s, W, L, i & 1, lane);
                         wg_barrier();
                         more = ++i < n1;
@@ -493,8 +506,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             if constexpr (KB < 16) if (packed) {
                 k_rows = false;
                 CodeRegs<KB> r;
-                load_codes<KB>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
-                scores_packed<KB, GQ>(r, Q, L, lane, s);
+                load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
+                scores_packed<KB, GQ, NARROW>(r, Q, L, lane, s);
             }
             if (k_rows) {
                 const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
@@ -531,7 +544,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         if constexpr (kFast) {
             if (n1 > 0) {
 #pragma unroll
-                for (int d = 0; d < DV - 1; d++) load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(d), lane, vr[d]);
+                for (int d = 0; d < DV - 1; d++) load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(d), lane, vr[d]);
             }
         }
 #pragma unroll
@@ -557,12 +570,12 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 #pragma unroll
                 for (int d = 0; d < DV; d++) {
                     if (more) {
-                        load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + DV - 1), lane, vr[(d + DV - 1) % DV]);
+                        load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + DV - 1), lane, vr[(d + DV - 1) % DV]);
                         // (always true here; as a run-time test it keeps the rarely taken re-base and rescale
                         // paths out of line, without it the register count of the loop grows by half)
                         if (i < n1) {
                             apply_rescale<GQ>(W, L, i & 1, lane);
-                            output_packed<VB, GQ>(vr[d], Q, W, L, i & 1, lane);
+                            output_packed<VB, GQ, NARROW>(vr[d], Q, W, L, i & 1, lane);
                         }
                         wg_barrier();
                         more = ++i < n1;
@@ -580,8 +593,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             if constexpr (VB < 16) if (packed) {
                 v_rows = false;
                 CodeRegs<VB> r;
-                load_codes<VB>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
-                output_packed<VB, GQ>(r, Q, W, L, buf, lane);
+                load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
+                output_packed<VB, GQ, NARROW>(r, Q, W, L, buf, lane);
             }
             if (v_rows) {
                 const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
@@ -620,28 +633,39 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     }
 }
 
-template <int KB, int VB>
+template <int KB, int VB, bool NARROW>
 hipError_t launch_gq(const DecodeArgs &a, hipStream_t s)
 {
     const int gq = a.Hq / a.Hkv;
     const int BH = a.B * a.Hkv;
     const dim3 block(128);
     if (gq <= 4) {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 4>), dim3(a.splits, BH, 1), block, 0, s, a);
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 8>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
     }
     return hipGetLastError();
 }
 
-template <int KB>
+template <int KB, bool NARROW>
 hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
 {
     switch (a.lv.vbits) {
-    case 2: return launch_gq<KB, 2>(a, s);
-    case 4: return launch_gq<KB, 4>(a, s);
-    case 8: return launch_gq<KB, 8>(a, s);
-    default: return launch_gq<KB, 16>(a, s);
+    case 2: return launch_gq<KB, 2, NARROW>(a, s);
+    case 4: return launch_gq<KB, 4, NARROW>(a, s);
+    case 8: return launch_gq<KB, 8, NARROW>(a, s);
+    default: return launch_gq<KB, 16, NARROW>(a, s);
+    }
+}
+
+template <bool NARROW>
+hipError_t launch_kb(const DecodeArgs &a, hipStream_t s)
+{
+    switch (a.lv.kbits) {
+    case 2: return launch_vb<2, NARROW>(a, s);
+    case 4: return launch_vb<4, NARROW>(a, s);
+    case 8: return launch_vb<8, NARROW>(a, s);
+    default: return launch_vb<16, NARROW>(a, s);
     }
 }
 
@@ -650,12 +674,7 @@ hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
 hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s)
 {
     if (a.B * a.Hkv > 65535) return hipErrorInvalidConfiguration;
-    switch (a.lv.kbits) {
-    case 2: return launch_vb<2>(a, s);
-    case 4: return launch_vb<4>(a, s);
-    case 8: return launch_vb<8>(a, s);
-    default: return launch_vb<16>(a, s);
-    }
+    return a.lv.narrow ? launch_kb<true>(a, s) : launch_kb<false>(a, s);
 }
 
 }  // namespace kvq

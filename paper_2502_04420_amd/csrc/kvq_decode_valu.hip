@@ -22,13 +22,18 @@ __device__ __forceinline__ void wave_lds_sync()
 __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
 
-// a block's metadata (128 fp32 scales, 128 fp16 zero-points) into an LDS tile of 256 floats, one wave
-__device__ __forceinline__ void stage_meta(const float *meta, float *tile, int lane)
+// a block's metadata (128 scales, fp32 or fp16; 128 fp16 zero-points) into an LDS tile of 256 floats, one wave
+__device__ __forceinline__ void stage_meta(const float *meta, bool narrow, float *tile, int lane)
 {
     if (lane < 32) {
-        *reinterpret_cast<float4 *>(&tile[4 * lane]) = *reinterpret_cast<const float4 *>(meta + 4 * lane);
+        if (narrow) {
+            const uint2 h = *reinterpret_cast<const uint2 *>(meta_scales16(meta) + 4 * lane);
+            *reinterpret_cast<float4 *>(&tile[4 * lane]) = make_float4(half_lo(h.x), half_hi(h.x), half_lo(h.y), half_hi(h.y));
+        } else {
+            *reinterpret_cast<float4 *>(&tile[4 * lane]) = *reinterpret_cast<const float4 *>(meta + 4 * lane);
+        }
     } else {
-        const uint2 z = *reinterpret_cast<const uint2 *>(meta_zeros(meta) + 4 * (lane - 32));
+        const uint2 z = *reinterpret_cast<const uint2 *>(meta_zeros(meta, narrow) + 4 * (lane - 32));
         *reinterpret_cast<float4 *>(&tile[kD + 4 * (lane - 32)]) = make_float4(half_lo(z.x), half_hi(z.x), half_lo(z.y), half_hi(z.y));
     }
 }
@@ -98,7 +103,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
                 dw[4 * c] = x.x; dw[4 * c + 1] = x.y; dw[4 * c + 2] = x.z; dw[4 * c + 3] = x.w;
             }
-            stage_meta(a.lv.kmeta + blk_index * kMetaWords, kmeta_lds[wave], lane);
+            stage_meta(a.lv.kmeta + blk_index * meta_words(a.lv.narrow != 0), a.lv.narrow != 0, kmeta_lds[wave], lane);
             wave_lds_sync();
 #pragma unroll
             for (int cb = 0; cb < 4; cb++) {
@@ -197,7 +202,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 const uint4 x = *reinterpret_cast<const uint4 *>(blk + c * 1024 + lane * 16);
                 dw[4 * c] = x.x; dw[4 * c + 1] = x.y; dw[4 * c + 2] = x.z; dw[4 * c + 3] = x.w;
             }
-            stage_meta(a.lv.vmeta + blk_index * kMetaWords, vmeta_lds[wave], lane);
+            stage_meta(a.lv.vmeta + blk_index * meta_words(a.lv.narrow != 0), a.lv.narrow != 0, vmeta_lds[wave], lane);
             wave_lds_sync();
             float sv[4][8], zv[4][8];     // [channel group][token 8*kq + e]
 #pragma unroll

@@ -10,13 +10,14 @@ namespace kvq {
 // Device pointers of one layer's cache inside the workspace.
 struct LayerView {
     uint8_t *kcode;       // [BH][NB] blocks of block_code_bytes(kbits)
-    float *kmeta;         // [BH][NB] metadata blocks of kMetaWords dwords (absent when kbits == 16)
+    float *kmeta;         // [BH][NB] metadata blocks of meta_words(narrow) dwords (absent when kbits == 16)
     uint8_t *vcode;       // [BH][NB] blocks of block_code_bytes(vbits)
-    float *vmeta;         // [BH][NB] metadata blocks of kMetaWords dwords (absent when vbits == 16)
+    float *vmeta;         // [BH][NB] metadata blocks of meta_words(narrow) dwords (absent when vbits == 16)
     uint32_t *bexp;       // [BH][NB] binary exponents of the block's largest key / value scale (lo / hi half)
     uint16_t *kres;       // [BH][RC][128] fp16 ring, slot = position % RC
     uint16_t *vres;
     int kbits, vbits;
+    int narrow;           // 1: scales stored (and used) as fp16
 };
 
 struct QuantArgs {

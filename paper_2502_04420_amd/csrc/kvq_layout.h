@@ -21,6 +21,7 @@
 //
 // Metadata of a block: 128 fp32 scales, then 128 zero-points as fp16 (768 bytes).  A zero-point
 // is the minimum of a group of fp16 inputs, so it is an fp16 number and the narrow store is exact.
+// In the narrow-metadata variant the scales are fp16 as well (512 bytes per block).
 //   keys  : index = channel              (per channel over the block's 32 tokens)
 //   values: index = 32*(channel/32) + token (per token over 32 channels)
 //
@@ -32,11 +33,11 @@ namespace kvq {
 
 constexpr int kD = 128;       // head dimension
 constexpr int kG = 32;        // group size: tokens per key group, channels per value group
-constexpr int kMetaBytes = 768;
-constexpr int kMetaWords = kMetaBytes / 4;   // a block's metadata in dwords: scales at [0, 128), zero-points at [128, 192)
+// a block's metadata in dwords: scales, then zero-points (fp16); narrow = scales as fp16 too
+__host__ __device__ constexpr int meta_words(bool narrow) { return narrow ? 128 : 192; }
 
 __host__ __device__ constexpr int block_code_bytes(int bits) { return bits == 16 ? 32 * kD * 2 : 512 * bits; }
-__host__ __device__ constexpr int block_meta_bytes(int bits) { return bits == 16 ? 0 : kMetaBytes; }
+__host__ __device__ constexpr int block_meta_bytes(int bits, bool narrow) { return bits == 16 ? 0 : 4 * meta_words(narrow); }
 
 // dword index (0 .. 2*bits-1) and bit shift of code ci (0..63) inside a lane's codes
 template <int BITS>
@@ -66,8 +67,11 @@ __host__ __device__ constexpr int key_ci(int t, int d) { return 8 * (4 * (t >> 4
 __host__ __device__ constexpr int val_lane(int t, int d) { return 16 * (t >> 3) + (d & 15); }
 __host__ __device__ constexpr int val_ci(int t, int d) { return 8 * (d >> 4) + (t & 7); }
 
-// zero-points of the metadata block that starts at `meta` (fp16 bit patterns)
-__host__ __device__ inline const uint16_t *meta_zeros(const float *meta) { return reinterpret_cast<const uint16_t *>(meta + kD); }
-__host__ __device__ inline uint16_t *meta_zeros(float *meta) { return reinterpret_cast<uint16_t *>(meta + kD); }
+// zero-points (fp16 bit patterns) and, in the narrow variant, scales (fp16 bit patterns) of the metadata
+// block that starts at `meta`
+__host__ __device__ inline const uint16_t *meta_zeros(const float *meta, bool narrow) { return reinterpret_cast<const uint16_t *>(meta) + (narrow ? 128 : 256); }
+__host__ __device__ inline uint16_t *meta_zeros(float *meta, bool narrow) { return reinterpret_cast<uint16_t *>(meta) + (narrow ? 128 : 256); }
+__host__ __device__ inline const uint16_t *meta_scales16(const float *meta) { return reinterpret_cast<const uint16_t *>(meta); }
+__host__ __device__ inline uint16_t *meta_scales16(float *meta) { return reinterpret_cast<uint16_t *>(meta); }
 
 }  // namespace kvq

@@ -62,9 +62,10 @@ __device__ __forceinline__ float round_exact(float d, float s)
 // from the correctly rounded quotient by less than 2^-22 of its value, so both round to the same integer
 // unless the product lies that close to a tie; the test below uses twice that distance.  If it fires for any
 // lane of the wave (rare for real data, always for exact ties) the eight elements are redone with the
-// defining division.  d >= 0 and rs >= 0 (rs is 0 where s is 0, giving code 0), so the fast result needs no clamp:
-// d / s <= (2^B - 1)(1 + 2^-23).
-template <int BITS>
+// defining division.  d >= 0 and rs >= 0 (rs is 0 where s is 0, giving code 0), so the fast result needs no clamp
+// from below, and none from above either while s is the fp32 scale: d / s <= (2^B - 1)(1 + 2^-23).  CLAMP is for
+// the narrow-metadata variant, whose rounded scale can be too small.
+template <int BITS, bool CLAMP>
 __device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s8)[8], const float (&z8)[8], const float (&r8)[8],
                                         float (&c8)[8])
 {
@@ -73,7 +74,7 @@ __device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s
     for (int e = 0; e < 8; e++) {
         d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
         const float t = d[e] * r8[e];
-        c8[e] = rintf(t);
+        c8[e] = CLAMP ? fminf(rintf(t), (float)((1 << BITS) - 1)) : rintf(t);
         u[e] = fmaf(t, 4.76837158203125e-07f, -fabsf(__builtin_amdgcn_fractf(t) - 0.5f));    // 2^-21 t - |frac(t) - 1/2|
     }
     // some element is within its margin of a tie <=> the largest u is >= 0
@@ -115,6 +116,20 @@ __device__ __forceinline__ float scale_of(float mn, float mx, int bits)
     return __fdiv_rn(mx - mn, (float)((1 << bits) - 1));
 }
 
+// the scale as it is stored and used: fp32, or rounded once to fp16 (round half to even) in the narrow variant
+template <bool NARROW>
+__device__ __forceinline__ float stored_scale(float s)
+{
+    if constexpr (NARROW) return (float)(_Float16)s;
+    return s;
+}
+template <bool NARROW>
+__device__ __forceinline__ void store_scale(float *meta, int idx, float s)
+{
+    if constexpr (NARROW) meta_scales16(meta)[idx] = __builtin_bit_cast(uint16_t, (_Float16)s);
+    else meta[idx] = s;
+}
+
 __device__ __forceinline__ float recip_or_zero(float s) { return s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f; }
 
 __device__ __forceinline__ void load8(const float *p, float (&v)[8])
@@ -148,7 +163,7 @@ __device__ __forceinline__ int value_row(int ch) { return (ch & 0x70) | ((ch ^ (
 // One wave per (tensor, block of 32 tokens, (b, h)); blockIdx.y = 0 keys, 1 values.  The statistics are
 // taken in the arrangement the rows are loaded in (16 bytes = 8 channels of a token per lane), the tile
 // goes through LDS, and each lane encodes exactly the 64 codes it stores.
-template <int KB, int VB>
+template <int KB, int VB, bool NARROW>
 __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
 {
     const int lane = threadIdx.x;
@@ -197,17 +212,17 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
                 mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
             }
-            float *meta = a.lv.kmeta + blk_index * kMetaWords;
+            float *meta = a.lv.kmeta + blk_index * meta_words(NARROW);
             float s_max = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 const uint32_t mnb = (mnp[e >> 1] >> (16 * (e & 1))) & 0xffffu;
                 const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mxp[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                const float s = scale_of(mn, mx, KB);
+                const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
                 s_max = fmaxf(s_max, s);
                 if (r == 0) {
                     sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn; rsc[8 * c16 + e] = recip_or_zero(s);
-                    meta[8 * c16 + e] = s; meta_zeros(meta)[8 * c16 + e] = (uint16_t)mnb;
+                    store_scale<NARROW>(meta, 8 * c16 + e, s); meta_zeros(meta, NARROW)[8 * c16 + e] = (uint16_t)mnb;
                 }
             }
 #pragma unroll
@@ -225,7 +240,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
                 float s8[8], z8[8], r8[8], c8[8];
                 load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
-                encode8<KB>(xw, s8, z8, r8, c8);
+                encode8<KB, NARROW>(xw, s8, z8, r8, c8);
                 pack8<KB>(c8, m, dw);
             }
             uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
@@ -242,7 +257,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 *reinterpret_cast<uint4 *>(dst + (8 * r + i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
             if (lane == 0) bexp16[1] = 32768;
         } else {
-            float *meta = a.lv.vmeta + blk_index * kMetaWords;
+            float *meta = a.lv.vmeta + blk_index * meta_words(NARROW);
             float s_max = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; i++) {
@@ -254,12 +269,12 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 mnp = pk_min(mnp, __shfl_xor(mnp, 2)); mxp = pk_max(mxp, __shfl_xor(mxp, 2));
                 const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
                 const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
-                const float s = scale_of(mn, mx, VB);
+                const float s = stored_scale<NARROW>(scale_of(mn, mx, VB));
                 s_max = fmaxf(s_max, s);
                 if ((c16 & 3) == 0) {
                     const int gd = c16 >> 2;
                     sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
-                    meta[32 * gd + t] = s; meta_zeros(meta)[32 * gd + t] = float_to_half_bits_exact(mn);
+                    store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
                 }
             }
             // 8 x 8 transpose in registers: channel 8*c16 + e gets its 8 tokens as one 16-byte chunk
@@ -284,7 +299,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
                 float s8[8], z8[8], r8[8], c8[8];
                 load8(&sc[32 * gd + 8 * kq], s8); load8(&zp[32 * gd + 8 * kq], z8); load8(&rsc[32 * gd + 8 * kq], r8);
-                encode8<VB>(xw, s8, z8, r8, c8);
+                encode8<VB, NARROW>(xw, s8, z8, r8, c8);
                 pack8<VB>(c8, m, dw);
             }
             uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
@@ -377,12 +392,13 @@ __global__ void export_meta(ExportArgs a, int which)   // 0 = keys, 1 = values
     const int within = (int)(idx % kD);
     const int g = (int)((idx / kD) % (a.n_packed / kG));
     const int bh = (int)(idx / ((long long)kD * (a.n_packed / kG)));
-    const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * kMetaWords;
+    const bool narrow = a.lv.narrow != 0;
+    const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * meta_words(narrow);
     float *so = which == 0 ? a.k_scale : a.v_scale, *zo = which == 0 ? a.k_zero : a.v_zero;
     // canonical value metadata is [token][group]; the device keeps [group][token]
     const int src = which == 0 ? within : 32 * (within & 3) + (within >> 2);
-    if (so) so[idx] = meta[src];
-    if (zo) zo[idx] = half_bits_to_float(meta_zeros(meta)[src]);
+    if (so) so[idx] = narrow ? half_bits_to_float(meta_scales16(meta)[src]) : meta[src];
+    if (zo) zo[idx] = half_bits_to_float(meta_zeros(meta, narrow)[src]);
 }
 
 // fp16 tensors: rows [bh][token][128]; one thread per 16 bytes.  which: 0/1 = 16-bit keys / values of the
@@ -410,17 +426,28 @@ __global__ void export_rows(ExportArgs a, int which)
     *reinterpret_cast<uint4 *>(dst + ((size_t)bh * n_tok + tok) * kD + 8 * c16) = *reinterpret_cast<const uint4 *>(src + 8 * c16);
 }
 
-template <int KB>
+template <int KB, bool NARROW>
 hipError_t launch_quantize_vb(const QuantArgs &a, hipStream_t s)
 {
     const dim3 grid((unsigned)a.n_blocks * (unsigned)a.BH, 2), block(64);
     switch (a.lv.vbits) {
-    case 2: hipLaunchKernelGGL((quantize_blocks<KB, 2>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((quantize_blocks<KB, 4>), grid, block, 0, s, a); break;
-    case 8: hipLaunchKernelGGL((quantize_blocks<KB, 8>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((quantize_blocks<KB, 16>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((quantize_blocks<KB, 2, NARROW>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((quantize_blocks<KB, 4, NARROW>), grid, block, 0, s, a); break;
+    case 8: hipLaunchKernelGGL((quantize_blocks<KB, 8, NARROW>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((quantize_blocks<KB, 16, NARROW>), grid, block, 0, s, a); break;
     }
     return hipGetLastError();
+}
+
+template <bool NARROW>
+hipError_t launch_quantize_kb(const QuantArgs &a, hipStream_t s)
+{
+    switch (a.lv.kbits) {
+    case 2: return launch_quantize_vb<2, NARROW>(a, s);
+    case 4: return launch_quantize_vb<4, NARROW>(a, s);
+    case 8: return launch_quantize_vb<8, NARROW>(a, s);
+    default: return launch_quantize_vb<16, NARROW>(a, s);
+    }
 }
 
 unsigned blocks_for(long long total, int threads) { return (unsigned)((total + threads - 1) / threads); }
@@ -431,12 +458,7 @@ hipError_t launch_quantize(const QuantArgs &a, hipStream_t s)
 {
     if (a.n_blocks < 1 || a.BH < 1) return hipSuccess;
     if ((long long)a.n_blocks * a.BH > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    switch (a.lv.kbits) {
-    case 2: return launch_quantize_vb<2>(a, s);
-    case 4: return launch_quantize_vb<4>(a, s);
-    case 8: return launch_quantize_vb<8>(a, s);
-    default: return launch_quantize_vb<16>(a, s);
-    }
+    return a.lv.narrow ? launch_quantize_kb<true>(a, s) : launch_quantize_kb<false>(a, s);
 }
 
 hipError_t launch_residual_copy(const ResidualCopyArgs &a, hipStream_t s)

@@ -112,6 +112,33 @@ def test_all_precision_pairs(kvq_mod, oracle_mod, kb, vb, variant):
     assert_outputs_close(out, o16, o64, "K%dV%d" % (kb, vb))
 
 
+@pytest.mark.parametrize("kb,vb", [(8, 8), (8, 4), (4, 4), (4, 2), (2, 2), (16, 4), (2, 16)])
+def test_fp16_scale_variant(kvq_mod, oracle_mod, kb, vb, variant):
+    """Narrow metadata (scales rounded to fp16 and used that way): same bars against the oracle in the same mode,
+    through chunked appends with window flushes, g_q = 7, a tiny-range channel whose scale underflows in fp16."""
+    w = W.Workload("meta16", 1, 2, 14, 2, 128, 32 * 7 + 11, [kb], [vb], seed=900 + kb * 17 + vb, outlier_channels=3)
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, 512, [kb], [vb], meta_dtype=kvq_mod.META_FP16)
+    g.set_decode_options(variant, 0)
+    o = oracle_mod.OracleCache(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, [kb], [vb], scale_fp16=True)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    K[:, :, :, 9] = (K[:, :, :, 9] * 2.0 ** -22).to(torch.float16)        # subnormal fp16 inputs: scale ~ 2^-24 .. 0 in fp16
+    V[:, :, 40:80, 32:64] = (V[:, :, 40:80, 32:64] * 2.0 ** -21).to(torch.float16)
+    pos = 0
+    for n in (100, 1, 31, 64, w.context - 196):
+        g.quantize_append(0, K[:, :, pos:pos + n].contiguous().cuda(), V[:, :, pos:pos + n].contiguous().cuda())
+        o.quantize_append(0, np.ascontiguousarray(K[:, :, pos:pos + n].numpy()), np.ascontiguousarray(V[:, :, pos:pos + n].numpy()))
+        pos += n
+    gd, od = g.debug_export(0), o.export(0)
+    assert_export_equal(gd, od, "meta16 K%dV%d" % (kb, vb))
+    for key in ("k_scale", "v_scale"):
+        if key in od:          # every scale in use is an fp16 number
+            assert np.array_equal(od[key].astype(np.float16).astype(np.float32), od[key])
+    q = W.query(w, 0)
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    assert_outputs_close(out, o16, o64, "meta16 K%dV%d" % (kb, vb))
+
+
 @pytest.mark.parametrize("gq,hkv", [(1, 3), (2, 2), (3, 1), (4, 2), (5, 1), (7, 4), (8, 1), (12, 1), (16, 1)])
 def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv, variant):
     w = W.Workload("gq", 1, 2, gq * hkv, hkv, 128, 32 * 4 + 7, [4], [2], seed=200 + gq, key_bias_std=20.0)

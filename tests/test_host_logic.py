@@ -50,8 +50,11 @@ def test_workspace_bytes_and_config_validation(lib):
     assert need > 0 and need % 256 == 0
     # codes + metadata of 8 blocks per (b, h) for both layers must fit
     assert need >= 4 * 8 * ((4096 + 2048 + 2 * 768) + (2048 + 1024 + 2 * 768))
+    c16, k16 = _cfg(meta_dtype=1)          # fp16 scales: 256 bytes less per block and tensor
+    need16 = lib.kvq_workspace_bytes(ctypes.byref(c16))
+    assert 0 < need16 < need and need - need16 >= 4 * 8 * 4 * 256
     for bad in (dict(head_dim=64), dict(group=16), dict(n_q_heads=7), dict(kbits=[8, 3]), dict(vbits=[1, 2]),
-                dict(max_tokens=0), dict(batch=0), dict(residual=-1)):
+                dict(max_tokens=0), dict(batch=0), dict(residual=-1), dict(meta_dtype=2)):
         c, k = _cfg(**bad)
         assert lib.kvq_workspace_bytes(ctypes.byref(c)) == 0, bad
         h = ctypes.c_void_p()
