@@ -148,6 +148,15 @@ def llama_kivi_c490() -> Tuple[List[int], List[int]]:
     ])
 
 
+def qwen_kivi_c392() -> Tuple[List[int], List[int]]:
+    """Qwen2.5-7B KIVI 3.92-bit schedule from the same table (28 layers; uniform pairs KV8 / KV4 / KV2)."""
+    return schedule_from_spec(28, [
+        (8, 8, [0, 2, 6, 11, 15, 17]),
+        (4, 4, [4, 5, 8, 12] + _rng(22, 26)),
+        (2, 2, [1, 3, 7, 9, 10, 13, 14, 16] + _rng(18, 21) + [27]),
+    ])
+
+
 def qwen_mix_40() -> Tuple[List[int], List[int]]:
     """The benchmark's 4.0-bit schedule for the 28-layer Qwen shape: even layers K8V2, odd K4V2."""
     return [8 if l % 2 == 0 else 4 for l in range(28)], [2] * 28
@@ -173,6 +182,30 @@ def config4(batch: int = 8, context: int = 32768) -> Workload:
     kb, vb = qwen_mix_40()
     return Workload("qwen7b-B%d-T%d-mix4.0" % (batch, context), 28, batch, 28, 4, 128, context, kb, vb,
                     seed=4, key_bias_std=20.0, note="g_q = 7, biased keys")
+
+
+SCHEDULES = {
+    # family -> schedule name -> (function, layers, q heads, kv heads, extra Workload arguments)
+    "llama8b": {"mix3.25": llama_mix_325, "kivi-c3.25": llama_kivi_c325, "kivi-c4.90": llama_kivi_c490},
+    "qwen7b": {"mix4.0": qwen_mix_40, "kivi-c3.92": qwen_kivi_c392},
+}
+
+
+def named(family: str, schedule: str, batch: int, context: int) -> Workload:
+    """Workload of a model shape (llama8b: 32 layers, 32/8 heads; qwen7b: 28 layers, 28/4 heads, biased keys) with one
+    of its layer-wise schedules, or "K<k>V<v>" for a uniform pair."""
+    shape = {"llama8b": (32, 32, 8, dict(seed=3, outlier_channels=3)), "qwen7b": (28, 28, 4, dict(seed=4, key_bias_std=20.0))}[family]
+    L, hq, hkv, extra = shape
+    if schedule in SCHEDULES[family]:
+        kb, vb = SCHEDULES[family][schedule]()
+    else:
+        import re
+
+        m = re.fullmatch(r"K(\d+)V(\d+)", schedule)
+        if not m:
+            raise ValueError("unknown schedule %r for %s (have %s or K<k>V<v>)" % (schedule, family, ", ".join(SCHEDULES[family])))
+        kb, vb = [int(m.group(1))] * L, [int(m.group(2))] * L
+    return Workload("%s-B%d-T%d-%s" % (family, batch, context, schedule), L, batch, hq, hkv, 128, context, kb, vb, **extra)
 
 
 def llama_uniform(kbit: int, vbit: int, batch: int, context: int, seed: int = 5) -> Workload:
