@@ -55,6 +55,10 @@ def _load():
     lib.kvo_quantize_group_ex.argtypes = [f32p, c_int, c_int, c_int, f32p, f32p, u8p]
     lib.kvo_set_scale_fp16.restype = c_int
     lib.kvo_set_scale_fp16.argtypes = [c_void_p, c_int]
+    lib.kvo_set_key_per_token.restype = c_int
+    lib.kvo_set_key_per_token.argtypes = [c_void_p, c_int]
+    lib.kvo_reconstruct.restype = c_int
+    lib.kvo_reconstruct.argtypes = [c_void_p, c_int, f64p, f64p]
     lib.kvo_create.restype = c_void_p
     lib.kvo_create.argtypes = [c_int] * 7 + [u8p, u8p]
     lib.kvo_destroy.restype = None
@@ -138,7 +142,7 @@ class OracleCache:
     """The oracle's mirror of configure / quantize_append / decode_attention."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, kbits, vbits, group=32,
-                 residual=32, scale_fp16=False):
+                 residual=32, scale_fp16=False, key_per_token=False):
         self.L, self.B, self.Hq, self.Hkv, self.D = n_layers, batch, n_q_heads, n_kv_heads, head_dim
         self.G, self.R = group, residual
         self.kbits = np.ascontiguousarray(kbits, dtype=np.uint8)
@@ -150,6 +154,9 @@ class OracleCache:
             raise ValueError("invalid oracle configuration")
         if scale_fp16 and _load().kvo_set_scale_fp16(self._h, 1):
             raise ValueError("could not select the fp16-scale variant")
+        self.key_per_token = bool(key_per_token)
+        if key_per_token and _load().kvo_set_key_per_token(self._h, 1):
+            raise ValueError("could not select per-token key grouping")
 
     def close(self):
         if self._h:
@@ -196,13 +203,27 @@ class OracleCache:
         res = (out.view(np.float16), o64)
         return res + (p,) if want_p else res
 
+    def reconstruct(self, layer: int):
+        """The layer's cache as attention sees it, in double: (K^, V^) [B, Hkv, T, D]; quantized tokens as
+        code * s + z (Eq. 2), window tokens as their fp16 values."""
+        npk, nr = self.tokens(layer)
+        shape = (self.B, self.Hkv, npk + nr, self.D)
+        Kh, Vh = np.zeros(shape, dtype=np.float64), np.zeros(shape, dtype=np.float64)
+        if _load().kvo_reconstruct(self._h, layer, _ptr(Kh, c_double), _ptr(Vh, c_double)):
+            raise ValueError("bad layer")
+        return Kh, Vh
+
     def export(self, layer: int) -> dict:
         """Canonical dump: packed codes, scales, zero-points, full-precision tail."""
         npk, nr = self.tokens(layer)
         kb, vb = int(self.kbits[layer]), int(self.vbits[layer])
         B, H, D, G = self.B, self.Hkv, self.D, self.G
         r = {"n_packed": npk, "n_residual": nr}
-        if kb < 16:
+        if kb < 16 and self.key_per_token:
+            r["k_codes"] = np.zeros((B, H, npk, D * kb // 8), dtype=np.uint8)
+            r["k_scale"] = np.zeros((B, H, npk, D // G), dtype=np.float32)
+            r["k_zero"] = np.zeros((B, H, npk, D // G), dtype=np.float32)
+        elif kb < 16:
             r["k_codes"] = np.zeros((B, H, npk // G, D, G * kb // 8), dtype=np.uint8)
             r["k_scale"] = np.zeros((B, H, npk // G, D), dtype=np.float32)
             r["k_zero"] = np.zeros((B, H, npk // G, D), dtype=np.float32)

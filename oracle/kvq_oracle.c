@@ -27,6 +27,8 @@
  *     T - N_p (at least R once T >= R) stay in full precision.  Key groups are
  *     therefore aligned to absolute positions [32 g, 32 g + 32).
  *   - 16 "bits" means the fp16 values are kept as they are.
+ *   - key grouping: the KIVI mode above by default; a second mode groups keys per
+ *     token like the values (the paper's per-token-asym mode).
  *   - metadata precision: s and z are fp32 by default.  A variant stores them as
  *     fp16 (z exactly, s rounded once); it encodes and decodes with the rounded s.
  *
@@ -158,6 +160,7 @@ typedef struct {
 typedef struct kvo_cache {
     int L, B, Hq, Hkv, D, G, R;
     int scale_fp16;     /* narrow-metadata variant: scales rounded to fp16 */
+    int key_per_token;  /* keys quantized like values: per token over each group of G channels */
     kvo_layer *layer;
 } kvo_cache;
 
@@ -189,6 +192,20 @@ int kvo_set_scale_fp16(kvo_cache *c, int on)
     for (int l = 0; l < c->L; l++)
         if (c->layer[l].T) return -1;
     c->scale_fp16 = on ? 1 : 0;
+    return 0;
+}
+
+/*
+ * Select the axis along which the keys are grouped for Eq. 2.  0 (default): per channel over G
+ * consecutive tokens (the KIVI mode).  1: per token over each group of G channels, exactly as the
+ * values (the paper's per-token-asym mode; its group size is not stated, the value grouping is
+ * used).  Only while every layer is empty.  The key metadata then has the value metadata's shape.
+ */
+int kvo_set_key_per_token(kvo_cache *c, int on)
+{
+    for (int l = 0; l < c->L; l++)
+        if (c->layer[l].T) return -1;
+    c->key_per_token = on ? 1 : 0;
     return 0;
 }
 
@@ -256,7 +273,20 @@ static void flush_group(const kvo_cache *c, kvo_layer *y, size_t bh)
     const size_t g = t0 / G;
     float *buf = malloc(sizeof(float) * (size_t)(G > D ? G : D));
     uint8_t *cbuf = malloc((size_t)(G > D ? G : D));
-    if (y->kbits < 16) {
+    if (y->kbits < 16 && c->key_per_token) {
+        for (int i = 0; i < G; i++) {
+            for (int j = 0; j < D / G; j++) {
+                for (int e = 0; e < G; e++)
+                    buf[e] = kvo_half_to_float(y->raw_k[(bh * cap + t0 + i) * D + j * G + e]);
+                float s, z;
+                kvo_quantize_group_ex(buf, G, y->kbits, c->scale_fp16, &s, &z, cbuf);
+                y->k_s[(bh * cap + t0 + i) * (D / G) + j] = s;      /* same element count as the per-channel shape */
+                y->k_z[(bh * cap + t0 + i) * (D / G) + j] = z;
+                for (int e = 0; e < G; e++)
+                    y->k_code[(bh * cap + t0 + i) * D + j * G + e] = cbuf[e];
+            }
+        }
+    } else if (y->kbits < 16) {
         for (int d = 0; d < D; d++) {
             for (int i = 0; i < G; i++)
                 buf[i] = kvo_half_to_float(y->raw_k[(bh * cap + t0 + i) * D + d]);
@@ -350,6 +380,42 @@ static void attend_row(const double *q, const double *Kh, const double *Vh, int 
         for (int d = 0; d < D; d++) o[d] += p[t] * Vh[(size_t)t * D + d];
 }
 
+/* The cache of one layer as attention sees it: X^ (Eq. 2) for quantized tokens, the fp16 values for the rest.
+ * Kh, Vh: double [B, Hkv, T, D]. */
+static void reconstruct_bh(const kvo_cache *c, const kvo_layer *y, size_t bh, double *Kh, double *Vh)
+{
+    const int D = c->D, G = c->G, T = y->T, Np = y->Np;
+    const size_t cap = (size_t)y->cap;
+    for (int t = 0; t < T; t++) {
+        for (int d = 0; d < D; d++) {
+            size_t e = (bh * cap + t) * D + d;
+            if (t < Np && y->kbits < 16 && c->key_per_token)
+                Kh[(size_t)t * D + d] = dequant(y->k_code[e], y->k_s[(bh * cap + t) * (D / G) + d / G],
+                                                y->k_z[(bh * cap + t) * (D / G) + d / G]);
+            else if (t < Np && y->kbits < 16)
+                Kh[(size_t)t * D + d] = dequant(y->k_code[e], y->k_s[(bh * (cap / G) + t / G) * D + d],
+                                                y->k_z[(bh * (cap / G) + t / G) * D + d]);
+            else
+                Kh[(size_t)t * D + d] = half_to_double(y->raw_k[e]);
+            if (t < Np && y->vbits < 16)
+                Vh[(size_t)t * D + d] = dequant(y->v_code[e], y->v_s[(bh * cap + t) * (D / G) + d / G],
+                                                y->v_z[(bh * cap + t) * (D / G) + d / G]);
+            else
+                Vh[(size_t)t * D + d] = half_to_double(y->raw_v[e]);
+        }
+    }
+}
+
+int kvo_reconstruct(const kvo_cache *c, int layer, double *K_hat, double *V_hat)
+{
+    if (layer < 0 || layer >= c->L) return -1;
+    const kvo_layer *y = &c->layer[layer];
+    const size_t per = (size_t)y->T * c->D;
+    for (long bh = 0; bh < (long)c->B * c->Hkv; bh++)
+        reconstruct_bh(c, y, (size_t)bh, K_hat + (size_t)bh * per, V_hat + (size_t)bh * per);
+    return 0;
+}
+
 /*
  * Decode attention of one layer over everything appended so far: quantized
  * tokens enter as X^ (Eq. 2), the rest as their fp16 values.
@@ -363,8 +429,7 @@ int kvo_decode_attention(const kvo_cache *c, int layer, const uint16_t *q, uint1
     if (layer < 0 || layer >= c->L) return -1;
     const kvo_layer *y = &c->layer[layer];
     if (y->T < 1) return -2;
-    const int D = c->D, G = c->G, T = y->T, Np = y->Np, gq = c->Hq / c->Hkv;
-    const size_t cap = (size_t)y->cap;
+    const int D = c->D, T = y->T, gq = c->Hq / c->Hkv;
     const long BH = (long)c->B * c->Hkv;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long bh = 0; bh < BH; bh++) {
@@ -373,21 +438,7 @@ int kvo_decode_attention(const kvo_cache *c, int layer, const uint16_t *q, uint1
         double *p = malloc(sizeof(double) * (size_t)T);
         double *qd = malloc(sizeof(double) * (size_t)D);
         double *o = malloc(sizeof(double) * (size_t)D);
-        for (int t = 0; t < T; t++) {
-            for (int d = 0; d < D; d++) {
-                size_t e = ((size_t)bh * cap + t) * D + d;
-                if (t < Np && y->kbits < 16)
-                    Kh[(size_t)t * D + d] = dequant(y->k_code[e], y->k_s[((size_t)bh * (cap / G) + t / G) * D + d],
-                                                    y->k_z[((size_t)bh * (cap / G) + t / G) * D + d]);
-                else
-                    Kh[(size_t)t * D + d] = half_to_double(y->raw_k[e]);
-                if (t < Np && y->vbits < 16)
-                    Vh[(size_t)t * D + d] = dequant(y->v_code[e], y->v_s[((size_t)bh * cap + t) * (D / G) + d / G],
-                                                    y->v_z[((size_t)bh * cap + t) * (D / G) + d / G]);
-                else
-                    Vh[(size_t)t * D + d] = half_to_double(y->raw_v[e]);
-            }
-        }
+        reconstruct_bh(c, y, (size_t)bh, Kh, Vh);
         const long b = bh / c->Hkv, h = bh % c->Hkv;
         for (int j = 0; j < gq; j++) {
             const size_t row = (size_t)b * c->Hq + (size_t)h * gq + j;   /* q head h*gq+j reads kv head h */
@@ -454,6 +505,7 @@ static void pack_bits(const uint8_t *codes, int n, int bits, uint8_t *dst)
  *   k_codes  kbits<16: [B,Hkv,Np/G,D][G*kbits/8 bytes]  the G tokens of a group, per channel
  *            kbits=16: fp16 [B,Hkv,Np,D]
  *   k_scale, k_zero    fp32 [B,Hkv,Np/G,D]              (kbits<16 only)
+ *            with keys grouped per token: k_codes [B,Hkv,Np][D*kbits/8 bytes], k_scale, k_zero [B,Hkv,Np,D/G]
  *   v_codes  vbits<16: [B,Hkv,Np][D*vbits/8 bytes]      the D channels of a token
  *            vbits=16: fp16 [B,Hkv,Np,D]
  *   v_scale, v_zero    fp32 [B,Hkv,Np,D/G]              (vbits<16 only)
@@ -468,7 +520,16 @@ int kvo_export(const kvo_cache *c, int layer, uint8_t *k_codes, float *k_scale, 
     const size_t Np = (size_t)y->Np, Nr = (size_t)(y->T - y->Np), cap = (size_t)y->cap;
     uint8_t *tmp = malloc(G > D ? G : D);
     for (size_t bh = 0; bh < BH; bh++) {
-        if (y->kbits < 16) {
+        if (y->kbits < 16 && c->key_per_token) {
+            const size_t tb = D * (size_t)y->kbits / 8;
+            for (size_t t = 0; t < Np; t++) {
+                if (k_codes) pack_bits(y->k_code + (bh * cap + t) * D, (int)D, y->kbits, k_codes + (bh * Np + t) * tb);
+                for (size_t j = 0; j < D / G; j++) {
+                    if (k_scale) k_scale[(bh * Np + t) * (D / G) + j] = y->k_s[(bh * cap + t) * (D / G) + j];
+                    if (k_zero) k_zero[(bh * Np + t) * (D / G) + j] = y->k_z[(bh * cap + t) * (D / G) + j];
+                }
+            }
+        } else if (y->kbits < 16) {
             const size_t gb = G * (size_t)y->kbits / 8;
             for (size_t g = 0; g < Np / G; g++)
                 for (size_t d = 0; d < D; d++) {
