@@ -28,6 +28,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
 SCALE_BYTES = 4                 # 2 with --meta fp16 (scales stored and used as fp16)
+KEYS_PER_TOKEN = False          # True with --keys per-token (keys grouped like values)
 
 
 def layer_bytes(w, kb, vb, n_packed, n_res):
@@ -74,7 +75,8 @@ def build_cache(torch, pkg, W, w, extra_tokens, variant=0, splits=0):
     dev = "cuda:0"
     cache = pkg.KVQ(w.n_layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.context + extra_tokens, w.kbits,
                     w.vbits, group=w.group, residual=w.residual, device=dev,
-                    meta_dtype=pkg.META_FP16 if SCALE_BYTES == 2 else pkg.META_FP32)
+                    meta_dtype=pkg.META_FP16 if SCALE_BYTES == 2 else pkg.META_FP32,
+                    key_mode=pkg.KEYS_PER_TOKEN if KEYS_PER_TOKEN else pkg.KEYS_PER_CHANNEL)
     cache.set_decode_options(variant, splits)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     q_ms = 0.0
@@ -217,7 +219,7 @@ def cpu_baseline(W, w, budget_s=20.0):
     for (kb, vb), layers in pairs.items():
         layer = layers[0]
         oc = oracle.OracleCache(1, b_s, w.n_q_heads, w.n_kv_heads, w.head_dim, [kb], [vb], group=w.group, residual=w.residual,
-                                scale_fp16=SCALE_BYTES == 2)
+                                scale_fp16=SCALE_BYTES == 2, key_per_token=KEYS_PER_TOKEN)
         K, V = W.kv_tokens(ws, layer, 0, w.context)
         oc.quantize_append(0, K.numpy(), V.numpy())
         kn, vn = W.kv_tokens(ws, layer, 0, 1, stream=1, total=1)
@@ -264,6 +266,8 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--meta", choices=["fp32", "fp16"], default="fp32",
                     help="precision of the stored scales (fp16 = the narrow-metadata variant; zero-points are exact either way)")
+    ap.add_argument("--keys", choices=["per-channel", "per-token"], default="per-channel",
+                    help="key grouping: per channel over 32 tokens (KIVI mode, default) or per token over 32 channels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv8", action="store_true")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
@@ -281,8 +285,9 @@ def main():
     import kvq_workloads as W
     import paper_2502_04420_amd as pkg
 
-    global SCALE_BYTES
+    global SCALE_BYTES, KEYS_PER_TOKEN
     SCALE_BYTES = 2 if args.meta == "fp16" else 4
+    KEYS_PER_TOKEN = args.keys == "per-token"
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
@@ -320,7 +325,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "decode_mfma<%s> (%d of %d layers)" % (dom, counts[dom], w_main.n_layers),
         "achieved": pk["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": pk["kernel_gbps"] / HBM_PEAK_GBPS,
-        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "")),
+        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else "")),
         "whole_call_ms": pk["call_ms"], "whole_call_frac": pk["call_gbps"] / HBM_PEAK_GBPS,
     }
     from paper_2502_04420_amd import equivalent_precision
@@ -336,7 +341,7 @@ def main():
         "config": {"workload": w_main.name, "layers": w_main.n_layers, "batch": w_main.batch, "q_heads": w_main.n_q_heads,
                    "kv_heads": w_main.n_kv_heads, "head_dim": w_main.head_dim, "context": w_main.context,
                    "equivalent_bits": equivalent_precision(w_main.kbits, w_main.vbits), "group": 32, "residual": 32,
-                   "scales": args.meta, "zero_points": "fp16 (exact)",
+                   "scales": args.meta, "zero_points": "fp16 (exact)", "key_grouping": args.keys,
                    "step": "per layer: append 1 token (+ flush of 32 every 32 steps) + fused decode attention"},
         "hbm_gbps": main_res["algorithmic_gbps"], "hbm_frac_of_peak": main_res["algorithmic_gbps"] / HBM_PEAK_GBPS,
         "step_bytes": main_res["step_bytes"], "gpu_ms_per_step": main_res["gpu_ms_per_step"],

@@ -56,6 +56,20 @@ typedef struct kvq_ctx kvq_ctx;
  *     rounds to zero encodes its group as all-zero codes.  Saves 8 bytes per token and tensor.
  * kvq_debug_export returns fp32 scales in both cases (exactly the values in use).
  */
+/*
+ * Axis along which the keys are grouped for Eq. 2 (values are always grouped per token over G
+ * channels).  The paper evaluates both (Section 3.2 and its table of per-channel vs per-token
+ * errors):
+ *   KVQ_KEYS_PER_CHANNEL: one (s, z) per channel over G consecutive tokens -- the KIVI mode
+ *     of the paper's experiments.  The default.
+ *   KVQ_KEYS_PER_TOKEN: one (s, z) per token over each group of G channels, exactly like the
+ *     values -- the paper's "per-token-asym" mode (same group size and window rule here).
+ */
+typedef enum kvq_key_mode {
+    KVQ_KEYS_PER_CHANNEL = 0,
+    KVQ_KEYS_PER_TOKEN = 1
+} kvq_key_mode;
+
 typedef enum kvq_meta_dtype {
     KVQ_META_FP32 = 0,
     KVQ_META_FP16 = 1
@@ -77,6 +91,7 @@ typedef struct kvq_config {
     const uint8_t *kbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
     const uint8_t *vbits;  /* host, [n_layers], each in {2, 4, 8, 16}                            */
     int32_t meta_dtype;    /* a kvq_meta_dtype: precision of the stored scales (see there)       */
+    int32_t key_mode;      /* a kvq_key_mode: axis along which keys are grouped (see there)      */
 } kvq_config;
 
 /* Bytes of device workspace kvq_configure needs for this configuration; 0 if it is invalid. */
@@ -126,6 +141,8 @@ int kvq_reset(kvq_ctx *ctx, int32_t layer);
  *             a token group packed little-endian (token i at bits [i*kbits, (i+1)*kbits));
  *             kbits = 16: fp16 [B, H, N_p, D].
  *   k_scale, k_zero : fp32 [B, H, N_p/G, D]   (s and z of Eq. 2; untouched when kbits = 16)
+ *             With KVQ_KEYS_PER_TOKEN the three key arrays take the value arrays' form:
+ *             k_codes uint8 [B, H, N_p, D*kbits/8], k_scale, k_zero fp32 [B, H, N_p, D/G].
  *   v_codes : vbits < 16: uint8 [B, H, N_p, D*vbits/8] -- per token, the D codes packed
  *             little-endian; vbits = 16: fp16 [B, H, N_p, D].
  *   v_scale, v_zero : fp32 [B, H, N_p, D/G]   (untouched when vbits = 16)

@@ -5,5 +5,6 @@ The work is done by hand-written HIP kernels behind the C ABI of ``include/kvq.h
 Python binding with the same call names.  There is no CPU fallback: using the binding
 without the built library raises.
 """
-from .binding import KVQ, KVQError, META_FP16, META_FP32, library_path, load_library  # noqa: F401
+from .binding import (KEYS_PER_CHANNEL, KEYS_PER_TOKEN, KVQ, KVQError, META_FP16, META_FP32, library_path,  # noqa: F401
+                      load_library)
 from .schedule import equivalent_precision, bytes_per_token, parse_pairs  # noqa: F401

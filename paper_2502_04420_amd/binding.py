@@ -30,7 +30,7 @@ class KVQError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [("n_layers", c_int32), ("batch", c_int32), ("n_q_heads", c_int32), ("n_kv_heads", c_int32),
                 ("head_dim", c_int32), ("max_tokens", c_int32), ("group", c_int32), ("residual", c_int32),
-                ("kbits", POINTER(c_uint8)), ("vbits", POINTER(c_uint8)), ("meta_dtype", c_int32)]
+                ("kbits", POINTER(c_uint8)), ("vbits", POINTER(c_uint8)), ("meta_dtype", c_int32), ("key_mode", c_int32)]
 
 
 def library_path() -> str:
@@ -83,15 +83,16 @@ def _check(status: int):
 
 
 META_FP32, META_FP16 = 0, 1
+KEYS_PER_CHANNEL, KEYS_PER_TOKEN = 0, 1
 
 
 def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, kbits, vbits, group=32, residual=32,
-                meta_dtype=META_FP32):
+                meta_dtype=META_FP32, key_mode=KEYS_PER_CHANNEL):
     """Returns (_Config, keepalive) -- the byte arrays must outlive the struct."""
     kb = (c_uint8 * len(kbits))(*kbits)
     vb = (c_uint8 * len(vbits))(*vbits)
     cfg = _Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, group, residual,
-                  ctypes.cast(kb, POINTER(c_uint8)), ctypes.cast(vb, POINTER(c_uint8)), meta_dtype)
+                  ctypes.cast(kb, POINTER(c_uint8)), ctypes.cast(vb, POINTER(c_uint8)), meta_dtype, key_mode)
     return cfg, (kb, vb)
 
 
@@ -105,7 +106,7 @@ class KVQ:
 
     def __init__(self, n_layers: int, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, max_tokens: int,
                  kbits: Sequence[int], vbits: Sequence[int], group: int = 32, residual: int = 32,
-                 device="cuda:0", stream=None, meta_dtype: int = META_FP32):
+                 device="cuda:0", stream=None, meta_dtype: int = META_FP32, key_mode: int = KEYS_PER_CHANNEL):
         import torch
 
         self._torch = torch
@@ -117,8 +118,8 @@ class KVQ:
         self.kbits, self.vbits = list(kbits), list(vbits)
         self.device = torch.device(device)
         cfg, self._keep = make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, max_tokens, self.kbits,
-                                      self.vbits, group, residual, meta_dtype)
-        self.meta_dtype = meta_dtype
+                                      self.vbits, group, residual, meta_dtype, key_mode)
+        self.meta_dtype, self.key_mode = meta_dtype, key_mode
         need = int(self._lib.kvq_workspace_bytes(ctypes.byref(cfg)))
         if need == 0:
             raise KVQError(-1, "configuration rejected by kvq_workspace_bytes")
@@ -202,7 +203,11 @@ class KVQ:
         def z(shape, dtype):
             return torch.zeros(shape, dtype=dtype, device=dev)
 
-        if kb < 16:
+        if kb < 16 and self.key_mode == KEYS_PER_TOKEN:
+            r["k_codes"] = z((B, H, npk, D * kb // 8), torch.uint8)
+            r["k_scale"] = z((B, H, npk, D // G), torch.float32)
+            r["k_zero"] = z((B, H, npk, D // G), torch.float32)
+        elif kb < 16:
             r["k_codes"] = z((B, H, npk // G, D, G * kb // 8), torch.uint8)
             r["k_scale"] = z((B, H, npk // G, D), torch.float32)
             r["k_zero"] = z((B, H, npk // G, D), torch.float32)

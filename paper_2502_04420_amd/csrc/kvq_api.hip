@@ -35,6 +35,7 @@ bool config_ok(const kvq_config *c)
     for (int l = 0; l < c->n_layers; l++)
         if (!bits_ok(c->kbits[l]) || !bits_ok(c->vbits[l])) return false;
     if (c->meta_dtype != KVQ_META_FP32 && c->meta_dtype != KVQ_META_FP16) return false;
+    if (c->key_mode != KVQ_KEYS_PER_CHANNEL && c->key_mode != KVQ_KEYS_PER_TOKEN) return false;
     return true;
 }
 
@@ -111,6 +112,7 @@ kvq::LayerView view(const kvq_ctx *c, int l)
     v.kbits = c->kbits[l];
     v.vbits = c->vbits[l];
     v.narrow = c->cfg.meta_dtype == KVQ_META_FP16 ? 1 : 0;
+    v.kpt = c->cfg.key_mode == KVQ_KEYS_PER_TOKEN ? 1 : 0;
     return v;
 }
 

@@ -177,7 +177,8 @@ template <int GQ>
 struct __attribute__((aligned(16))) PairLds {
     _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]
     _Float16 Av[4][16][32 + 8];    // value wave: output A tiles [channel group][row][token]
-    _Float16 Zk[kD];               // key wave: key zero-points (fp16 as stored)
+    _Float16 Zk[kD];               // key wave: key zero-points (fp16 as stored); per-token keys: 32 floats of query sums
+    float Mk[2][kD];               // key wave, per-token keys: the block's scales and zero-points as [group][token] floats
     float P[2][8][32];             // hand-off: softmax numerators of a block per head, double-buffered
     float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
     int rescale[2][2];             // hand-off: non-zero when alpha is not all ones (padded to 16 bytes)
@@ -189,6 +190,8 @@ struct QueryRegs {
     const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows 2j and 2j + 1 = head j)
     float c, alpha_h;              // log2(e)/sqrt(D); weight of the partial scores
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
+    float kappa;                   // per-token keys: weight of the partial score sums
+    float qs[2][4];                // per-token keys: c * sum of q over channel group g, heads 2*rq, 2*rq + 1
 };
 
 template <int GQ>
@@ -242,6 +245,38 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
         s[0][hh] = fmaf(ah, S0[2 * hh] + S0[2 * hh + 1], zc);
         s[1][hh] = fmaf(ah, S1[2 * hh] + S1[2 * hh + 1], zc);
     }
+}
+
+// Scores of a quantized block whose keys are grouped per token (one (s, z) per token and 32-channel group):
+//   sum_d q_d (c_td s_tg + z_tg) = sum_g [ s_tg * sum_{d in g} q_d c_td  +  z_tg * sum_{d in g} q_d ].
+// A channel group is exactly the depth of one MFMA, so each MFMA yields one inner sum per (head, token); the
+// scale is applied to its result.  The A tile holds the exact fp16 queries (times a power of two and the code
+// position weight; rows 2j, the odd rows are not used) and is built once per kernel.
+template <int KB, int GQ, bool NARROW>
+__device__ __forceinline__ void scores_packed_per_token(const CodeRegs<KB> &blk, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
+                                                        float (&s)[2][2])
+{
+    const int n = lane & 15, rq = lane >> 4;
+    const float2 sc = scales_of<NARROW>(blk);
+    *reinterpret_cast<float2 *>(&L.Mk[0][2 * lane]) = make_float2(sc.x * Q.kappa, sc.y * Q.kappa);
+    *reinterpret_cast<float2 *>(&L.Mk[1][2 * lane]) = make_float2(half_lo(blk.z), half_hi(blk.z));
+    wave_lds_sync();
+    s[0][0] = s[0][1] = s[1][0] = s[1][1] = 0.0f;
+    const float4v zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int cb = 0; cb < 4; cb++) {
+        const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
+        const float4v D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb), zero, 0, 0, 0);
+        const float4v D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb), zero, 0, 0, 0);
+        const float s0 = L.Mk[0][32 * cb + n], s1 = L.Mk[0][32 * cb + 16 + n];
+        const float z0 = L.Mk[1][32 * cb + n], z1 = L.Mk[1][32 * cb + 16 + n];
+#pragma unroll
+        for (int hh = 0; hh < 2; hh++) {
+            s[0][hh] = fmaf(s0, D0[2 * hh], fmaf(z0, Q.qs[hh][cb], s[0][hh]));
+            s[1][hh] = fmaf(s1, D1[2 * hh], fmaf(z1, Q.qs[hh][cb], s[1][hh]));
+        }
+    }
+    wave_lds_sync();          // the metadata tile is rewritten for the next block
 }
 
 // scores of up to 32 fp16 rows (16-bit region or window ring); rows 2j and 2j + 1 of the query tile are equal
@@ -377,7 +412,7 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
 
 // ------------------------------------------------------------------ kernel
 
-template <int KB, int VB, int GQ, bool NARROW>
+template <int KB, int VB, int GQ, bool NARROW, bool KPT>
 __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows 2j and 2j + 1 of a 16-row tile");
@@ -442,14 +477,16 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             }
         }
         {
-            // scaled queries for the q * s operand: divided by a power of two that brings the largest to [0.5, 1)
+            // queries divided by a power of two that brings the largest to [0.5, 1).  Per-channel keys: with the softmax
+            // constant folded in, for the q * s operand.  Per-token keys: the raw fp16 queries, scaled exactly.
+            constexpr bool kPerToken = KPT && KB < 16;
             float qraw[GQ][2];
             float qmax = 0.0f;
 #pragma unroll
             for (int j = 0; j < GQ; j++) {
                 const uint32_t w = qw[j];
-                qraw[j][0] = half_lo(w) * Q.c;
-                qraw[j][1] = half_hi(w) * Q.c;
+                qraw[j][0] = kPerToken ? half_lo(w) : half_lo(w) * Q.c;
+                qraw[j][1] = kPerToken ? half_hi(w) : half_hi(w) * Q.c;
                 qmax = fmaxf(qmax, fmaxf(fabsf(qraw[j][0]), fabsf(qraw[j][1])));
             }
             // maximum over the wave: 16-lane rows by DPP, the 4 rows as unsigned integers (the values are >= 0)
@@ -463,11 +500,32 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             qmax = __builtin_bit_cast(float, qbits);
             int qexp = 0;
             if (qmax > 0.0f) (void)frexpf(qmax, &qexp);      // qmax = f * 2^qexp, f in [0.5, 1)
-            Q.alpha_h = ldexpf(1.0f, CodeShift<KB < 16 ? KB : 8>::value + qexp);   // undo the code position and 2^-qexp of q
+            constexpr int kshift = CodeShift<KB < 16 ? KB : 8>::value;
+            const float w0 = code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7), w1 = code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
+            if constexpr (kPerToken) {
+                // constant A tile: row 2j = q_j * 2^(13 - qexp) / (code position weight), exact in fp16; odd rows unused
+                Q.kappa = Q.c * ldexpf(1.0f, kshift + qexp - 13);
+                float *qs_lds = reinterpret_cast<float *>(&L.Zk[0]);      // [head][group] sums, 4 * GQ <= 32 floats
 #pragma unroll
-            for (int j = 0; j < GQ; j++) {
-                Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane) & 7);
-                Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * code_weight_inv<KB < 16 ? KB : 8>((2 * lane + 1) & 7);
+                for (int j = 0; j < GQ; j++) {
+                    *reinterpret_cast<uint32_t *>(&L.Ak[2 * j][2 * lane]) =
+                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ldexpf(qraw[j][0], 13 - qexp) * w0, ldexpf(qraw[j][1], 13 - qexp) * w1));
+                    *reinterpret_cast<uint32_t *>(&L.Ak[2 * j + 1][2 * lane]) = 0u;
+                    const float part = row_sum16(qraw[j][0] + qraw[j][1]);       // this lane row's channel group is rq
+                    if (n == 0) qs_lds[4 * j + rq] = part * Q.c;
+                }
+                wave_lds_sync();
+#pragma unroll
+                for (int hh = 0; hh < 2; hh++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) Q.qs[hh][g] = 2 * rq + hh < nvalid ? qs_lds[4 * ((2 * rq + hh) % GQ) + g] : 0.0f;
+            } else {
+                Q.alpha_h = ldexpf(1.0f, kshift + qexp);     // undo the code position and 2^-qexp of q
+#pragma unroll
+                for (int j = 0; j < GQ; j++) {
+                    Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * w0;
+                    Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * w1;
+                }
             }
             if constexpr (GQ < 8) {
                 // A-tile rows of heads that do not exist are never written: they must read as zero
@@ -489,7 +547,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
                 for (int d = 0; d < DK; d++) {
                     if (more) {
                         load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + DK - 1), lane, kr[(d + DK - 1) % DK]);
-                        scores_packed<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
+                        if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
+                        else scores_packed<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
                         softmax_publish<GQ>(s, W, L, i & 1, lane);
                         wg_barrier();
                         more = ++i < n1;
@@ -507,7 +566,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
                 k_rows = false;
                 CodeRegs<KB> r;
                 load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
-                scores_packed<KB, GQ, NARROW>(r, Q, L, lane, s);
+                if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(r, Q, L, lane, s);
+                else scores_packed<KB, GQ, NARROW>(r, Q, L, lane, s);
             }
             if (k_rows) {
                 const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
@@ -633,39 +693,48 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     }
 }
 
-template <int KB, int VB, bool NARROW>
+template <int KB, int VB, bool NARROW, bool KPT>
 hipError_t launch_gq(const DecodeArgs &a, hipStream_t s)
 {
     const int gq = a.Hq / a.Hkv;
     const int BH = a.B * a.Hkv;
     const dim3 block(128);
     if (gq <= 4) {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW>), dim3(a.splits, BH, 1), block, 0, s, a);
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW, KPT>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW, KPT>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
     }
     return hipGetLastError();
 }
 
-template <int KB, bool NARROW>
+template <int KB, bool NARROW, bool KPT>
 hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
 {
     switch (a.lv.vbits) {
-    case 2: return launch_gq<KB, 2, NARROW>(a, s);
-    case 4: return launch_gq<KB, 4, NARROW>(a, s);
-    case 8: return launch_gq<KB, 8, NARROW>(a, s);
-    default: return launch_gq<KB, 16, NARROW>(a, s);
+    case 2: return launch_gq<KB, 2, NARROW, KPT>(a, s);
+    case 4: return launch_gq<KB, 4, NARROW, KPT>(a, s);
+    case 8: return launch_gq<KB, 8, NARROW, KPT>(a, s);
+    default: return launch_gq<KB, 16, NARROW, KPT>(a, s);
     }
 }
 
 template <bool NARROW>
 hipError_t launch_kb(const DecodeArgs &a, hipStream_t s)
 {
+    // the key grouping only matters for quantized keys
+    if (a.lv.kpt) {
+        switch (a.lv.kbits) {
+        case 2: return launch_vb<2, NARROW, true>(a, s);
+        case 4: return launch_vb<4, NARROW, true>(a, s);
+        case 8: return launch_vb<8, NARROW, true>(a, s);
+        default: break;
+        }
+    }
     switch (a.lv.kbits) {
-    case 2: return launch_vb<2, NARROW>(a, s);
-    case 4: return launch_vb<4, NARROW>(a, s);
-    case 8: return launch_vb<8, NARROW>(a, s);
-    default: return launch_vb<16, NARROW>(a, s);
+    case 2: return launch_vb<2, NARROW, false>(a, s);
+    case 4: return launch_vb<4, NARROW, false>(a, s);
+    case 8: return launch_vb<8, NARROW, false>(a, s);
+    default: return launch_vb<16, NARROW, false>(a, s);
     }
 }
 

@@ -113,10 +113,21 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 *reinterpret_cast<float4 *>(&s8[4]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][ch0 + 4]);
                 *reinterpret_cast<float4 *>(&z8[0]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][kD + ch0]);
                 *reinterpret_cast<float4 *>(&z8[4]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][kD + ch0 + 4]);
+                if (a.lv.kpt) {
+                    // keys grouped per token: one (s, z) per token and 32-channel group cb, stored at [group][token]
+                    const float s0 = kmeta_lds[wave][32 * cb + n], s1 = kmeta_lds[wave][32 * cb + 16 + n];
+                    const float z0 = kmeta_lds[wave][kD + 32 * cb + n], z1 = kmeta_lds[wave][kD + 32 * cb + 16 + n];
 #pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    k0[e] = fmaf(code_as_float<KB>(dw, 8 * cb + e), s8[e], z8[e]);
-                    k1[e] = fmaf(code_as_float<KB>(dw, 8 * (4 + cb) + e), s8[e], z8[e]);
+                    for (int e = 0; e < 8; e++) {
+                        k0[e] = fmaf(code_as_float<KB>(dw, 8 * cb + e), s0, z0);
+                        k1[e] = fmaf(code_as_float<KB>(dw, 8 * (4 + cb) + e), s1, z1);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        k0[e] = fmaf(code_as_float<KB>(dw, 8 * cb + e), s8[e], z8[e]);
+                        k1[e] = fmaf(code_as_float<KB>(dw, 8 * (4 + cb) + e), s8[e], z8[e]);
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < GQ; j++) {

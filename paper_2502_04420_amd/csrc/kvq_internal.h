@@ -18,6 +18,7 @@ struct LayerView {
     uint16_t *vres;
     int kbits, vbits;
     int narrow;           // 1: scales stored (and used) as fp16
+    int kpt;              // 1: keys grouped per token over 32 channels (metadata laid out like the values')
 };
 
 struct QuantArgs {

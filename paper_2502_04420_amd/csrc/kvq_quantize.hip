@@ -199,30 +199,53 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 *reinterpret_cast<uint4 *>(dst + (r + 4 * i) * (kD * 2) + c16 * 16) = make_uint4(x[i][0], x[i][1], x[i][2], x[i][3]);
             if (lane == 0) bexp16[0] = 32768;
         } else {
-            // min / max per channel over the lane's 8 tokens, then across the 4 lane rows by shuffles
-            uint32_t mnp[4], mxp[4];
-#pragma unroll
-            for (int p = 0; p < 4; p++) { mnp[p] = x[0][p]; mxp[p] = x[0][p]; }
-#pragma unroll
-            for (int i = 1; i < 8; i++)
-#pragma unroll
-                for (int p = 0; p < 4; p++) { mnp[p] = pk_min(mnp[p], x[i][p]); mxp[p] = pk_max(mxp[p], x[i][p]); }
-#pragma unroll
-            for (int p = 0; p < 4; p++) {
-                mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
-                mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
-            }
+            const bool kpt = a.lv.kpt != 0;                  // keys grouped per token over 32 channels, like the values
             float *meta = a.lv.kmeta + blk_index * meta_words(NARROW);
             float s_max = 0.0f;
+            if (!kpt) {
+                // min / max per channel over the lane's 8 tokens, then across the 4 lane rows by shuffles
+                uint32_t mnp[4], mxp[4];
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const uint32_t mnb = (mnp[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mxp[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
-                s_max = fmaxf(s_max, s);
-                if (r == 0) {
-                    sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn; rsc[8 * c16 + e] = recip_or_zero(s);
-                    store_scale<NARROW>(meta, 8 * c16 + e, s); meta_zeros(meta, NARROW)[8 * c16 + e] = (uint16_t)mnb;
+                for (int p = 0; p < 4; p++) { mnp[p] = x[0][p]; mxp[p] = x[0][p]; }
+#pragma unroll
+                for (int i = 1; i < 8; i++)
+#pragma unroll
+                    for (int p = 0; p < 4; p++) { mnp[p] = pk_min(mnp[p], x[i][p]); mxp[p] = pk_max(mxp[p], x[i][p]); }
+#pragma unroll
+                for (int p = 0; p < 4; p++) {
+                    mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
+                    mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
+                }
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t mnb = (mnp[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                    const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mxp[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                    const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
+                    s_max = fmaxf(s_max, s);
+                    if (r == 0) {
+                        sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn; rsc[8 * c16 + e] = recip_or_zero(s);
+                        store_scale<NARROW>(meta, 8 * c16 + e, s); meta_zeros(meta, NARROW)[8 * c16 + e] = (uint16_t)mnb;
+                    }
+                }
+            } else {
+                // min / max per token over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd;
+                // metadata index 32*gd + token, as for values
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    const int t = r + 4 * i;
+                    uint32_t mnp = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
+                    uint32_t mxp = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
+                    mnp = pk_min(mnp, __shfl_xor(mnp, 1)); mxp = pk_max(mxp, __shfl_xor(mxp, 1));
+                    mnp = pk_min(mnp, __shfl_xor(mnp, 2)); mxp = pk_max(mxp, __shfl_xor(mxp, 2));
+                    const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
+                    const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
+                    const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
+                    s_max = fmaxf(s_max, s);
+                    if ((c16 & 3) == 0) {
+                        const int gd = c16 >> 2;
+                        sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
+                        store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
+                    }
                 }
             }
 #pragma unroll
@@ -239,7 +262,13 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[token * (kD + 8) + ch0]);
                 const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
                 float s8[8], z8[8], r8[8], c8[8];
-                load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
+                if (!kpt) {
+                    load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
+                } else {
+                    const int gi = 32 * (m & 3) + token;          // one (s, z) for the 8 channels of this token and group
+#pragma unroll
+                    for (int e = 0; e < 8; e++) { s8[e] = sc[gi]; z8[e] = zp[gi]; r8[e] = rsc[gi]; }
+                }
                 encode8<KB, NARROW>(xw, s8, z8, r8, c8);
                 pack8<KB>(c8, m, dw);
             }
@@ -341,6 +370,27 @@ __device__ __forceinline__ uint32_t fetch_code_rt(int bits, const uint8_t *block
     return bits == 8 ? fetch_code<8>(block, lane, ci) : bits == 4 ? fetch_code<4>(block, lane, ci) : fetch_code<2>(block, lane, ci);
 }
 
+// keys grouped per token: one thread per canonical output byte [bh][token][byte], the 128 channels of a token
+__global__ void export_key_codes_per_token(ExportArgs a)
+{
+    const int kb = a.lv.kbits;
+    const int tbytes = kD * kb / 8, per_byte = 8 / kb;
+    const long long total = (long long)a.BH * a.n_packed * tbytes;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int by = (int)(idx % tbytes);
+    const int tok = (int)((idx / tbytes) % a.n_packed);
+    const int bh = (int)(idx / ((long long)tbytes * a.n_packed));
+    const uint8_t *block = a.lv.kcode + ((size_t)bh * a.NB + tok / kG) * block_code_bytes(kb);
+    const int t = tok % kG;
+    uint32_t v = 0;
+    for (int j = 0; j < per_byte; j++) {
+        const int d = by * per_byte + j;
+        v |= fetch_code_rt(kb, block, key_lane(t, d), key_ci(t, d)) << (j * kb);
+    }
+    a.k_codes[idx] = (uint8_t)v;
+}
+
 // keys: one thread per canonical output byte [bh][g][d][byte]
 __global__ void export_key_codes(ExportArgs a)
 {
@@ -395,8 +445,8 @@ __global__ void export_meta(ExportArgs a, int which)   // 0 = keys, 1 = values
     const bool narrow = a.lv.narrow != 0;
     const float *meta = (which == 0 ? a.lv.kmeta : a.lv.vmeta) + ((size_t)bh * a.NB + g) * meta_words(narrow);
     float *so = which == 0 ? a.k_scale : a.v_scale, *zo = which == 0 ? a.k_zero : a.v_zero;
-    // canonical value metadata is [token][group]; the device keeps [group][token]
-    const int src = which == 0 ? within : 32 * (within & 3) + (within >> 2);
+    // canonical value (and per-token key) metadata is [token][group]; the device keeps [group][token]
+    const int src = which == 0 && !a.lv.kpt ? within : 32 * (within & 3) + (within >> 2);
     if (so) so[idx] = narrow ? half_bits_to_float(meta_scales16(meta)[src]) : meta[src];
     if (zo) zo[idx] = half_bits_to_float(meta_zeros(meta, narrow)[src]);
 }
@@ -476,7 +526,8 @@ hipError_t launch_export(const ExportArgs &a, hipStream_t s)
         const long long meta_elems = (long long)a.BH * (a.n_packed / kG) * kD;
         if (a.lv.kbits < 16) {
             if (a.k_codes)
-                hipLaunchKernelGGL(export_key_codes, dim3(blocks_for(meta_elems * (kG * a.lv.kbits / 8), T)), dim3(T), 0, s, a);
+                hipLaunchKernelGGL(a.lv.kpt ? export_key_codes_per_token : export_key_codes,
+                                   dim3(blocks_for(meta_elems * (kG * a.lv.kbits / 8), T)), dim3(T), 0, s, a);
             if (a.k_scale || a.k_zero) hipLaunchKernelGGL(export_meta, dim3(blocks_for(meta_elems, T)), dim3(T), 0, s, a, 0);
         } else if (a.k_codes) {
             hipLaunchKernelGGL(export_rows, dim3(blocks_for((long long)a.BH * a.n_packed * 16, T)), dim3(T), 0, s, a, 0);

@@ -139,6 +139,35 @@ def test_fp16_scale_variant(kvq_mod, oracle_mod, kb, vb, variant):
     assert_outputs_close(out, o16, o64, "meta16 K%dV%d" % (kb, vb))
 
 
+@pytest.mark.parametrize("meta16", [False, True], ids=["fp32scales", "fp16scales"])
+@pytest.mark.parametrize("kb,vb,gq", [(8, 8, 4), (8, 4, 7), (4, 4, 4), (4, 2, 2), (2, 2, 8), (4, 16, 4), (2, 8, 5), (16, 4, 4)])
+def test_per_token_key_grouping(kvq_mod, oracle_mod, kb, vb, gq, meta16, variant):
+    """Keys grouped per token like the values (the paper's per-token-asym mode): canonical export (its key arrays have
+    the value arrays' form) and outputs against the oracle in the same mode; chunked appends, biased keys."""
+    hkv = 2
+    w = W.Workload("kpt", 1, 2, gq * hkv, hkv, 128, 32 * 6 + 27, [kb], [vb], seed=1200 + kb * 17 + vb, outlier_channels=3,
+                   key_bias_std=4.0)
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, hkv, 128, 512, [kb], [vb], key_mode=kvq_mod.KEYS_PER_TOKEN,
+                    meta_dtype=kvq_mod.META_FP16 if meta16 else kvq_mod.META_FP32)
+    g.set_decode_options(variant, 0)
+    o = oracle_mod.OracleCache(1, w.batch, w.n_q_heads, hkv, 128, [kb], [vb], key_per_token=True, scale_fp16=meta16)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    pos = 0
+    for n in (70, 1, 1, 95, w.context - 167):
+        g.quantize_append(0, K[:, :, pos:pos + n].contiguous().cuda(), V[:, :, pos:pos + n].contiguous().cuda())
+        o.quantize_append(0, np.ascontiguousarray(K[:, :, pos:pos + n].numpy()), np.ascontiguousarray(V[:, :, pos:pos + n].numpy()))
+        pos += n
+    gd, od = g.debug_export(0), o.export(0)
+    if kb < 16:
+        assert tuple(gd["k_scale"].shape) == (2, hkv, od["n_packed"], 4)
+    assert_export_equal(gd, od, "per-token keys K%dV%d" % (kb, vb))
+    for step in range(2):
+        q = W.query(w, 0, step)
+        out = g.decode_attention(0, q.cuda())
+        o16, o64 = o.decode_attention(0, q.numpy())
+        assert_outputs_close(out, o16, o64, "per-token keys K%dV%d step %d" % (kb, vb, step))
+
+
 @pytest.mark.parametrize("gq,hkv", [(1, 3), (2, 2), (3, 1), (4, 2), (5, 1), (7, 4), (8, 1), (12, 1), (16, 1)])
 def test_query_group_sizes(kvq_mod, oracle_mod, gq, hkv, variant):
     w = W.Workload("gq", 1, 2, gq * hkv, hkv, 128, 32 * 4 + 7, [4], [2], seed=200 + gq, key_bias_std=20.0)
