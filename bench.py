@@ -80,14 +80,19 @@ def build_cache(torch, pkg, W, w, extra_tokens, variant=0, splits=0):
     cache.set_decode_options(variant, splits)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     q_ms = 0.0
+    # the seeded generator works on 64-bit integers: draw the context in token chunks (multiples of the group) that keep
+    # its temporaries near 2 GiB each, and append chunk by chunk (chunked appends give the same cache as one bulk append)
+    chunk = max(w.group, ((1 << 28) // (w.batch * w.n_kv_heads * w.head_dim)) // w.group * w.group)
     for layer in range(w.n_layers):
-        K, V = W.kv_tokens(w, layer, 0, w.context, device=dev)
-        ev0.record()
-        cache.quantize_append(layer, K, V)
-        ev1.record()
-        torch.cuda.synchronize()
-        q_ms += ev0.elapsed_time(ev1)
-        del K, V
+        for t0 in range(0, w.context, chunk):
+            t1 = min(w.context, t0 + chunk)
+            K, V = W.kv_tokens(w, layer, t0, t1, device=dev)
+            ev0.record()
+            cache.quantize_append(layer, K, V)
+            ev1.record()
+            torch.cuda.synchronize()
+            q_ms += ev0.elapsed_time(ev1)
+            del K, V
     return cache, q_ms
 
 
