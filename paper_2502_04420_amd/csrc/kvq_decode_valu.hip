@@ -44,7 +44,7 @@ __device__ __forceinline__ float code_as_float(const uint32_t *dw, int ci)
     return (float)((dw[code_dword<BITS>(ci)] >> code_shift<BITS>(ci)) & ((1u << BITS) - 1u));
 }
 
-template <int KB, int VB, int GQ>
+template <int KB, int VB, int GQ, bool KPT>
 __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
                 *reinterpret_cast<float4 *>(&s8[4]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][ch0 + 4]);
                 *reinterpret_cast<float4 *>(&z8[0]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][kD + ch0]);
                 *reinterpret_cast<float4 *>(&z8[4]) = *reinterpret_cast<const float4 *>(&kmeta_lds[wave][kD + ch0 + 4]);
-                if (a.lv.kpt) {
+                if constexpr (KPT) {
                     // keys grouped per token: one (s, z) per token and 32-channel group cb, stored at [group][token]
                     const float s0 = kmeta_lds[wave][32 * cb + n], s1 = kmeta_lds[wave][32 * cb + 16 + n];
                     const float z0 = kmeta_lds[wave][kD + 32 * cb + n], z1 = kmeta_lds[wave][kD + 32 * cb + 16 + n];
@@ -337,32 +337,32 @@ __global__ __launch_bounds__(128) void combine_splits(DecodeArgs a)
     a.out[row * kD + d] = __builtin_bit_cast(uint16_t, (_Float16)(O / L));
 }
 
-template <int KB, int VB>
+template <int KB, int VB, bool KPT>
 hipError_t launch_gq(const DecodeArgs &a, hipStream_t s)
 {
     const int gq = a.Hq / a.Hkv;
     const int BH = a.B * a.Hkv;
     const dim3 block(256);
     if (gq == 1) {
-        hipLaunchKernelGGL((decode_valu<KB, VB, 1>), dim3(a.splits, BH, 1), block, 0, s, a);
+        hipLaunchKernelGGL((decode_valu<KB, VB, 1, KPT>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else if (gq == 2) {
-        hipLaunchKernelGGL((decode_valu<KB, VB, 2>), dim3(a.splits, BH, 1), block, 0, s, a);
+        hipLaunchKernelGGL((decode_valu<KB, VB, 2, KPT>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else if (gq <= 4) {
-        hipLaunchKernelGGL((decode_valu<KB, VB, 4>), dim3(a.splits, BH, 1), block, 0, s, a);
+        hipLaunchKernelGGL((decode_valu<KB, VB, 4, KPT>), dim3(a.splits, BH, 1), block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((decode_valu<KB, VB, 8>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
+        hipLaunchKernelGGL((decode_valu<KB, VB, 8, KPT>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
     }
     return hipGetLastError();
 }
 
-template <int KB>
+template <int KB, bool KPT>
 hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
 {
     switch (a.lv.vbits) {
-    case 2: return launch_gq<KB, 2>(a, s);
-    case 4: return launch_gq<KB, 4>(a, s);
-    case 8: return launch_gq<KB, 8>(a, s);
-    default: return launch_gq<KB, 16>(a, s);
+    case 2: return launch_gq<KB, 2, KPT>(a, s);
+    case 4: return launch_gq<KB, 4, KPT>(a, s);
+    case 8: return launch_gq<KB, 8, KPT>(a, s);
+    default: return launch_gq<KB, 16, KPT>(a, s);
     }
 }
 
@@ -371,11 +371,19 @@ hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
 hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s)
 {
     if (a.B * a.Hkv > 65535) return hipErrorInvalidConfiguration;
+    if (a.lv.kpt) {                 // the key grouping only matters for quantized keys
+        switch (a.lv.kbits) {
+        case 2: return launch_vb<2, true>(a, s);
+        case 4: return launch_vb<4, true>(a, s);
+        case 8: return launch_vb<8, true>(a, s);
+        default: break;
+        }
+    }
     switch (a.lv.kbits) {
-    case 2: return launch_vb<2>(a, s);
-    case 4: return launch_vb<4>(a, s);
-    case 8: return launch_vb<8>(a, s);
-    default: return launch_vb<16>(a, s);
+    case 2: return launch_vb<2, false>(a, s);
+    case 4: return launch_vb<4, false>(a, s);
+    case 8: return launch_vb<8, false>(a, s);
+    default: return launch_vb<16, false>(a, s);
     }
 }
 
