@@ -29,6 +29,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 SCALE_BYTES = 4                 # 2 with --meta fp16 (scales stored and used as fp16)
 KEYS_PER_TOKEN = False          # True with --keys per-token (keys grouped like values)
+FUSED_STEP = True               # False with --separate-calls (kvq_quantize_append + kvq_decode_attention per layer)
 
 
 def layer_bytes(w, kb, vb, n_packed, n_res):
@@ -116,6 +117,12 @@ def run_steps(torch, cache, w, qs, ks, vs, outs, s0, s1):
     L = w.n_layers
     for s in range(s0, s1):
         for layer in range(L):
+            if FUSED_STEP:
+                rc = lib.kvq_append_decode_attention(h, layer, c_void_p(ks[layer][s].data_ptr()), c_void_p(vs[layer][s].data_ptr()),
+                                                     c_void_p(qs[layer][s].data_ptr()), c_void_p(outs[layer].data_ptr()))
+                if rc:
+                    raise RuntimeError("kvq_append_decode_attention failed: %d" % rc)
+                continue
             rc = lib.kvq_quantize_append(h, layer, c_void_p(ks[layer][s].data_ptr()), c_void_p(vs[layer][s].data_ptr()), 1)
             if rc:
                 raise RuntimeError("kvq_quantize_append failed: %d" % rc)
@@ -273,6 +280,9 @@ def main():
                     help="precision of the stored scales (fp16 = the narrow-metadata variant; zero-points are exact either way)")
     ap.add_argument("--keys", choices=["per-channel", "per-token"], default="per-channel",
                     help="key grouping: per channel over 32 tokens (KIVI mode, default) or per token over 32 channels")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="per layer and step call kvq_quantize_append and kvq_decode_attention instead of the one-call "
+                         "step kvq_append_decode_attention (same work, one more launch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv8", action="store_true")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
@@ -290,7 +300,8 @@ def main():
     import kvq_workloads as W
     import paper_2502_04420_amd as pkg
 
-    global SCALE_BYTES, KEYS_PER_TOKEN
+    global SCALE_BYTES, KEYS_PER_TOKEN, FUSED_STEP
+    FUSED_STEP = not args.separate_calls
     SCALE_BYTES = 2 if args.meta == "fp16" else 4
     KEYS_PER_TOKEN = args.keys == "per-token"
     if not torch.cuda.is_available():
@@ -347,7 +358,8 @@ def main():
                    "kv_heads": w_main.n_kv_heads, "head_dim": w_main.head_dim, "context": w_main.context,
                    "equivalent_bits": equivalent_precision(w_main.kbits, w_main.vbits), "group": 32, "residual": 32,
                    "scales": args.meta, "zero_points": "fp16 (exact)", "key_grouping": args.keys,
-                   "step": "per layer: append 1 token (+ flush of 32 every 32 steps) + fused decode attention"},
+                   "step": "per layer: append 1 token (+ flush of 32 every 32 steps) + fused decode attention, "
+                           + ("two calls" if args.separate_calls else "one call (kvq_append_decode_attention)")},
         "hbm_gbps": main_res["algorithmic_gbps"], "hbm_frac_of_peak": main_res["algorithmic_gbps"] / HBM_PEAK_GBPS,
         "step_bytes": main_res["step_bytes"], "gpu_ms_per_step": main_res["gpu_ms_per_step"],
         "prefill_quantize_input_gbps": main_res["prefill_quantize_input_gbps"],

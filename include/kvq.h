@@ -127,6 +127,20 @@ int kvq_quantize_append(kvq_ctx *ctx, int32_t layer, const void *k_device, const
  */
 int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void *out_device);
 
+/*
+ * One decode step of a layer in a single call: append exactly one new token per sequence
+ * (k_device, v_device: fp16 [batch, n_kv_heads, 1, head_dim]) and then attend over all tokens,
+ * the new one included (Eq. 1: K is the concatenation of the cached keys and the current one).
+ * Same result and same cache state as kvq_quantize_append(.., 1) followed by
+ * kvq_decode_attention; the difference is that the decode kernel itself takes the new rows
+ * from k_device / v_device and stores them into the fp16 window, which saves the separate
+ * window-copy launch.  k_device / v_device must stay unchanged until the enqueued work has
+ * run (as for every other call).  Errors as for the two calls it replaces; nothing is changed
+ * when KVQ_ECAPACITY is returned.
+ */
+int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_device, const void *v_device,
+                                const void *q_device, void *out_device);
+
 /* Tokens currently held quantized / in fp16 by a layer (host-side bookkeeping, no GPU work). */
 int kvq_layer_tokens(const kvq_ctx *ctx, int32_t layer, int32_t *n_packed, int32_t *n_residual);
 

@@ -15,8 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libkvq.so")
 _lib = None
 
 EXPORTED = [
-    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_layer_tokens",
-    "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
+    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_append_decode_attention",
+    "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
     "kvq_last_error",
 ]
 
@@ -173,6 +173,20 @@ class KVQ:
             out = torch.empty(shape, dtype=torch.float16, device=self.device)
         op = self._dev_ptr(out, shape, torch.float16, "out")
         _check(self._lib.kvq_decode_attention(self._h, layer, qp, op))
+        return out
+
+    def append_decode_attention(self, layer: int, K, V, q, out=None):
+        """One decode step: append one token per sequence (K, V: fp16 [batch, n_kv_heads, 1, head_dim]) and attend."""
+        torch = self._torch
+        kshape = (self.batch, self.n_kv_heads, 1, self.head_dim)
+        kp = self._dev_ptr(K, kshape, torch.float16, "K")
+        vp = self._dev_ptr(V, kshape, torch.float16, "V")
+        shape = (self.batch, self.n_q_heads, self.head_dim)
+        qp = self._dev_ptr(q, shape, torch.float16, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.float16, device=self.device)
+        op = self._dev_ptr(out, shape, torch.float16, "out")
+        _check(self._lib.kvq_append_decode_attention(self._h, layer, kp, vp, qp, op))
         return out
 
     # -- bookkeeping and debugging

@@ -92,6 +92,8 @@ struct kvq_ctx {
 
 namespace {
 
+int decode_variant(const kvq_ctx *c) { return c->variant == 0 ? 2 : c->variant; }     // the matrix-core kernel is the default
+
 int packed_tokens(const kvq_ctx *c, int T)
 {
     const int over = T - c->cfg.residual;
@@ -159,9 +161,12 @@ int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, 
     return KVQ_OK;
 }
 
-int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const void *v_device, int32_t n_tokens)
+namespace {
+
+// Append n_tokens to a layer: quantize the groups that leave the fp16 window, then (unless the caller's decode
+// launch takes the single new token along) copy the tokens that stay in the window into the ring.
+int append_tokens(kvq_ctx *c, int layer, const void *k_device, const void *v_device, int n_tokens, bool copy_window)
 {
-    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_device || !v_device || n_tokens < 1) return KVQ_EINVAL;
     const int t_old = c->tokens[layer];
     if ((int64_t)t_old + n_tokens > c->cfg.max_tokens) return KVQ_ECAPACITY;
     const int t_new = t_old + n_tokens;
@@ -186,7 +191,7 @@ int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const v
     }
     // 2. new tokens that stay in the window go to the ring (after step 1 has read the old slots)
     const int pos0 = np_new > t_old ? np_new : t_old;
-    if (t_new > pos0) {
+    if (copy_window && t_new > pos0) {
         kvq::ResidualCopyArgs a;
         a.lv = view(c, layer);
         a.k_in = static_cast<const uint16_t *>(k_device);
@@ -204,9 +209,10 @@ int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const v
     return KVQ_OK;
 }
 
-int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *out_device)
+// Decode attention over the layer's tokens.  k_new / v_new: rows of a token that append_tokens() left out of the
+// window ring (fused append), or NULL.
+int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, const void *k_new, const void *v_new)
 {
-    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
     const int T = c->tokens[layer];
     if (T < 1) return KVQ_ESTATE;
     const int np = packed_tokens(c, T);
@@ -224,8 +230,11 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     a.NB = c->plan.NB;
     a.RC = c->plan.RC;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
+    a.k_new = static_cast<const uint16_t *>(k_new);
+    a.v_new = static_cast<const uint16_t *>(v_new);
+    a.new_pos = T - 1;
     const int units = a.n_blocks + (a.n_res + 31) / 32;
-    const int variant = c->variant == 0 ? 2 : c->variant;     // the matrix-core kernel is the default
+    const int variant = decode_variant(c);
     int splits = c->splits;
     if (splits <= 0) {
         // 16 waves per compute unit (4 on every SIMD) over 256 compute units: 2048 two-wave groups of the
@@ -250,6 +259,32 @@ int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *
     e = kvq::launch_combine(a, c->stream);
     if (e != hipSuccess) return launch_failed("combine kernel", e);
     return KVQ_OK;
+}
+
+}  // namespace
+
+int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const void *v_device, int32_t n_tokens)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_device || !v_device || n_tokens < 1) return KVQ_EINVAL;
+    return append_tokens(c, layer, k_device, v_device, n_tokens, true);
+}
+
+int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *out_device)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
+    return decode_layer(c, layer, q_device, out_device, nullptr, nullptr);
+}
+
+int kvq_append_decode_attention(kvq_ctx *c, int32_t layer, const void *k_device, const void *v_device, const void *q_device,
+                                void *out_device)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_device || !v_device || !q_device || !out_device) return KVQ_EINVAL;
+    // the matrix-core kernel takes the new token along (if it stays in the fp16 window); otherwise copy it first
+    const int t_new = c->tokens[layer] + 1;
+    const bool fused = decode_variant(c) == 2 && t_new <= c->cfg.max_tokens && t_new > packed_tokens(c, t_new);
+    const int rc = append_tokens(c, layer, k_device, v_device, 1, !fused);
+    if (rc != KVQ_OK) return rc;
+    return decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr);
 }
 
 int kvq_layer_tokens(const kvq_ctx *c, int32_t layer, int32_t *n_packed, int32_t *n_residual)

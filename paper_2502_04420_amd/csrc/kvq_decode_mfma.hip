@@ -393,12 +393,13 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
 
 // output contribution of nt fp16 rows: lane owns channels 2*lane, 2*lane+1
 template <int GQ>
-__device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, ValueState<GQ> &W,
-                                            const PairLds<GQ> &L, int buf, int lane)
+__device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, const uint16_t *new_row, int new_pos,
+                                            ValueState<GQ> &W, const PairLds<GQ> &L, int buf, int lane)
 {
     for (int tt = 0; tt < nt; tt++) {
         const int pos = pos0 + tt;
         const uint16_t *row = base + (size_t)(ring ? pos % ring : pos) * kD;
+        if (new_row && pos == new_pos) row = new_row;          // the token of a fused append is not in the ring yet
         const uint32_t x = *reinterpret_cast<const uint32_t *>(row + 2 * lane);
         const float v0 = half_lo(x), v1 = half_hi(x);
 #pragma unroll
@@ -573,7 +574,16 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
                 const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
                                                : a.lv.kres + (size_t)bh * a.RC * kD;
                 const int p0 = pos0 + n, p1 = pos0 + 16 + n;
-                scores_rows<GQ>(kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD, nt, Q, lane, s);
+                const uint16_t *row0 = kbase + (size_t)(packed ? p0 : p0 % a.RC) * kD, *row1 = kbase + (size_t)(packed ? p1 : p1 % a.RC) * kD;
+                if (!packed && a.k_new && a.new_pos >= pos0 && a.new_pos < pos0 + nt) {
+                    // fused append: this chunk holds the new token.  Read its row from the caller's tensor and
+                    // put it into the window ring for later launches (nothing reads that slot in this launch).
+                    const uint16_t *src = a.k_new + (size_t)bh * kD;
+                    if (p0 == a.new_pos) row0 = src;
+                    if (p1 == a.new_pos) row1 = src;
+                    reinterpret_cast<uint32_t *>(a.lv.kres + ((size_t)bh * a.RC + a.new_pos % a.RC) * kD)[lane] = reinterpret_cast<const uint32_t *>(src)[lane];
+                }
+                scores_rows<GQ>(row0, row1, nt, Q, lane, s);
             }
             softmax_publish<GQ>(s, W, L, (n1 + i) & 1, lane);
             wg_barrier();
@@ -659,7 +669,12 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             if (v_rows) {
                 const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD
                                                : a.lv.vres + (size_t)bh * a.RC * kD;
-                output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, W, L, buf, lane);
+                const uint16_t *new_row = nullptr;
+                if (!packed && a.v_new && a.new_pos >= pos0 && a.new_pos < pos0 + nt) {
+                    new_row = a.v_new + (size_t)bh * kD;
+                    reinterpret_cast<uint32_t *>(a.lv.vres + ((size_t)bh * a.RC + a.new_pos % a.RC) * kD)[lane] = reinterpret_cast<const uint32_t *>(new_row)[lane];
+                }
+                output_rows<GQ>(vbase, pos0, nt, packed ? 0 : a.RC, new_row, a.new_pos, W, L, buf, lane);
             }
             wg_barrier();
         }

@@ -63,6 +63,10 @@ struct DecodeArgs {
     int splits;            // gridDim.x
     int units_per_split;   // work units (blocks, then chunks of <= 32 fp16 tokens) per split
     float scale_log2e;     // log2(e) / sqrt(D)
+    // fused append of one token per sequence (matrix-core kernel only): its fp16 rows [B*Hkv][128], not yet in the
+    // window ring; the kernel reads them from here and stores them into the ring for later launches.  NULL: none.
+    const uint16_t *k_new, *v_new;
+    int new_pos;           // absolute position of that token
 };
 
 hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);

@@ -322,6 +322,39 @@ def test_quotients_next_to_ties_are_coded_identically(kvq_mod, oracle_mod):
         assert_export_equal(g.debug_export(0), o.export(0), "near ties %d bit" % bits)
 
 
+@pytest.mark.parametrize("residual", [0, 32, 64])
+@pytest.mark.parametrize("kb,vb", [(4, 2), (8, 8), (16, 4), (2, 16)])
+def test_fused_append_decode_step(kvq_mod, oracle_mod, kb, vb, residual, variant):
+    """kvq_append_decode_attention over 70 decode steps (window flushes included) against the oracle's append + decode,
+    and bit for bit against the two separate calls on a second cache; the cache state at the end is compared too."""
+    w = W.Workload("fused", 1, 2, 8, 2, 128, 32 * 3 + 5, [kb], [vb], seed=1500 + kb * 17 + vb + residual, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 256, residual=residual, variant=variant)
+    g2, _ = _pair(kvq_mod, oracle_mod, w, 256, residual=residual, variant=variant)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    for c in (g, g2):
+        c.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    steps = 70
+    Kn, Vn = W.kv_tokens(w, 0, 0, steps, stream=1, total=steps)
+    for s_ in range(steps):
+        k1, v1 = Kn[:, :, s_:s_ + 1].contiguous(), Vn[:, :, s_:s_ + 1].contiguous()
+        q = W.query(w, 0, s_)
+        out = g.append_decode_attention(0, k1.cuda(), v1.cuda(), q.cuda())
+        g2.quantize_append(0, k1.cuda(), v1.cuda())
+        out2 = g2.decode_attention(0, q.cuda())
+        assert torch.equal(out, out2), "step %d: fused call differs from append + decode" % s_
+        o.quantize_append(0, k1.numpy(), v1.numpy())
+        if s_ % 7 == 0 or s_ == steps - 1:
+            o16, o64 = o.decode_attention(0, q.numpy())
+            assert_outputs_close(out, o16, o64, "fused step %d" % s_)
+    assert g.layer_tokens(0) == g2.layer_tokens(0) == o.tokens(0)
+    assert_export_equal(g.debug_export(0), o.export(0), "after fused steps")
+    with pytest.raises(kvq_mod.KVQError):            # capacity: 101 + 70 = 171 tokens held, 256 allowed
+        for _ in range(100):
+            g.append_decode_attention(0, k1.cuda(), v1.cuda(), q.cuda())
+    assert g.layer_tokens(0)[0] + g.layer_tokens(0)[1] == 256
+
+
 def test_sixteen_bit_mode_equals_exact_attention(kvq_mod, oracle_mod, variant):
     w = W.Workload("fp16", 1, 2, 8, 2, 128, 300, [16], [16], seed=700)
     g, _ = _pair(kvq_mod, oracle_mod, w, 512, variant=variant)

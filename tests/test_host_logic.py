@@ -81,6 +81,8 @@ def test_configure_and_call_errors_without_gpu(lib):
         assert lib.kvq_quantize_append(h, 0, fake, fake, 0) == -1
         assert lib.kvq_quantize_append(h, 0, fake, None, 1) == -1
         assert lib.kvq_quantize_append(h, 0, fake, fake, 257) == -2      # beyond max_tokens
+        assert lib.kvq_append_decode_attention(h, 0, fake, fake, None, fake) == -1
+        assert lib.kvq_append_decode_attention(h, 7, fake, fake, fake, fake) == -1
         a, b = ctypes.c_int32(-1), ctypes.c_int32(-1)
         assert lib.kvq_layer_tokens(h, 1, ctypes.byref(a), ctypes.byref(b)) == 0 and (a.value, b.value) == (0, 0)
         assert lib.kvq_layer_tokens(h, 5, ctypes.byref(a), ctypes.byref(b)) == -1
