@@ -303,23 +303,26 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
 }
 
 // Merge the splits of one (batch, query head) by log-sum-exp and store fp16 (round to nearest even).
-// The partial records are fetched eight at a time with independent loads: a plain loop would pay one
-// memory latency per split.
-__global__ __launch_bounds__(128) void combine_splits(DecodeArgs a)
+// 512 threads: thread = (quarter g, channel d).  Quarter g merges the splits g, g + 4, g + 8, .., fetching
+// eight partial records at a time with independent loads (a plain loop would pay one memory latency per
+// split); the four quarter results are merged through LDS.  The order of all sums is fixed.
+__global__ __launch_bounds__(512) void combine_splits(DecodeArgs a)
 {
     const size_t row = blockIdx.x;
-    const int d = threadIdx.x;
+    const int d = threadIdx.x & 127, g = threadIdx.x >> 7;
     const float *ml = a.part_ml + row * a.splits * 2;
     const float *po = a.part_o + row * a.splits * kD + d;
+    __shared__ float Mq[4], Lq[4], Oq[4][kD];
     float M = -INFINITY, L = 0.0f, O = 0.0f;
-    for (int s0 = 0; s0 < a.splits; s0 += 8) {
+    for (int s0 = g; s0 < a.splits; s0 += 32) {
         float m8[8], l8[8], o8[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-            const bool ok = s0 + k < a.splits;
-            m8[k] = ok ? ml[(s0 + k) * 2] : -INFINITY;
-            l8[k] = ok ? ml[(s0 + k) * 2 + 1] : 0.0f;
-            o8[k] = ok ? po[(size_t)(s0 + k) * kD] : 0.0f;
+            const int sp = s0 + 4 * k;
+            const bool ok = sp < a.splits;
+            m8[k] = ok ? ml[sp * 2] : -INFINITY;
+            l8[k] = ok ? ml[sp * 2 + 1] : 0.0f;
+            o8[k] = ok ? po[(size_t)sp * kD] : 0.0f;
         }
         float Mn = M;
 #pragma unroll
@@ -328,13 +331,26 @@ __global__ __launch_bounds__(128) void combine_splits(DecodeArgs a)
         L *= fo; O *= fo;
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-            const float f = exp2f(m8[k] - Mn);
+            const float f = exp2f(m8[k] - Mn);   // an absent split has m = -inf: factor 0
             L = fmaf(l8[k], f, L);
             O = fmaf(o8[k], f, O);
         }
         M = Mn;
     }
-    a.out[row * kD + d] = __builtin_bit_cast(uint16_t, (_Float16)(O / L));
+    Oq[g][d] = O;
+    if (d == 0) { Mq[g] = M; Lq[g] = L; }
+    __syncthreads();
+    if (g == 0) {
+        const float Mt = fmaxf(fmaxf(Mq[0], Mq[1]), fmaxf(Mq[2], Mq[3]));      // quarter 0 always holds split 0: finite
+        float Lt = 0.0f, Ot = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const float f = exp2f(Mq[k] - Mt);   // an empty quarter has M = -inf: factor 0
+            Lt = fmaf(Lq[k], f, Lt);
+            Ot = fmaf(Oq[k][d], f, Ot);
+        }
+        a.out[row * kD + d] = __builtin_bit_cast(uint16_t, (_Float16)(Ot / Lt));
+    }
 }
 
 template <int KB, int VB, bool KPT>
@@ -389,7 +405,7 @@ hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s)
 
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(combine_splits, dim3(a.B * a.Hq), dim3(128), 0, s, a);
+    hipLaunchKernelGGL(combine_splits, dim3(a.B * a.Hq), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
