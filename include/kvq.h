@@ -81,7 +81,7 @@ typedef enum kvq_meta_dtype {
  */
 typedef struct kvq_config {
     int32_t n_layers;      /* L >= 1                                                             */
-    int32_t batch;         /* sequences, >= 1                                                    */
+    int32_t batch;         /* sequences, >= 1; batch * n_kv_heads <= 65535                       */
     int32_t n_q_heads;     /* multiple of n_kv_heads (grouped-query attention)                   */
     int32_t n_kv_heads;    /* >= 1                                                               */
     int32_t head_dim;      /* D of Eq. 1 (per head); this build supports 128                     */

@@ -32,6 +32,7 @@ bool config_ok(const kvq_config *c)
     if (c->head_dim != kvq::kD || c->group != kvq::kG) return false;
     if (c->max_tokens < 1 || c->residual < 0 || c->residual > (1 << 20)) return false;
     if ((int64_t)c->batch * c->n_q_heads > (1 << 24)) return false;
+    if ((int64_t)c->batch * c->n_kv_heads > 65535) return false;        // one grid row per (batch, kv head)
     for (int l = 0; l < c->n_layers; l++)
         if (!bits_ok(c->kbits[l]) || !bits_ok(c->vbits[l])) return false;
     if (c->meta_dtype != KVQ_META_FP32 && c->meta_dtype != KVQ_META_FP16) return false;

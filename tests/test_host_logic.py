@@ -54,7 +54,7 @@ def test_workspace_bytes_and_config_validation(lib):
     need16 = lib.kvq_workspace_bytes(ctypes.byref(c16))
     assert 0 < need16 < need and need - need16 >= 4 * 8 * 4 * 256
     for bad in (dict(head_dim=64), dict(group=16), dict(n_q_heads=7), dict(kbits=[8, 3]), dict(vbits=[1, 2]),
-                dict(max_tokens=0), dict(batch=0), dict(residual=-1), dict(meta_dtype=2)):
+                dict(max_tokens=0), dict(batch=0), dict(residual=-1), dict(meta_dtype=2), dict(key_mode=2), dict(batch=32768)):
         c, k = _cfg(**bad)
         assert lib.kvq_workspace_bytes(ctypes.byref(c)) == 0, bad
         h = ctypes.c_void_p()
