@@ -109,14 +109,24 @@ def step_inputs(torch, W, w, n_steps):
     return qs, ks, vs
 
 
-def run_steps(torch, cache, w, qs, ks, vs, outs, s0, s1):
-    """Decode steps s0..s1-1 through the C ABI with pre-resolved pointers (no per-call Python checks)."""
+def run_steps(torch, cache, w, qs, ks, vs, outs, s0, s1, probes=None):
+    """Decode steps s0..s1-1 through the C ABI with pre-resolved pointers (no per-call Python checks).
+
+    probes = {layer: [(begin, end) HIP event pair per step]}: on those layers the main decode kernel of step s stamps
+    its pair with its own start and end (the live measurement inside the timed region)."""
     from ctypes import c_void_p
 
     lib, h = cache._lib, cache._h
     L = w.n_layers
+    hooked = False
     for s in range(s0, s1):
         for layer in range(L):
+            if probes is not None and layer in probes:
+                lib.kvq_set_kernel_events(h, probes[layer][s - s0][0], probes[layer][s - s0][1])
+                hooked = True
+            elif hooked:
+                lib.kvq_set_kernel_events(h, None, None)
+                hooked = False
             if FUSED_STEP:
                 rc = lib.kvq_append_decode_attention(h, layer, c_void_p(ks[layer][s].data_ptr()), c_void_p(vs[layer][s].data_ptr()),
                                                      c_void_p(qs[layer][s].data_ptr()), c_void_p(outs[layer].data_ptr()))
@@ -129,27 +139,50 @@ def run_steps(torch, cache, w, qs, ks, vs, outs, s0, s1):
             rc = lib.kvq_decode_attention(h, layer, c_void_p(qs[layer][s].data_ptr()), c_void_p(outs[layer].data_ptr()))
             if rc:
                 raise RuntimeError("kvq_decode_attention failed: %d" % rc)
+        if hooked:
+            lib.kvq_set_kernel_events(h, None, None)
+            hooked = False
 
 
 def time_workload(torch, pkg, W, w, steps, warmup, variant=0, splits=0, per_kernel=True):
     """Returns a dict with step time, tokens/s, algorithmic GB/s and per-layer-type decode timings."""
-    from ctypes import c_void_p
-
     total_steps = warmup + steps
     cache, prefill_ms = build_cache(torch, pkg, W, w, total_steps + 8, variant, splits)
     qs, ks, vs = step_inputs(torch, W, w, total_steps)
     outs = [torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float16, device="cuda:0") for _ in range(w.n_layers)]
     run_steps(torch, cache, w, qs, ks, vs, outs, 0, warmup)
     torch.cuda.synchronize()
+    # One layer of every precision pair is timed live inside the timed region: its main decode kernel stamps a HIP
+    # event pair with its own start and end, one pair per step (kvq_set_kernel_events).
+    hip = HipEvents()
+    by_pair = {}
+    for l in range(w.n_layers):
+        by_pair.setdefault((w.kbits[l], w.vbits[l]), []).append(l)
+    probes = {ls[len(ls) // 2]: [(hip.create(), hip.create()) for _ in range(steps)] for ls in by_pair.values()}
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
-    run_steps(torch, cache, w, qs, ks, vs, outs, warmup, total_steps)
+    run_steps(torch, cache, w, qs, ks, vs, outs, warmup, total_steps, probes if per_kernel else None)
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
     ms_per_step = max(wall_ms, gpu_ms) / steps
+    cache.set_kernel_events(None, None)
+    t_mid = w.context + warmup + steps // 2
+    np_mid = w.group * (max(t_mid - w.residual, 0) // w.group)
+    per_pair = {}
+    for layer, evs in probes.items():
+        key = (w.kbits[layer], w.vbits[layer])
+        if per_kernel:
+            ms = [hip.elapsed_ms(a, b) for a, b in evs]
+            nbytes = layer_bytes(w, key[0], key[1], np_mid, t_mid - np_mid)
+            per_pair["K%dV%d" % key] = {"layers": len(by_pair[key]), "probed_layer": layer, "launches": len(ms),
+                                        "kernel_ms": sum(ms) / len(ms), "bytes": nbytes,
+                                        "kernel_gbps": nbytes / (sum(ms) / len(ms) * 1e-3) / 1e9}
+        for a, b in evs:
+            hip.destroy(a)
+            hip.destroy(b)
 
     # bytes of one step at the middle of the timed region
     T_mid = w.context + warmup + steps // 2
@@ -159,53 +192,9 @@ def time_workload(torch, pkg, W, w, steps, warmup, variant=0, splits=0, per_kern
         "workload": w.name, "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / steps, "wall_ms_per_step": wall_ms / steps,
         "tokens_per_s": w.batch / (ms_per_step * 1e-3), "step_bytes": step_bytes,
         "algorithmic_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
-        "prefill_quantize_ms": prefill_ms,
+        "prefill_quantize_ms": prefill_ms, "per_pair": per_pair,
         "prefill_quantize_input_gbps": (w.n_layers * w.batch * w.n_kv_heads * w.context * w.head_dim * 4) / (prefill_ms * 1e-3) / 1e9,
     }
-    if per_kernel:
-        # Per precision pair: (a) the main decode kernel alone, between two HIP events that the library records on its
-        # launch stream right before and after that kernel, (b) the whole kvq_decode_attention call (main kernel +
-        # split-merge kernel) between two events recorded by the caller on the same stream.
-        lib, h = cache._lib, cache._h
-        hip = HipEvents()
-        per_type = {}
-        reps = 20
-        for layer in range(w.n_layers):
-            key = (w.kbits[layer], w.vbits[layer])
-            if key in per_type and per_type[key]["layers"] >= 4:
-                continue
-            n_packed, n_res = cache.layer_tokens(layer)
-            qp, op = c_void_p(qs[layer][0].data_ptr()), c_void_p(outs[layer].data_ptr())
-            for _ in range(3):
-                lib.kvq_decode_attention(h, layer, qp, op)
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-            for a, b in evs:
-                a.record()
-                lib.kvq_decode_attention(h, layer, qp, op)
-                b.record()
-            torch.cuda.synchronize()
-            call_ms = [a.elapsed_time(b) for a, b in evs]
-            kern_ms = []
-            kev = [(hip.create(), hip.create()) for _ in range(reps)]
-            for a, b in kev:
-                cache.set_kernel_events(a, b)
-                lib.kvq_decode_attention(h, layer, qp, op)
-            cache.set_kernel_events(None, None)
-            torch.cuda.synchronize()
-            for a, b in kev:
-                kern_ms.append(hip.elapsed_ms(a, b))
-                hip.destroy(a)
-                hip.destroy(b)
-            d = per_type.setdefault(key, {"layers": 0, "call_ms": 0.0, "kern_ms": 0.0,
-                                          "bytes": layer_bytes(w, key[0], key[1], n_packed, n_res)})
-            d["layers"] += 1
-            d["call_ms"] += sum(call_ms) / len(call_ms)
-            d["kern_ms"] += sum(kern_ms) / len(kern_ms)
-        res["per_pair"] = {
-            "K%dV%d" % k: {"kernel_ms": v["kern_ms"] / v["layers"], "call_ms": v["call_ms"] / v["layers"], "bytes": v["bytes"],
-                           "kernel_gbps": v["bytes"] / (v["kern_ms"] / v["layers"] * 1e-3) / 1e9,
-                           "call_gbps": v["bytes"] / (v["call_ms"] / v["layers"] * 1e-3) / 1e9}
-            for k, v in per_type.items()}
     cache.close()
     del cache, qs, ks, vs, outs
     torch.cuda.empty_cache()
@@ -341,8 +330,9 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "decode_mfma<%s> (%d of %d layers)" % (dom, counts[dom], w_main.n_layers),
         "achieved": pk["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": pk["kernel_gbps"] / HBM_PEAK_GBPS,
-        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else "")),
-        "whole_call_ms": pk["call_ms"], "whole_call_frac": pk["call_gbps"] / HBM_PEAK_GBPS,
+        "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "launches_timed": pk["launches"],
+        "timed": "inside the timed region, layer %d of every step, between HIP events stamped by the kernel's own dispatch" % pk["probed_layer"],
+        "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else "")),
     }
     from paper_2502_04420_amd import equivalent_precision
 

@@ -176,11 +176,11 @@ int kvq_set_decode_options(kvq_ctx *ctx, int32_t variant, int32_t splits);
 /*
  * Measurement hook (optional).  begin_event / end_event: two hipEvent_t handles owned by the
  * caller (created with timing enabled), or both NULL to switch the hook off.  While set,
- * every kvq_decode_attention records begin_event on the context's stream right before its
- * main kernel (the fused dequantize-and-attend kernel) and end_event right after it, i.e.
- * before the small kernel that merges the token-range splits; the caller synchronises and
- * reads hipEventElapsedTime.  The events must outlive the hook.  Returns KVQ_EINVAL when
- * exactly one of the two is NULL.
+ * every decode call makes its main kernel (the fused dequantize-and-attend kernel) stamp
+ * begin_event with the start and end_event with the end of that kernel's own execution on the
+ * context's stream (the small kernel that merges the token-range splits runs after end_event);
+ * the caller synchronises and reads hipEventElapsedTime.  The events must outlive the hook.
+ * Returns KVQ_EINVAL when exactly one of the two is NULL.
  */
 int kvq_set_kernel_events(kvq_ctx *ctx, void *begin_event, void *end_event);
 

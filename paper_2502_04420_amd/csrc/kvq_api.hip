@@ -253,10 +253,16 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     a.units_per_split = (units + splits - 1) / splits;
     a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
     const bool timed = c->ev_begin && c->ev_end;
-    if (timed && hipEventRecord(c->ev_begin, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
-    hipError_t e = variant == 2 ? kvq::launch_decode_mfma(a, c->stream) : kvq::launch_decode_valu(a, c->stream);
+    hipError_t e;
+    if (variant == 2) {
+        // the matrix-core kernel's dispatch stamps the two events itself (its own start and end, no marker in between)
+        e = kvq::launch_decode_mfma(a, c->stream, timed ? c->ev_begin : nullptr, timed ? c->ev_end : nullptr);
+    } else {
+        if (timed && hipEventRecord(c->ev_begin, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
+        e = kvq::launch_decode_valu(a, c->stream);
+        if (e == hipSuccess && timed && hipEventRecord(c->ev_end, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
+    }
     if (e != hipSuccess) return launch_failed("decode kernel", e);
-    if (timed && hipEventRecord(c->ev_end, c->stream) != hipSuccess) return launch_failed("event record", hipGetLastError());
     e = kvq::launch_combine(a, c->stream);
     if (e != hipSuccess) return launch_failed("combine kernel", e);
     return KVQ_OK;

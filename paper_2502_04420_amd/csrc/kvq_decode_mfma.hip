@@ -22,6 +22,8 @@
 // neighbouring blocks overlap on different SIMDs and each wave carries only half of the state
 // (which is what lets 4 waves share a SIMD and hide the memory latency).  Each wave writes its
 // part of the split's partial result itself; the splits are merged by combine_splits.
+#include <hip/hip_ext.h>
+
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -708,57 +710,65 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     }
 }
 
+struct LaunchEvents { hipEvent_t begin, end; };
+
 template <int KB, int VB, bool NARROW, bool KPT>
-hipError_t launch_gq(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_gq(const DecodeArgs &a, hipStream_t s, LaunchEvents ev)
 {
     const int gq = a.Hq / a.Hkv;
     const int BH = a.B * a.Hkv;
     const dim3 block(128);
-    if (gq <= 4) {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW, KPT>), dim3(a.splits, BH, 1), block, 0, s, a);
+    const dim3 grid(a.splits, BH, gq <= 4 ? 1 : (gq + 7) / 8);
+    if (ev.begin && ev.end) {
+        // measurement: the runtime's extended launch stamps the events with the dispatch's own start and end times
+        if (gq <= 4) hipExtLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW, KPT>), grid, block, 0, s, ev.begin, ev.end, 0, a);
+        else hipExtLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW, KPT>), grid, block, 0, s, ev.begin, ev.end, 0, a);
+    } else if (gq <= 4) {
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 4, NARROW, KPT>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW, KPT>), dim3(a.splits, BH, (gq + 7) / 8), block, 0, s, a);
+        hipLaunchKernelGGL((decode_mfma<KB, VB, 8, NARROW, KPT>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }
 
 template <int KB, bool NARROW, bool KPT>
-hipError_t launch_vb(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_vb(const DecodeArgs &a, hipStream_t s, LaunchEvents ev)
 {
     switch (a.lv.vbits) {
-    case 2: return launch_gq<KB, 2, NARROW, KPT>(a, s);
-    case 4: return launch_gq<KB, 4, NARROW, KPT>(a, s);
-    case 8: return launch_gq<KB, 8, NARROW, KPT>(a, s);
-    default: return launch_gq<KB, 16, NARROW, KPT>(a, s);
+    case 2: return launch_gq<KB, 2, NARROW, KPT>(a, s, ev);
+    case 4: return launch_gq<KB, 4, NARROW, KPT>(a, s, ev);
+    case 8: return launch_gq<KB, 8, NARROW, KPT>(a, s, ev);
+    default: return launch_gq<KB, 16, NARROW, KPT>(a, s, ev);
     }
 }
 
 template <bool NARROW>
-hipError_t launch_kb(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_kb(const DecodeArgs &a, hipStream_t s, LaunchEvents ev)
 {
     // the key grouping only matters for quantized keys
     if (a.lv.kpt) {
         switch (a.lv.kbits) {
-        case 2: return launch_vb<2, NARROW, true>(a, s);
-        case 4: return launch_vb<4, NARROW, true>(a, s);
-        case 8: return launch_vb<8, NARROW, true>(a, s);
+        case 2: return launch_vb<2, NARROW, true>(a, s, ev);
+        case 4: return launch_vb<4, NARROW, true>(a, s, ev);
+        case 8: return launch_vb<8, NARROW, true>(a, s, ev);
         default: break;
         }
     }
     switch (a.lv.kbits) {
-    case 2: return launch_vb<2, NARROW, false>(a, s);
-    case 4: return launch_vb<4, NARROW, false>(a, s);
-    case 8: return launch_vb<8, NARROW, false>(a, s);
-    default: return launch_vb<16, NARROW, false>(a, s);
+    case 2: return launch_vb<2, NARROW, false>(a, s, ev);
+    case 4: return launch_vb<4, NARROW, false>(a, s, ev);
+    case 8: return launch_vb<8, NARROW, false>(a, s, ev);
+    default: return launch_vb<16, NARROW, false>(a, s, ev);
     }
 }
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end)
 {
     if (a.B * a.Hkv > 65535) return hipErrorInvalidConfiguration;
-    return a.lv.narrow ? launch_kb<true>(a, s) : launch_kb<false>(a, s);
+    const LaunchEvents ev = {ev_begin, ev_end};
+    return a.lv.narrow ? launch_kb<true>(a, s, ev) : launch_kb<false>(a, s, ev);
 }
 
 }  // namespace kvq

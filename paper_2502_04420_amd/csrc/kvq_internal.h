@@ -73,7 +73,8 @@ hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);
 hipError_t launch_residual_copy(const ResidualCopyArgs &a, hipStream_t s);
 hipError_t launch_export(const ExportArgs &a, hipStream_t s);
 hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s);
-hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s);
+// ev_begin / ev_end (both or neither): receive the start and stop time stamps of the kernel's own dispatch
+hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s);
 
 }  // namespace kvq
