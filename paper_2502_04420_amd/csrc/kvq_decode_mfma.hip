@@ -156,17 +156,6 @@ __device__ __forceinline__ float row_sum16(float x)
     return x;
 }
 
-// lo = the value held by lanes 0..31, hi = the value held by lanes 32..63, both in every lane.
-// Written as inline assembly: the compiler builtin for this instruction returned its first
-// result twice with this toolchain.  The s_nop covers the VALU-write -> permlane read hazard.
-__device__ __forceinline__ void halves_of(float x, float &lo, float &hi)
-{
-    uint32_t a = __builtin_bit_cast(uint32_t, x), b = a;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    lo = __builtin_bit_cast(float, a);      // [x.lanes0-31, x.lanes0-31]
-    hi = __builtin_bit_cast(float, b);      // [x.lanes32-63, x.lanes32-63]
-}
-
 // Work-group barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for
 // the global loads of the next block, which are meant to stay in flight across it.
 __device__ __forceinline__ void wg_barrier()
