@@ -70,16 +70,31 @@ __device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s
                                         float (&c8)[8])
 {
     float d[8], u[8];
+    bool redo;
+    if constexpr (!CLAMP && BITS <= 4) {
+        // few levels: one margin for all, 2^-21 times an upper bound 2^B of the quotient; u = distance to the nearest tie
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-        d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
-        const float t = d[e] * r8[e];
-        c8[e] = CLAMP ? fminf(rintf(t), (float)((1 << BITS) - 1)) : rintf(t);
-        u[e] = fmaf(t, 4.76837158203125e-07f, -fabsf(__builtin_amdgcn_fractf(t) - 0.5f));    // 2^-21 t - |frac(t) - 1/2|
+        for (int e = 0; e < 8; e++) {
+            d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
+            const float t = d[e] * r8[e];
+            c8[e] = rintf(t);
+            u[e] = fabsf(__builtin_amdgcn_fractf(t) - 0.5f);
+        }
+        const float nearest = fminf(fminf(fminf(u[0], u[1]), fminf(u[2], u[3])), fminf(fminf(u[4], u[5]), fminf(u[6], u[7])));
+        redo = __any(nearest <= (float)(1 << BITS) * 4.76837158203125e-07f);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
+            const float t = d[e] * r8[e];
+            c8[e] = CLAMP ? fminf(rintf(t), (float)((1 << BITS) - 1)) : rintf(t);
+            u[e] = fmaf(t, 4.76837158203125e-07f, -fabsf(__builtin_amdgcn_fractf(t) - 0.5f));    // 2^-21 t - |frac(t) - 1/2|
+        }
+        // some element is within its margin of a tie <=> the largest u is >= 0
+        const float worst = fmaxf(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])), fmaxf(fmaxf(u[4], u[5]), fmaxf(u[6], u[7])));
+        redo = __any(worst >= 0.0f);
     }
-    // some element is within its margin of a tie <=> the largest u is >= 0
-    const float worst = fmaxf(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])), fmaxf(fmaxf(u[4], u[5]), fmaxf(u[6], u[7])));
-    if (__any(worst >= 0.0f)) {
+    if (redo) {
 #pragma unroll
         for (int e = 0; e < 8; e++) c8[e] = round_exact<BITS>(d[e], s8[e]);
     }
@@ -216,16 +231,18 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
                     mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
                 }
+                // every lane row now holds the statistics of all 8 channels: row r finishes channels 2r and 2r + 1
+                const uint32_t mn2 = r == 0 ? mnp[0] : r == 1 ? mnp[1] : r == 2 ? mnp[2] : mnp[3];
+                const uint32_t mx2 = r == 0 ? mxp[0] : r == 1 ? mxp[1] : r == 2 ? mxp[2] : mxp[3];
 #pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    const uint32_t mnb = (mnp[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                    const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mxp[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                for (int h = 0; h < 2; h++) {
+                    const int ch = 8 * c16 + 2 * r + h;
+                    const uint32_t mnb = (mn2 >> (16 * h)) & 0xffffu;
+                    const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mx2 >> (16 * h)) & 0xffffu);
                     const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
                     s_max = fmaxf(s_max, s);
-                    if (r == 0) {
-                        sc[8 * c16 + e] = s; zp[8 * c16 + e] = mn; rsc[8 * c16 + e] = recip_or_zero(s);
-                        store_scale<NARROW>(meta, 8 * c16 + e, s); meta_zeros(meta, NARROW)[8 * c16 + e] = (uint16_t)mnb;
-                    }
+                    sc[ch] = s; zp[ch] = mn; rsc[ch] = recip_or_zero(s);
+                    store_scale<NARROW>(meta, ch, s); meta_zeros(meta, NARROW)[ch] = (uint16_t)mnb;
                 }
             } else {
                 // min / max per token over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd;
@@ -288,23 +305,29 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
         } else {
             float *meta = a.lv.vmeta + blk_index * meta_words(NARROW);
             float s_max = 0.0f;
+            // min / max over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd (fp16 pairs:
+            // the two halves are merged below)
+            uint32_t mnp[8], mxp[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-                const int t = 8 * r + i;
-                // min / max over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd
-                uint32_t mnp = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
-                uint32_t mxp = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
-                mnp = pk_min(mnp, __shfl_xor(mnp, 1)); mxp = pk_max(mxp, __shfl_xor(mxp, 1));
-                mnp = pk_min(mnp, __shfl_xor(mnp, 2)); mxp = pk_max(mxp, __shfl_xor(mxp, 2));
-                const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
-                const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
+                mnp[i] = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
+                mxp[i] = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
+                mnp[i] = pk_min(mnp[i], __shfl_xor(mnp[i], 1)); mxp[i] = pk_max(mxp[i], __shfl_xor(mxp[i], 1));
+                mnp[i] = pk_min(mnp[i], __shfl_xor(mnp[i], 2)); mxp[i] = pk_max(mxp[i], __shfl_xor(mxp[i], 2));
+            }
+            // the 4 lanes of a group hold the same 8 results: lane q = c16 & 3 finishes tokens q and q + 4 of its row
+            const int q4 = c16 & 3, gd = c16 >> 2;
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t mnb = q4 == 0 ? mnp[4 * h] : q4 == 1 ? mnp[4 * h + 1] : q4 == 2 ? mnp[4 * h + 2] : mnp[4 * h + 3];
+                const uint32_t mxb = q4 == 0 ? mxp[4 * h] : q4 == 1 ? mxp[4 * h + 1] : q4 == 2 ? mxp[4 * h + 2] : mxp[4 * h + 3];
+                const int t = 8 * r + 4 * h + q4;
+                const float mn = fminf(half_bits_to_float(mnb & 0xffffu), half_bits_to_float(mnb >> 16));
+                const float mx = fmaxf(half_bits_to_float(mxb & 0xffffu), half_bits_to_float(mxb >> 16));
                 const float s = stored_scale<NARROW>(scale_of(mn, mx, VB));
                 s_max = fmaxf(s_max, s);
-                if ((c16 & 3) == 0) {
-                    const int gd = c16 >> 2;
-                    sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
-                    store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
-                }
+                sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
+                store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
             }
             // 8 x 8 transpose in registers: channel 8*c16 + e gets its 8 tokens as one 16-byte chunk
             const int krow = (c16 & 7) | (((c16 ^ (c16 >> 3)) & 1) << 3);      // value_row(8*c16 + e) = (c16 >> 1) << 4 | (krow ^ e)
