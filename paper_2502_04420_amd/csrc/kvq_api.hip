@@ -16,6 +16,7 @@
 namespace {
 
 constexpr int kMaxSplits = 128;
+constexpr int kWindowWeight = 4;   // cost of the fp16 window in a split's share, in packed blocks (measured: 2..8 alike, 0 slower)
 constexpr size_t kAlign = 256;
 
 thread_local char g_last_error[256] = "";
@@ -234,24 +235,31 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     a.k_new = static_cast<const uint16_t *>(k_new);
     a.v_new = static_cast<const uint16_t *>(v_new);
     a.new_pos = T - 1;
-    const int units = a.n_blocks + (a.n_res + 31) / 32;
     const int variant = decode_variant(c);
     int splits = c->splits;
     if (splits <= 0) {
         // 16 waves per compute unit (4 on every SIMD) over 256 compute units: 2048 two-wave groups of the
         // matrix-core kernel or 1024 four-wave groups of the vector kernel.  More splits only add per-group
-        // set-up and merge work, so split no further and keep at least 4 (8) units per group.
+        // set-up and merge work, so split no further and keep at least 4 (8) blocks per group.
         const int BH = a.B * a.Hkv;
         const int groups = variant == 2 ? 2048 : 1024, min_units = variant == 2 ? 4 : 8;
         splits = (groups + BH - 1) / BH;
-        const int cap = (units + min_units - 1) / min_units;
+        const int cap = (a.n_blocks + min_units - 1) / min_units + (a.n_res > 0 ? 1 : 0);
         if (splits > cap) splits = cap;
     }
     if (splits > kMaxSplits) splits = kMaxSplits;
-    if (splits > units) splits = units;
     if (splits < 1) splits = 1;
-    a.units_per_split = (units + splits - 1) / splits;
-    a.splits = (units + a.units_per_split - 1) / a.units_per_split;   // no empty split
+    // The fp16 window rides on the last split.  Its rows go through the vector units one token at a time, which costs
+    // about as much as kWindowWeight packed blocks, so the last split is handed that many blocks fewer (none at all
+    // when its fair share is smaller than that).
+    const int window = a.n_res > 0 ? kWindowWeight : 0;
+    if (a.n_blocks == 0) splits = 1;
+    a.units_per_split = (a.n_blocks + window + splits - 1) / splits;
+    if (a.units_per_split < 1) a.units_per_split = 1;
+    const int block_splits = (a.n_blocks + a.units_per_split - 1) / a.units_per_split;   // splits that own packed blocks
+    if (splits > block_splits + (window ? 1 : 0)) splits = block_splits + (window ? 1 : 0);   // no empty split
+    if (splits < 1) splits = 1;
+    a.splits = splits;
     const bool timed = c->ev_begin && c->ev_end;
     hipError_t e;
     if (variant == 2) {

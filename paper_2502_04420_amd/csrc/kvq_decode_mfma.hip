@@ -387,17 +387,27 @@ template <int GQ>
 __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int nt, int ring, const uint16_t *new_row, int new_pos,
                                             ValueState<GQ> &W, const PairLds<GQ> &L, int buf, int lane)
 {
-    for (int tt = 0; tt < nt; tt++) {
-        const int pos = pos0 + tt;
-        const uint16_t *row = base + (size_t)(ring ? pos % ring : pos) * kD;
-        if (new_row && pos == new_pos) row = new_row;          // the token of a fused append is not in the ring yet
-        const uint32_t x = *reinterpret_cast<const uint32_t *>(row + 2 * lane);
-        const float v0 = half_lo(x), v1 = half_hi(x);
+    // eight rows are fetched at a time with independent loads (a token-by-token loop pays one memory latency per token)
+    for (int t0 = 0; t0 < nt; t0 += 8) {
+        uint32_t x[8];
 #pragma unroll
-        for (int j = 0; j < GQ; j++) {
-            const float pj = L.P[buf][j][tt];
-            W.oF[j][0] = fmaf(pj, v0, W.oF[j][0]);
-            W.oF[j][1] = fmaf(pj, v1, W.oF[j][1]);
+        for (int k = 0; k < 8; k++) {
+            const int pos = pos0 + (t0 + k < nt ? t0 + k : t0);        // past the end: a valid row again, not used
+            const uint16_t *row = base + (size_t)(ring ? pos % ring : pos) * kD;
+            if (new_row && pos == new_pos) row = new_row;              // the token of a fused append is not in the ring yet
+            x[k] = *reinterpret_cast<const uint32_t *>(row + 2 * lane);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            if (t0 + k < nt) {
+                const float v0 = half_lo(x[k]), v1 = half_hi(x[k]);
+#pragma unroll
+                for (int j = 0; j < GQ; j++) {
+                    const float pj = L.P[buf][j][t0 + k];
+                    W.oF[j][0] = fmaf(pj, v0, W.oF[j][0]);
+                    W.oF[j][1] = fmaf(pj, v1, W.oF[j][1]);
+                }
+            }
         }
     }
 }
@@ -431,9 +441,8 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     // ---- work of this group: units [u0, u1) = quantized blocks, then chunks of <= 32 fp16 window tokens.
     // Phase 1 covers the fully quantized blocks (only when both tensors are quantized), phase 2 the rest.
     // Unit number it (counted from u0) is handed over through buffer it & 1.
-    const int units = a.n_blocks + (a.n_res + 31) / 32;
-    const int u0 = split * a.units_per_split;
-    const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
+    int u0, u1;
+    split_range(a, split, u0, u1);
     const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
     const int f1c = f1 > u0 ? f1 : u0;
     const int n1 = f1c - u0, n2 = u1 - f1c;

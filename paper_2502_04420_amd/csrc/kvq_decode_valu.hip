@@ -77,9 +77,8 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
         for (int c = 0; c < 8; c++) oP[j][c] = 0.0f;
     }
 
-    const int units = a.n_blocks + (a.n_res + 31) / 32;
-    const int u0 = split * a.units_per_split;
-    const int u1 = u0 + a.units_per_split < units ? u0 + a.units_per_split : units;
+    int u0, u1;
+    split_range(a, split, u0, u1);
 
     for (int u = u0 + wave; u < u1; u += 4) {
         const bool packed = u < a.n_blocks;

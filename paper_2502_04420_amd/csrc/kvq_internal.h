@@ -61,13 +61,24 @@ struct DecodeArgs {
     int n_res;             // fp16 tokens at positions [32*n_blocks, 32*n_blocks + n_res)
     int NB, RC;
     int splits;            // gridDim.x
-    int units_per_split;   // work units (blocks, then chunks of <= 32 fp16 tokens) per split
+    int units_per_split;   // quantized blocks per split (the last split takes what is left of them, then the fp16 window)
     float scale_log2e;     // log2(e) / sqrt(D)
     // fused append of one token per sequence (matrix-core kernel only): its fp16 rows [B*Hkv][128], not yet in the
     // window ring; the kernel reads them from here and stores them into the ring for later launches.  NULL: none.
     const uint16_t *k_new, *v_new;
     int new_pos;           // absolute position of that token
 };
+
+// Work units [u0, u1) of a split: units are the quantized blocks, then the chunks of <= 32 fp16 window tokens.  Every
+// split takes units_per_split blocks; the last one takes the blocks that are left (possibly none) and the window.
+__device__ __forceinline__ void split_range(const DecodeArgs &a, int split, int &u0, int &u1)
+{
+    u0 = split * a.units_per_split;
+    if (u0 > a.n_blocks) u0 = a.n_blocks;
+    u1 = u0 + a.units_per_split;
+    if (u1 > a.n_blocks) u1 = a.n_blocks;
+    if (split == a.splits - 1) u1 = a.n_blocks + (a.n_res + 31) / 32;
+}
 
 hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);
 hipError_t launch_residual_copy(const ResidualCopyArgs &a, hipStream_t s);
