@@ -71,6 +71,8 @@ def _load():
     lib.kvo_tokens.argtypes = [c_void_p, c_int, POINTER(c_int), POINTER(c_int)]
     lib.kvo_decode_attention.restype = c_int
     lib.kvo_decode_attention.argtypes = [c_void_p, c_int, u16p, u16p, f64p, f64p]
+    lib.kvo_prefill_attention.restype = c_int
+    lib.kvo_prefill_attention.argtypes = [c_void_p, c_int, u16p, c_int, u16p, f64p]
     lib.kvo_attention_exact.restype = None
     lib.kvo_attention_exact.argtypes = [u16p, u16p, u16p] + [c_int] * 5 + [u16p, f64p, f64p]
     lib.kvo_export.restype = c_int
@@ -202,6 +204,20 @@ class OracleCache:
             raise ValueError("oracle decode_attention failed (%d)" % rc)
         res = (out.view(np.float16), o64)
         return res + (p,) if want_p else res
+
+    def prefill_attention(self, layer: int, q):
+        """Causal attention of the last n_q tokens over the cache as it stands (Section 5.3's calibration
+        design: the prompt's attention reads the dequantized cache).  q fp16 [B, Hq, n_q, D].
+        Returns (out fp16 [B, Hq, n_q, D], out fp64)."""
+        qu = _as_u16(q)
+        assert qu.ndim == 4 and qu.shape[0] == self.B and qu.shape[1] == self.Hq and qu.shape[3] == self.D
+        n_q = qu.shape[2]
+        out = np.zeros(qu.shape, dtype=np.uint16)
+        o64 = np.zeros(qu.shape, dtype=np.float64)
+        rc = _load().kvo_prefill_attention(self._h, layer, _ptr(qu, c_uint16), n_q, _ptr(out, c_uint16), _ptr(o64, c_double))
+        if rc:
+            raise ValueError("oracle prefill_attention failed (%d)" % rc)
+        return out.view(np.float16), o64
 
     def reconstruct(self, layer: int):
         """The layer's cache as attention sees it, in double: (K^, V^) [B, Hkv, T, D]; quantized tokens as

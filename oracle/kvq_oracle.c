@@ -456,6 +456,48 @@ int kvo_decode_attention(const kvo_cache *c, int layer, const uint16_t *q, uint1
 }
 
 /*
+ * Prefill-stage attention of one layer over the cache as it stands.  The paper quantizes the cache in the
+ * prefill stage as well as in decoding and lets the prompt's own attention read the dequantized K and V
+ * (calibration design of Section 5.3, experimental-settings appendix).  Reading taken here: the queries are
+ * the last n_q tokens appended; the query at absolute position p attends to positions 0..p (Eq. 1 under the
+ * usual causal mask); a token enters as X^ (Eq. 2) if the cache holds it quantized now, else as its fp16 value.
+ * q: fp16 [B, Hq, n_q, D];  out: fp16 [B, Hq, n_q, D];  out_f64 (nullable): the unrounded outputs.
+ */
+int kvo_prefill_attention(const kvo_cache *c, int layer, const uint16_t *q, int n_q, uint16_t *out, double *out_f64)
+{
+    if (layer < 0 || layer >= c->L) return -1;
+    const kvo_layer *y = &c->layer[layer];
+    if (y->T < 1 || n_q < 1 || n_q > y->T) return -2;
+    const int D = c->D, T = y->T, gq = c->Hq / c->Hkv;
+    const long BH = (long)c->B * c->Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; bh++) {
+        double *Kh = malloc(sizeof(double) * (size_t)T * D);
+        double *Vh = malloc(sizeof(double) * (size_t)T * D);
+        double *p = malloc(sizeof(double) * (size_t)T);
+        double *qd = malloc(sizeof(double) * (size_t)D);
+        double *o = malloc(sizeof(double) * (size_t)D);
+        reconstruct_bh(c, y, (size_t)bh, Kh, Vh);
+        const long b = bh / c->Hkv, h = bh % c->Hkv;
+        for (int j = 0; j < gq; j++) {
+            const size_t head = (size_t)b * c->Hq + (size_t)h * gq + j;
+            for (int i = 0; i < n_q; i++) {
+                const int pos = T - n_q + i;                       /* absolute position of this query */
+                const size_t row = head * (size_t)n_q + (size_t)i;
+                for (int d = 0; d < D; d++) qd[d] = half_to_double(q[row * D + d]);
+                attend_row(qd, Kh, Vh, pos + 1, D, p, o);          /* keys and values 0..pos */
+                for (int d = 0; d < D; d++) {
+                    out[row * D + d] = double_to_half(o[d]);
+                    if (out_f64) out_f64[row * D + d] = o[d];
+                }
+            }
+        }
+        free(Kh); free(Vh); free(p); free(qd); free(o);
+    }
+    return 0;
+}
+
+/*
  * Brute-force Eq. 1 on raw fp16 tensors, no quantization anywhere.
  * q [B,Hq,D], K,V [B,Hkv,T,D] fp16; outputs as in kvo_decode_attention.
  */
