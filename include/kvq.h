@@ -141,6 +141,22 @@ int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void
 int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_device, const void *v_device,
                                 const void *q_device, void *out_device);
 
+/*
+ * Prefill-stage attention of one layer over the cache as it stands: the prompt's own causal
+ * attention reading the dequantized cache (the paper quantizes the cache in the prefill stage
+ * as well as in decoding; calibration design of Section 5.3).  The queries are the last n_q
+ * tokens appended; the query at absolute position p attends to positions 0..p (Eq. 1 under
+ * the causal mask).  A token enters as X^ = Q(X) s + z (Section 3.2) if the layer holds it
+ * quantized now, else as its fp16 value.
+ *   q_device   : fp16 [batch, n_q_heads, n_q, head_dim], contiguous, device.
+ *   out_device : fp16 [batch, n_q_heads, n_q, head_dim], device, written.
+ *   n_q        : 1 .. tokens held by the layer (else KVQ_EINVAL; KVQ_ESTATE for an empty layer).
+ * Query head h attends kv head h / (n_q_heads / n_kv_heads).  The dequantized operands and the
+ * softmax weights are rounded to fp16 for the matrix cores; accumulation is fp32.  The cache
+ * is not modified.  With n_q = 1 the result is that of kvq_decode_attention up to rounding.
+ */
+int kvq_prefill_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, int32_t n_q, void *out_device);
+
 /* Tokens currently held quantized / in fp16 by a layer (host-side bookkeeping, no GPU work). */
 int kvq_layer_tokens(const kvq_ctx *ctx, int32_t layer, int32_t *n_packed, int32_t *n_residual);
 

@@ -221,7 +221,7 @@ def llama_mix(batch: int, context: int, seed: int = 5) -> Workload:
 
 # --------------------------------------------------------------------------- tensors
 
-_K, _V, _Q, _CH, _BIAS = 0, 1, 2, 3, 4
+_K, _V, _Q, _CH, _BIAS, _QP = 0, 1, 2, 3, 4, 5
 
 
 def _tid(layer: int, kind: int, stream: int = 0) -> int:
@@ -285,3 +285,14 @@ def query(w: Workload, layer: int, step: int = 0, device="cpu") -> torch.Tensor:
     n = w.batch * w.n_q_heads * w.head_dim
     idx = torch.arange(n, dtype=torch.int64, device=device) + step * n
     return standard_normal(w.seed, _tid(layer, _Q), idx).to(torch.float16).reshape(w.batch, w.n_q_heads, w.head_dim)
+
+
+def prefill_queries(w: Workload, layer: int, n_q: int, device="cpu", heads=None) -> torch.Tensor:
+    """fp16 queries [B, Hq, n_q, D] of the last n_q prompt positions of one layer (standard normal, like the decode
+    queries).  heads: optional (first, count) range of query heads to draw, for sampling a large tensor."""
+    h0, hc = (0, w.n_q_heads) if heads is None else heads
+    b = torch.arange(w.batch, dtype=torch.int64, device=device).view(-1, 1, 1)
+    h = torch.arange(h0, h0 + hc, dtype=torch.int64, device=device).view(1, -1, 1)
+    e = torch.arange(n_q * w.head_dim, dtype=torch.int64, device=device).view(1, 1, -1)
+    idx = (b * w.n_q_heads + h) * (n_q * w.head_dim) + e
+    return standard_normal(w.seed, _tid(layer, _QP), idx.reshape(-1)).to(torch.float16).reshape(w.batch, hc, n_q, w.head_dim)

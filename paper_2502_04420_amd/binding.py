@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libkvq.so")
 _lib = None
 
 EXPORTED = [
-    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_append_decode_attention",
+    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_append_decode_attention", "kvq_prefill_attention",
     "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
     "kvq_last_error",
 ]
@@ -54,6 +54,8 @@ def load_library():
     lib.kvq_quantize_append.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32]
     lib.kvq_decode_attention.restype = c_int32
     lib.kvq_decode_attention.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
+    lib.kvq_prefill_attention.restype = c_int32
+    lib.kvq_prefill_attention.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
     lib.kvq_layer_tokens.restype = c_int32
     lib.kvq_layer_tokens.argtypes = [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32)]
     lib.kvq_reset.restype = c_int32
@@ -187,6 +189,20 @@ class KVQ:
             out = torch.empty(shape, dtype=torch.float16, device=self.device)
         op = self._dev_ptr(out, shape, torch.float16, "out")
         _check(self._lib.kvq_append_decode_attention(self._h, layer, kp, vp, qp, op))
+        return out
+
+    def prefill_attention(self, layer: int, q, out=None):
+        """Causal attention of the last n_q tokens over the layer's cache as it stands.
+        q: fp16 [batch, n_q_heads, n_q, head_dim]; returns out of the same shape (allocated if not given)."""
+        torch = self._torch
+        if q.dim() != 4:
+            raise ValueError("q must be [batch, n_q_heads, n_q, head_dim]")
+        shape = (self.batch, self.n_q_heads, int(q.shape[2]), self.head_dim)
+        qp = self._dev_ptr(q, shape, torch.float16, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.float16, device=self.device)
+        op = self._dev_ptr(out, shape, torch.float16, "out")
+        _check(self._lib.kvq_prefill_attention(self._h, layer, qp, shape[2], op))
         return out
 
     # -- bookkeeping and debugging

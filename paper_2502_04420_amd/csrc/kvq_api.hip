@@ -302,6 +302,35 @@ int kvq_append_decode_attention(kvq_ctx *c, int32_t layer, const void *k_device,
     return decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr);
 }
 
+int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32_t n_q, void *out_device)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
+    const int T = c->tokens[layer];
+    if (T < 1) return KVQ_ESTATE;
+    if (n_q < 1 || n_q > T) {
+        snprintf(g_last_error, sizeof g_last_error, "kvq_prefill_attention: n_q = %d queries, the layer holds %d tokens", n_q, T);
+        return KVQ_EINVAL;
+    }
+    const int np = packed_tokens(c, T);
+    kvq::PrefillArgs a;
+    a.lv = view(c, layer);
+    a.q = static_cast<const uint16_t *>(q_device);
+    a.out = static_cast<uint16_t *>(out_device);
+    a.B = c->cfg.batch;
+    a.Hq = c->cfg.n_q_heads;
+    a.Hkv = c->cfg.n_kv_heads;
+    a.n_blocks = np / kvq::kG;
+    a.n_res = T - np;
+    a.NB = c->plan.NB;
+    a.RC = c->plan.RC;
+    a.n_q = n_q;
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
+    const bool timed = c->ev_begin && c->ev_end;
+    const hipError_t e = kvq::launch_prefill_attention(a, c->stream, timed ? c->ev_begin : nullptr, timed ? c->ev_end : nullptr);
+    if (e != hipSuccess) return launch_failed("prefill attention kernel", e);
+    return KVQ_OK;
+}
+
 int kvq_layer_tokens(const kvq_ctx *c, int32_t layer, int32_t *n_packed, int32_t *n_residual)
 {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !n_packed || !n_residual) return KVQ_EINVAL;

@@ -69,6 +69,18 @@ struct DecodeArgs {
     int new_pos;           // absolute position of that token
 };
 
+struct PrefillArgs {
+    LayerView lv;
+    const uint16_t *q;     // fp16 [B][Hq][n_q][128]: the last n_q positions
+    uint16_t *out;         // fp16 [B][Hq][n_q][128]
+    int B, Hq, Hkv;
+    int n_blocks;          // quantized blocks (N_p / 32)
+    int n_res;             // fp16 tokens at positions [32*n_blocks, 32*n_blocks + n_res)
+    int NB, RC;
+    int n_q;               // 1 <= n_q <= 32*n_blocks + n_res
+    float scale_log2e;     // log2(e) / sqrt(D)
+};
+
 // Work units [u0, u1) of a split: units are the quantized blocks, then the chunks of <= 32 fp16 window tokens.  Every
 // split takes units_per_split blocks; the last one takes the blocks that are left (possibly none) and the window.
 __device__ __forceinline__ void split_range(const DecodeArgs &a, int split, int &u0, int &u1)
@@ -86,6 +98,7 @@ hipError_t launch_export(const ExportArgs &a, hipStream_t s);
 hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s);
 // ev_begin / ev_end (both or neither): receive the start and stop time stamps of the kernel's own dispatch
 hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s);
 
 }  // namespace kvq

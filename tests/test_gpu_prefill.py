@@ -1,0 +1,132 @@
+"""GPU parity of the prefill-stage attention (causal attention of the prompt over the dequantized cache) against the
+CPU oracle, every element.
+
+Bars: per tensor ||gpu - oracle||_2 / ||oracle||_2 <= 1e-3, and per element |gpu - oracle| <= 2e-3 + 2^-10 |oracle|.
+The second term is one fp16 spacing of the value: early prompt positions average over few tokens, so their
+outputs reach the magnitude of single values (2..8 here), where a result that is right to well under the absolute
+budget can still round to the neighbouring fp16 number.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvq_workloads as W
+from test_gpu_parity import _pair, kvq_mod  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-3
+REL_L2 = 1e-3
+
+
+def assert_prefill_close(gpu_out, ora64, where=""):
+    g = gpu_out.float().cpu().numpy().astype(np.float64)
+    assert g.shape == ora64.shape, (where, g.shape, ora64.shape)
+    assert np.all(np.isfinite(g)), where
+    err = np.abs(g - ora64)
+    bound = MAX_ABS + 2.0 ** -10 * np.abs(ora64)
+    worst = (err - bound).max()
+    assert worst <= 0, (where, "elementwise", float(err.max()), np.unravel_index(np.argmax(err - bound), err.shape))
+    rel = np.linalg.norm(g - ora64) / max(np.linalg.norm(ora64), 1e-30)
+    assert rel <= REL_L2, (where, "rel l2", rel)
+    return rel
+
+
+def _run(kvq_mod, oracle_mod, w, n_q, meta=None, keys=None, max_tokens=None):
+    kw = {}
+    if meta is not None:
+        kw["meta_dtype"] = meta
+    if keys is not None:
+        kw["key_mode"] = keys
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, max_tokens or (w.context + 64), w.kbits, w.vbits, **kw)
+    o = oracle_mod.OracleCache(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.kbits, w.vbits,
+                               scale_fp16=meta == kvq_mod.META_FP16 if meta is not None else False,
+                               key_per_token=keys == kvq_mod.KEYS_PER_TOKEN if keys is not None else False)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    q = W.prefill_queries(w, 0, n_q)
+    out = g.prefill_attention(0, q.cuda())
+    o16, o64 = o.prefill_attention(0, q.numpy())
+    return out, o64, g, o, q
+
+
+PAIRS = [(8, 8), (8, 4), (4, 4), (4, 2), (2, 2), (2, 8), (16, 16), (16, 4), (2, 16)]
+
+
+@pytest.mark.parametrize("kb,vb", PAIRS)
+def test_all_precision_pairs_full_prompt(kvq_mod, oracle_mod, kb, vb):
+    """10 blocks plus a ragged window (51 tokens): three query tiles of 128, the last one partial; g_q = 4."""
+    w = W.Workload("prefill", 1, 2, 8, 2, 128, 32 * 11 + 19, [kb], [vb], seed=300 + kb * 17 + vb, outlier_channels=3)
+    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, w.context)
+    assert g.layer_tokens(0) == (320, 51)
+    assert_prefill_close(out, o64, "K%dV%d" % (kb, vb))
+    g.close()
+
+
+@pytest.mark.parametrize("T,n_q", [(1, 1), (5, 5), (31, 31), (32, 32), (33, 7), (63, 63), (64, 64), (65, 65), (96, 1), (127, 100),
+                                   (200, 129), (257, 256), (300, 17)])
+def test_ragged_lengths_and_query_counts(kvq_mod, oracle_mod, T, n_q):
+    """Lengths around the window and block boundaries, with fewer queries than tokens (the last n_q positions)."""
+    w = W.Workload("ragged", 1, 1, 4, 1, 128, T, [4], [2], seed=400 + T, outlier_channels=2)
+    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, n_q)
+    assert_prefill_close(out, o64, "T%d nq%d" % (T, n_q))
+    g.close()
+
+
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (7, 1), (8, 1), (6, 3), (28, 4)])
+def test_head_ratios(kvq_mod, oracle_mod, hq, hkv):
+    w = W.Workload("heads", 1, 2, hq, hkv, 128, 32 * 5 + 9, [4], [4], seed=500 + hq, outlier_channels=2)
+    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, w.context)
+    assert_prefill_close(out, o64, "Hq%d Hkv%d" % (hq, hkv))
+    g.close()
+
+
+@pytest.mark.parametrize("kb,vb", [(8, 4), (4, 2), (2, 2)])
+def test_fp16_scales_and_per_token_keys(kvq_mod, oracle_mod, kb, vb):
+    w = W.Workload("modes", 1, 1, 8, 2, 128, 32 * 7 + 40, [kb], [vb], seed=600 + kb + vb, outlier_channels=3)
+    for meta, keys in ((kvq_mod.META_FP16, kvq_mod.KEYS_PER_CHANNEL), (kvq_mod.META_FP32, kvq_mod.KEYS_PER_TOKEN),
+                       (kvq_mod.META_FP16, kvq_mod.KEYS_PER_TOKEN)):
+        out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, w.context, meta=meta, keys=keys)
+        assert_prefill_close(out, o64, "K%dV%d meta %d keys %d" % (kb, vb, meta, keys))
+        g.close()
+
+
+def test_last_row_is_the_decode_step_and_cache_is_untouched(kvq_mod, oracle_mod):
+    """With every token visible the last query is a decode query: both kernels agree with the oracle; the call
+    leaves the cache as it was (export before == export after); chunked appends give the same answer."""
+    from test_gpu_parity import assert_export_equal, assert_outputs_close
+
+    w = W.Workload("last", 1, 2, 8, 2, 128, 32 * 6 + 33, [4], [2], seed=77, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 512)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    for t0, t1 in ((0, 100), (100, 101), (101, w.context)):
+        g.quantize_append(0, K[:, :, t0:t1].contiguous().cuda(), V[:, :, t0:t1].contiguous().cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    q = W.prefill_queries(w, 0, 40)
+    before = o.export(0)
+    out = g.prefill_attention(0, q.cuda())
+    assert_export_equal(g.debug_export(0), before, "after prefill attention")
+    o16, o64 = o.prefill_attention(0, q.numpy())
+    assert_prefill_close(out, o64, "chunked")
+    dec = g.decode_attention(0, q[:, :, -1, :].contiguous().cuda())
+    d16, d64 = o.decode_attention(0, q[:, :, -1, :].contiguous().numpy())
+    assert_outputs_close(dec, d16, d64, "decode on the last query")
+    assert np.array_equal(d64, o64[:, :, -1, :])
+    g.close()
+
+
+def test_argument_errors(kvq_mod):
+    g = kvq_mod.KVQ(1, 1, 4, 1, 128, 256, [4], [4])
+    q = torch.zeros(1, 4, 8, 128, dtype=torch.float16, device="cuda:0")
+    with pytest.raises(kvq_mod.KVQError):
+        g.prefill_attention(0, q)                                   # empty layer
+    z = torch.zeros(1, 1, 5, 128, dtype=torch.float16, device="cuda:0")
+    g.quantize_append(0, z, z)
+    with pytest.raises(kvq_mod.KVQError):
+        g.prefill_attention(0, q)                                   # 8 queries, 5 tokens
+    with pytest.raises(kvq_mod.KVQError):
+        g.prefill_attention(1, q[:, :, :5].contiguous())            # bad layer
+    out = g.prefill_attention(0, q[:, :, :5].contiguous())
+    assert torch.all(out == 0)
+    g.close()
