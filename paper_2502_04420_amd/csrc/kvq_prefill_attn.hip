@@ -40,177 +40,189 @@ struct Tiles {
     _Float16 Vt[kD][kVStride];          // V^[channel][token]
 };
 
-// Registers of a unit on its way from memory to LDS.  Quantized tensor: [0..3] codes, [4..11] scales, [12..15]
-// zero-points (keys grouped per token: [4], [5] scales and [6], [7] zero-points of the thread's two tokens, as fp32).
-// fp16 rows (16-bit tensor or window): [0..7] two 16-byte row pieces.
-struct Stage { uint32_t k[16], v[16]; };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Registers of one tensor's unit on its way from memory to LDS.  Quantized: c = codes, s0 / s1 = eight scales (fp32,
+// or fp16 packed in s0 alone), z = eight zero-points (fp16); keys grouped per token: s0[0], s0[1] = scales and
+// z[0], z[1] = zero-points of the thread's two tokens, as fp32 bits.  fp16 rows (16-bit tensor or window): c and
+// s0 = two 16-byte row pieces.
+struct Staged { u32x4 c, s0, s1, z; };
 
 __device__ __forceinline__ float half_bits(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
 __device__ __forceinline__ float lo_half(uint32_t w) { return half_bits(w & 0xffffu); }
 __device__ __forceinline__ float hi_half(uint32_t w) { return half_bits(w >> 16); }
+__device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
 
 __device__ __forceinline__ uint32_t pack2(float a, float b)
 {
     const uint32_t lo = __builtin_bit_cast(uint16_t, (_Float16)a), hi = __builtin_bit_cast(uint16_t, (_Float16)b);
     return lo | (hi << 16);
 }
+__device__ __forceinline__ u32x4 pack8(const float *x)
+{
+    return u32x4{pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7])};
+}
 
 // ---- fp16 rows: thread tid takes 16-byte piece c16 of token t for idx = tid and tid + 256
-__device__ __forceinline__ void load_rows(const uint16_t *base, int ring, int pos0, int T, int tid, uint32_t *dst)
+__device__ __forceinline__ u32x4 load_row_piece(const uint16_t *base, int ring, int pos0, int T, int idx)
 {
+    const int t = idx >> 4, c16 = idx & 15, pos = pos0 + t;
+    u32x4 x = u32x4{0u, 0u, 0u, 0u};                       // tokens past the end read as zero (their weights are zero)
+    if (pos < T) x = ld16(base + (size_t)(ring ? pos % ring : pos) * kD + 8 * c16);
+    return x;
+}
+
+__device__ __forceinline__ void load_rows(const uint16_t *base, int ring, int pos0, int T, int tid, Staged &st)
+{
+    st.c = load_row_piece(base, ring, pos0, T, tid);
+    st.s0 = load_row_piece(base, ring, pos0, T, tid + 256);
+    st.s1 = u32x4{0u, 0u, 0u, 0u};
+    st.z = u32x4{0u, 0u, 0u, 0u};
+}
+
+__device__ __forceinline__ void store_key_rows(Tiles &L, int tid, const Staged &st)
+{
+    *reinterpret_cast<u32x4 *>(&L.K[tid >> 4][8 * (tid & 15)]) = st.c;
+    *reinterpret_cast<u32x4 *>(&L.K[16 + (tid >> 4)][8 * (tid & 15)]) = st.s0;
+}
+
+__device__ __forceinline__ void store_value_piece(Tiles &L, int idx, u32x4 x)
+{
+    const int t = idx >> 4, c16 = idx & 15;
 #pragma unroll
-    for (int r = 0; r < 2; r++) {
-        const int idx = tid + 256 * r, t = idx >> 4, c16 = idx & 15, pos = pos0 + t;
-        uint4 x = make_uint4(0, 0, 0, 0);                  // tokens past the end read as zero (their weights are zero)
-        if (pos < T) x = *reinterpret_cast<const uint4 *>(base + (size_t)(ring ? pos % ring : pos) * kD + 8 * c16);
-        dst[4 * r] = x.x; dst[4 * r + 1] = x.y; dst[4 * r + 2] = x.z; dst[4 * r + 3] = x.w;
+    for (int e = 0; e < 8; e++) {
+        const uint32_t w = x[e >> 1];
+        L.Vt[8 * c16 + e][t] = __builtin_bit_cast(_Float16, (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu));
     }
 }
 
-__device__ __forceinline__ void store_key_rows(Tiles &L, int tid, const uint32_t *src)
+__device__ __forceinline__ void store_value_rows(Tiles &L, int tid, const Staged &st)
 {
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-        const int idx = tid + 256 * r, t = idx >> 4, c16 = idx & 15;
-        *reinterpret_cast<uint4 *>(&L.K[t][8 * c16]) = make_uint4(src[4 * r], src[4 * r + 1], src[4 * r + 2], src[4 * r + 3]);
-    }
-}
-
-__device__ __forceinline__ void store_value_rows(Tiles &L, int tid, const uint32_t *src)
-{
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-        const int idx = tid + 256 * r, t = idx >> 4, c16 = idx & 15;
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const uint32_t w = src[4 * r + (e >> 1)];
-            L.Vt[8 * c16 + e][t] = __builtin_bit_cast(_Float16, (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu));
-        }
-    }
+    store_value_piece(L, tid, st.c);
+    store_value_piece(L, tid + 256, st.s0);
 }
 
 // ---- metadata: 8 consecutive scales and zero-points starting at index i0 (a multiple of 8)
-__device__ __forceinline__ void load_meta8(const float *meta, bool narrow, int i0, uint32_t *dst)
+__device__ __forceinline__ void load_meta8(const float *meta, bool narrow, int i0, Staged &st)
+{
+    // no branch: with fp16 scales the second load repeats the first (its result is not used)
+    const void *p0 = narrow ? static_cast<const void *>(meta_scales16(meta) + i0) : static_cast<const void *>(meta + i0);
+    const void *p1 = narrow ? p0 : static_cast<const void *>(meta + i0 + 4);
+    st.s0 = ld16(p0);
+    st.s1 = ld16(p1);
+    st.z = ld16(meta_zeros(meta, narrow) + i0);
+}
+
+// the eight scales and zero-points of a staged unit as fp32
+__device__ __forceinline__ void unpack_meta8(const Staged &st, bool narrow, float *s, float *z)
 {
     if (narrow) {
-        const uint4 s = *reinterpret_cast<const uint4 *>(meta_scales16(meta) + i0);
-        dst[4] = s.x; dst[5] = s.y; dst[6] = s.z; dst[7] = s.w;
+#pragma unroll
+        for (int e = 0; e < 8; e++) s[e] = (e & 1) ? hi_half(st.s0[e >> 1]) : lo_half(st.s0[e >> 1]);
     } else {
-        const uint4 s0 = *reinterpret_cast<const uint4 *>(meta + i0), s1 = *reinterpret_cast<const uint4 *>(meta + i0 + 4);
-        dst[4] = s0.x; dst[5] = s0.y; dst[6] = s0.z; dst[7] = s0.w;
-        dst[8] = s1.x; dst[9] = s1.y; dst[10] = s1.z; dst[11] = s1.w;
+#pragma unroll
+        for (int e = 0; e < 8; e++) s[e] = __builtin_bit_cast(float, e < 4 ? st.s0[e & 3] : st.s1[e & 3]);
     }
-    const uint4 z = *reinterpret_cast<const uint4 *>(meta_zeros(meta, narrow) + i0);
-    dst[12] = z.x; dst[13] = z.y; dst[14] = z.z; dst[15] = z.w;
+#pragma unroll
+    for (int e = 0; e < 8; e++) z[e] = (e & 1) ? hi_half(st.z[e >> 1]) : lo_half(st.z[e >> 1]);
 }
-
-__device__ __forceinline__ float scale8(const uint32_t *st, bool narrow, int e)
-{
-    return narrow ? ((e & 1) ? hi_half(st[4 + (e >> 1)]) : lo_half(st[4 + (e >> 1)])) : __builtin_bit_cast(float, st[4 + e]);
-}
-__device__ __forceinline__ float zero8(const uint32_t *st, int e) { return (e & 1) ? hi_half(st[12 + (e >> 1)]) : lo_half(st[12 + (e >> 1)]); }
 
 // code e (0..7) of the group of eight codes numbered m, from the dwords w0, w1 that hold it
-__device__ __forceinline__ float code_of(int bits, uint32_t w0, uint32_t w1, int m, int e)
+template <int BITS>
+__device__ __forceinline__ float code_of(uint32_t w0, uint32_t w1, int m, int e)
 {
-    if (bits == 8) return (float)(((e < 4 ? w0 : w1) >> (8 * (e & 3))) & 255u);
-    if (bits == 4) return (float)((w0 >> (4 * ((e >> 1) + 4 * (e & 1)))) & 15u);
-    return (float)((w0 >> (2 * (4 * (m & 1) + (e >> 1) + 8 * (e & 1)))) & 3u);
+    if constexpr (BITS == 8) return (float)(((e < 4 ? w0 : w1) >> (8 * (e & 3))) & 255u);
+    else if constexpr (BITS == 4) return (float)((w0 >> (4 * ((e >> 1) + 4 * (e & 1)))) & 15u);
+    else return (float)((w0 >> (2 * (4 * (m & 1) + (e >> 1) + 8 * (e & 1)))) & 3u);
 }
 
 // ---- quantized keys: thread (lane l, channel group cb = tid >> 6) takes the code groups m = cb (token n) and
-// m = 4 + cb (token 16 + n), channels 32 cb + 8 kq .. + 7
-__device__ __forceinline__ void load_key_codes(const LayerView &lv, size_t blk, int tid, uint32_t *st)
+// m = 4 + cb (token 16 + n), channels 32 cb + 8 kq .. + 7.  c[0], c[1]: dwords of the first group, c[2], c[3]: second.
+__device__ __forceinline__ void load_key_codes(const LayerView &lv, size_t blk, int tid, Staged &st)
 {
     const int l = tid & 63, cb = tid >> 6, kb = lv.kbits;
     const uint8_t *block = lv.kcode + blk * (size_t)block_code_bytes(kb);
     const bool narrow = lv.narrow != 0;
     const float *meta = lv.kmeta + blk * (size_t)meta_words(narrow);
-    if (kb == 8) {
-        const uint2 a = *reinterpret_cast<const uint2 *>(block + dword_offset(l, 2 * cb));
-        const uint2 b = *reinterpret_cast<const uint2 *>(block + dword_offset(l, 8 + 2 * cb));
-        st[0] = a.x; st[1] = a.y; st[2] = b.x; st[3] = b.y;
-    } else if (kb == 4) {
-        st[0] = *reinterpret_cast<const uint32_t *>(block + dword_offset(l, cb));
-        st[2] = *reinterpret_cast<const uint32_t *>(block + dword_offset(l, 4 + cb));
-    } else {
-        st[0] = *reinterpret_cast<const uint32_t *>(block + dword_offset(l, cb >> 1));
-        st[2] = *reinterpret_cast<const uint32_t *>(block + dword_offset(l, 2 + (cb >> 1)));
-    }
+    // first dword of the two groups: 8 bit -> dwords 2 m, 2 m + 1; 4 bit -> dword m; 2 bit -> dword m / 2
+    const int d0 = kb == 8 ? 2 * cb : kb == 4 ? cb : cb >> 1;
+    const int d1 = kb == 8 ? 8 + 2 * cb : kb == 4 ? 4 + cb : 2 + (cb >> 1);
+    const uint32_t *p0 = reinterpret_cast<const uint32_t *>(block + dword_offset(l, d0));
+    const uint32_t *p1 = reinterpret_cast<const uint32_t *>(block + dword_offset(l, d1));
+    // the odd dword of an 8-bit group lies in the same 16-byte chunk; narrower codes load the even one twice
+    const int odd = kb == 8 ? 1 : 0;
+    st.c = u32x4{p0[0], p0[odd], p1[0], p1[odd]};
     if (lv.kpt) {
         // one (s, z) per token and channel group: index 32 * group + token
         const int n = l & 15;
-#pragma unroll
-        for (int th = 0; th < 2; th++) {
-            const int i = 32 * cb + 16 * th + n;
-            st[4 + th] = __builtin_bit_cast(uint32_t, narrow ? half_bits(meta_scales16(meta)[i]) : meta[i]);
-            st[6 + th] = __builtin_bit_cast(uint32_t, half_bits(meta_zeros(meta, narrow)[i]));
-        }
+        const int i0 = 32 * cb + n, i1 = i0 + 16;
+        st.s0 = u32x4{__builtin_bit_cast(uint32_t, narrow ? half_bits(meta_scales16(meta)[i0]) : meta[i0]),
+                      __builtin_bit_cast(uint32_t, narrow ? half_bits(meta_scales16(meta)[i1]) : meta[i1]), 0u, 0u};
+        st.s1 = u32x4{0u, 0u, 0u, 0u};
+        st.z = u32x4{__builtin_bit_cast(uint32_t, half_bits(meta_zeros(meta, narrow)[i0])),
+                     __builtin_bit_cast(uint32_t, half_bits(meta_zeros(meta, narrow)[i1])), 0u, 0u};
     } else {
         load_meta8(meta, narrow, 32 * cb + 8 * (l >> 4), st);
     }
 }
 
-__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, int tid, const uint32_t *st)
+template <int BITS>
+__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, int tid, const Staged &st)
 {
-    const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4, kb = lv.kbits;
-    const bool narrow = lv.narrow != 0, kpt = lv.kpt != 0;
+    const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
+    const bool kpt = lv.kpt != 0;
+    float s[8], z[8];
+    unpack_meta8(st, lv.narrow != 0, s, z);                  // (grouped per token: not used)
 #pragma unroll
     for (int th = 0; th < 2; th++) {
+        const float st_ = __builtin_bit_cast(float, th == 0 ? st.s0[0] : st.s0[1]);
+        const float zt_ = __builtin_bit_cast(float, th == 0 ? st.z[0] : st.z[1]);
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const float c = code_of(kb, st[2 * th], st[2 * th + 1], cb, e);      // m = 4 th + cb: m & 1 == cb & 1
-            const float s = kpt ? __builtin_bit_cast(float, st[4 + th]) : scale8(st, narrow, e);
-            const float z = kpt ? __builtin_bit_cast(float, st[6 + th]) : zero8(st, e);
-            x[e] = fmaf(c, s, z);
-        }
-        *reinterpret_cast<uint4 *>(&L.K[16 * th + n][32 * cb + 8 * kq]) =
-            make_uint4(pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7]));
+        for (int e = 0; e < 8; e++)      // m = 4 th + cb: m & 1 == cb & 1
+            x[e] = fmaf(code_of<BITS>(st.c[2 * th], st.c[2 * th + 1], cb, e), kpt ? st_ : s[e], kpt ? zt_ : z[e]);
+        *reinterpret_cast<u32x4 *>(&L.K[16 * th + n][32 * cb + 8 * kq]) = pack8(x);
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
-        *reinterpret_cast<uint4 *>(&L.Klo[16 * th + n][32 * cb + 8 * kq]) =
-            make_uint4(pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7]));
+        *reinterpret_cast<u32x4 *>(&L.Klo[16 * th + n][32 * cb + 8 * kq]) = pack8(x);
     }
 }
 
 // ---- quantized values: thread (lane l, channel group g = tid >> 6) takes the code groups m = 2 g, 2 g + 1
 // (channels 16 m + n), tokens 8 kq .. + 7; both share the metadata of group g
-__device__ __forceinline__ void load_value_codes(const LayerView &lv, size_t blk, int tid, uint32_t *st)
+__device__ __forceinline__ void load_value_codes(const LayerView &lv, size_t blk, int tid, Staged &st)
 {
     const int l = tid & 63, g = tid >> 6, vb = lv.vbits;
     const uint8_t *block = lv.vcode + blk * (size_t)block_code_bytes(vb);
     const bool narrow = lv.narrow != 0;
     const float *meta = lv.vmeta + blk * (size_t)meta_words(narrow);
-    if (vb == 8) {
-        const uint4 a = *reinterpret_cast<const uint4 *>(block + dword_offset(l, 4 * g));
-        st[0] = a.x; st[1] = a.y; st[2] = a.z; st[3] = a.w;
-    } else if (vb == 4) {
-        const uint2 a = *reinterpret_cast<const uint2 *>(block + dword_offset(l, 2 * g));
-        st[0] = a.x; st[1] = a.y;
-    } else {
-        st[0] = *reinterpret_cast<const uint32_t *>(block + dword_offset(l, g));
-    }
+    // 8 bit: dwords 4 g .. 4 g + 3 (one chunk); 4 bit: dwords 2 g, 2 g + 1; 2 bit: dword g
+    const uint32_t *p = reinterpret_cast<const uint32_t *>(block + dword_offset(l, vb == 8 ? 4 * g : vb == 4 ? 2 * g : g));
+    // dwords beyond the width's own are loaded from the first again, not from beyond the lane's chunk
+    st.c = u32x4{p[0], p[vb >= 4 ? 1 : 0], p[vb == 8 ? 2 : 0], p[vb == 8 ? 3 : 0]};
     load_meta8(meta, narrow, 32 * g + 8 * (l >> 4), st);
 }
 
-__device__ __forceinline__ void store_value_codes(const LayerView &lv, Tiles &L, int tid, const uint32_t *st)
+template <int BITS>
+__device__ __forceinline__ void store_value_codes(const LayerView &lv, Tiles &L, int tid, const Staged &st)
 {
-    const int l = tid & 63, g = tid >> 6, n = l & 15, kq = l >> 4, vb = lv.vbits;
-    const bool narrow = lv.narrow != 0;
+    const int l = tid & 63, g = tid >> 6, n = l & 15, kq = l >> 4;
+    float s[8], z[8];
+    unpack_meta8(st, lv.narrow != 0, s, z);
 #pragma unroll
     for (int mm = 0; mm < 2; mm++) {
-        const uint32_t w0 = vb == 8 ? st[2 * mm] : vb == 4 ? st[mm] : st[0];
-        const uint32_t w1 = st[2 * mm + 1];
+        const uint32_t w0 = BITS == 8 ? st.c[2 * mm] : BITS == 4 ? st.c[mm] : st.c[0];
+        const uint32_t w1 = st.c[2 * mm + 1];
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = fmaf(code_of(vb, w0, w1, mm, e), scale8(st, narrow, e), zero8(st, e));
-        *reinterpret_cast<uint4 *>(&L.Vt[16 * (2 * g + mm) + n][8 * kq]) =
-            make_uint4(pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7]));
+        for (int e = 0; e < 8; e++) x[e] = fmaf(code_of<BITS>(w0, w1, mm, e), s[e], z[e]);
+        *reinterpret_cast<u32x4 *>(&L.Vt[16 * (2 * g + mm) + n][8 * kq]) = pack8(x);
     }
 }
 
 // ---- one unit: memory -> registers, registers -> LDS
+struct Stage { Staged k, v; };
+
 __device__ __forceinline__ void load_unit(const PrefillArgs &a, int bh, int u, int T, int tid, Stage &st)
 {
     const bool packed = u < a.n_blocks;
@@ -226,9 +238,13 @@ __device__ __forceinline__ void load_unit(const PrefillArgs &a, int bh, int u, i
 __device__ __forceinline__ void store_unit(const PrefillArgs &a, int u, int tid, const Stage &st, Tiles &L)
 {
     const bool packed = u < a.n_blocks;
-    if (packed && a.lv.kbits < 16) store_key_codes(a.lv, L, tid, st.k);
+    if (packed && a.lv.kbits == 8) store_key_codes<8>(a.lv, L, tid, st.k);
+    else if (packed && a.lv.kbits == 4) store_key_codes<4>(a.lv, L, tid, st.k);
+    else if (packed && a.lv.kbits == 2) store_key_codes<2>(a.lv, L, tid, st.k);
     else store_key_rows(L, tid, st.k);
-    if (packed && a.lv.vbits < 16) store_value_codes(a.lv, L, tid, st.v);
+    if (packed && a.lv.vbits == 8) store_value_codes<8>(a.lv, L, tid, st.v);
+    else if (packed && a.lv.vbits == 4) store_value_codes<4>(a.lv, L, tid, st.v);
+    else if (packed && a.lv.vbits == 2) store_value_codes<2>(a.lv, L, tid, st.v);
     else store_value_rows(L, tid, st.v);
 }
 
