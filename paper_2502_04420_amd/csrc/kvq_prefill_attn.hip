@@ -32,7 +32,7 @@ constexpr int kWaves = 4;
 constexpr int kQW = 32;                 // queries per wave
 constexpr int kQB = kQW * kWaves;       // queries per work-group
 constexpr int kKStride = kD + 8;        // halves per K^ row (272 bytes: the 16 rows of a 16-byte read fall on different banks)
-constexpr int kVStride = 32 + 8;        // halves per V^ channel row (80 bytes, 16-byte aligned rows)
+constexpr int kVStride = 32 + 4;        // halves per V^ channel row (72 bytes = 18 banks: the 16 rows of an 8-byte read fall on different banks)
 
 struct Tiles {
     _Float16 K[32][kKStride];           // K^[token][channel], rounded to fp16
@@ -42,16 +42,31 @@ struct Tiles {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Registers of one tensor's unit on its way from memory to LDS.  Quantized: c = codes, s0 / s1 = eight scales (fp32,
-// or fp16 packed in s0 alone), z = eight zero-points (fp16); keys grouped per token: s0[0], s0[1] = scales and
-// z[0], z[1] = zero-points of the thread's two tokens, as fp32 bits.  fp16 rows (16-bit tensor or window): c and
-// s0 = two 16-byte row pieces.
-struct Staged { u32x4 c, s0, s1, z; };
+// Metadata of the unit being dequantized, one slab per wave (wave w dequantizes channel group w of the keys and of the
+// values, so it needs 32 scales and 32 zero-points of each tensor and nobody else's): written and read by the same
+// wave, no work-group barrier in between.
+struct MetaSlab {
+    uint32_t ks[32];     // key scales (fp32, or 32 fp16 numbers in the first 16 dwords)
+    uint16_t kz[32];     // key zero-points
+    uint32_t vs[32];     // value scales
+    uint16_t vz[32];     // value zero-points
+};
+
+// Registers of a unit on its way from memory to LDS.  Quantized tensor: k0 / v0 = the dwords of the thread's two code
+// groups; fp16 rows (16-bit tensor or window): k0, k1 / v0, v1 = two 16-byte row pieces.  m = this lane's 16-byte
+// piece of the wave's metadata (lanes 0..23).
+struct Stage { u32x4 k0, k1, v0, v1, m; };
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 __device__ __forceinline__ float half_bits(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
-__device__ __forceinline__ float lo_half(uint32_t w) { return half_bits(w & 0xffffu); }
-__device__ __forceinline__ float hi_half(uint32_t w) { return half_bits(w >> 16); }
 __device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 zero4() { return u32x4{0u, 0u, 0u, 0u}; }
 
 __device__ __forceinline__ uint32_t pack2(float a, float b)
 {
@@ -63,68 +78,45 @@ __device__ __forceinline__ u32x4 pack8(const float *x)
     return u32x4{pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7])};
 }
 
-// ---- fp16 rows: thread tid takes 16-byte piece c16 of token t for idx = tid and tid + 256
+// ---- fp16 rows: thread tid takes 16-byte piece c16 of token t for idx = tid and tid + 256.  A token past the end reads
+// the last one instead; it is zeroed on its way to LDS (an operation on the loaded value right here would make the
+// wave wait for the load where it is issued).
 __device__ __forceinline__ u32x4 load_row_piece(const uint16_t *base, int ring, int pos0, int T, int idx)
 {
-    const int t = idx >> 4, c16 = idx & 15, pos = pos0 + t;
-    u32x4 x = u32x4{0u, 0u, 0u, 0u};                       // tokens past the end read as zero (their weights are zero)
-    if (pos < T) x = ld16(base + (size_t)(ring ? pos % ring : pos) * kD + 8 * c16);
-    return x;
+    const int t = idx >> 4, c16 = idx & 15, pos = pos0 + t, pc = pos < T ? pos : T - 1;
+    return ld16(base + (size_t)(ring ? pc % ring : pc) * kD + 8 * c16);
 }
 
-__device__ __forceinline__ void load_rows(const uint16_t *base, int ring, int pos0, int T, int tid, Staged &st)
+// tokens past the end count as zero (their weights are zero)
+__device__ __forceinline__ u32x4 live_piece(u32x4 x, int pos0, int T, int idx)
 {
-    st.c = load_row_piece(base, ring, pos0, T, tid);
-    st.s0 = load_row_piece(base, ring, pos0, T, tid + 256);
-    st.s1 = u32x4{0u, 0u, 0u, 0u};
-    st.z = u32x4{0u, 0u, 0u, 0u};
+    const bool live = pos0 + (idx >> 4) < T;
+    return u32x4{live ? x[0] : 0u, live ? x[1] : 0u, live ? x[2] : 0u, live ? x[3] : 0u};
 }
 
-__device__ __forceinline__ void store_key_rows(Tiles &L, int tid, const Staged &st)
+__device__ __forceinline__ void store_key_rows(Tiles &L, int tid, u32x4 r0, u32x4 r1)
 {
-    *reinterpret_cast<u32x4 *>(&L.K[tid >> 4][8 * (tid & 15)]) = st.c;
-    *reinterpret_cast<u32x4 *>(&L.K[16 + (tid >> 4)][8 * (tid & 15)]) = st.s0;
+    *reinterpret_cast<u32x4 *>(&L.K[tid >> 4][8 * (tid & 15)]) = r0;
+    *reinterpret_cast<u32x4 *>(&L.K[16 + (tid >> 4)][8 * (tid & 15)]) = r1;
 }
 
-__device__ __forceinline__ void store_value_piece(Tiles &L, int idx, u32x4 x)
+// value rows are staged with the token index fastest across the lanes (piece idx: token idx & 31, 16-byte piece
+// idx >> 5): the transposed 2-byte writes of a wave then fall on consecutive addresses instead of on two banks
+__device__ __forceinline__ u32x4 load_value_row_piece(const uint16_t *base, int ring, int pos0, int T, int idx)
 {
-    const int t = idx >> 4, c16 = idx & 15;
+    const int t = idx & 31, c16 = idx >> 5, pos = pos0 + t, pc = pos < T ? pos : T - 1;
+    return ld16(base + (size_t)(ring ? pc % ring : pc) * kD + 8 * c16);
+}
+
+__device__ __forceinline__ void store_value_piece(Tiles &L, int idx, u32x4 x, int pos0, int T)
+{
+    const int t = idx & 31, c16 = idx >> 5;
+    const bool live = pos0 + t < T;                        // tokens past the end count as zero
 #pragma unroll
     for (int e = 0; e < 8; e++) {
         const uint32_t w = x[e >> 1];
-        L.Vt[8 * c16 + e][t] = __builtin_bit_cast(_Float16, (uint16_t)((e & 1) ? w >> 16 : w & 0xffffu));
+        L.Vt[8 * c16 + e][t] = __builtin_bit_cast(_Float16, (uint16_t)(live ? ((e & 1) ? w >> 16 : w & 0xffffu) : 0u));
     }
-}
-
-__device__ __forceinline__ void store_value_rows(Tiles &L, int tid, const Staged &st)
-{
-    store_value_piece(L, tid, st.c);
-    store_value_piece(L, tid + 256, st.s0);
-}
-
-// ---- metadata: 8 consecutive scales and zero-points starting at index i0 (a multiple of 8)
-__device__ __forceinline__ void load_meta8(const float *meta, bool narrow, int i0, Staged &st)
-{
-    // no branch: with fp16 scales the second load repeats the first (its result is not used)
-    const void *p0 = narrow ? static_cast<const void *>(meta_scales16(meta) + i0) : static_cast<const void *>(meta + i0);
-    const void *p1 = narrow ? p0 : static_cast<const void *>(meta + i0 + 4);
-    st.s0 = ld16(p0);
-    st.s1 = ld16(p1);
-    st.z = ld16(meta_zeros(meta, narrow) + i0);
-}
-
-// the eight scales and zero-points of a staged unit as fp32
-__device__ __forceinline__ void unpack_meta8(const Staged &st, bool narrow, float *s, float *z)
-{
-    if (narrow) {
-#pragma unroll
-        for (int e = 0; e < 8; e++) s[e] = (e & 1) ? hi_half(st.s0[e >> 1]) : lo_half(st.s0[e >> 1]);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; e++) s[e] = __builtin_bit_cast(float, e < 4 ? st.s0[e & 3] : st.s1[e & 3]);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; e++) z[e] = (e & 1) ? hi_half(st.z[e >> 1]) : lo_half(st.z[e >> 1]);
 }
 
 // code e (0..7) of the group of eight codes numbered m, from the dwords w0, w1 that hold it
@@ -137,119 +129,267 @@ __device__ __forceinline__ float code_of(uint32_t w0, uint32_t w1, int m, int e)
 }
 
 // ---- quantized keys: thread (lane l, channel group cb = tid >> 6) takes the code groups m = cb (token n) and
-// m = 4 + cb (token 16 + n), channels 32 cb + 8 kq .. + 7.  c[0], c[1]: dwords of the first group, c[2], c[3]: second.
-__device__ __forceinline__ void load_key_codes(const LayerView &lv, size_t blk, int tid, Staged &st)
+// m = 4 + cb (token 16 + n), channels 32 cb + 8 kq .. + 7.  Returned: [0], [1] dwords of the first group, [2], [3] of
+// the second.  Always four loads (codes narrower than 8 bits load their one dword twice): the number of loads in
+// flight does not depend on the bit width.
+__device__ __forceinline__ u32x4 load_key_codes(const LayerView &lv, size_t blk, int tid)
 {
     const int l = tid & 63, cb = tid >> 6, kb = lv.kbits;
     const uint8_t *block = lv.kcode + blk * (size_t)block_code_bytes(kb);
-    const bool narrow = lv.narrow != 0;
-    const float *meta = lv.kmeta + blk * (size_t)meta_words(narrow);
-    // first dword of the two groups: 8 bit -> dwords 2 m, 2 m + 1; 4 bit -> dword m; 2 bit -> dword m / 2
+    // first dword of the two groups: 8 bit -> dwords 2 m, 2 m + 1 (same 16-byte chunk); 4 bit -> dword m; 2 bit -> dword m / 2
     const int d0 = kb == 8 ? 2 * cb : kb == 4 ? cb : cb >> 1;
     const int d1 = kb == 8 ? 8 + 2 * cb : kb == 4 ? 4 + cb : 2 + (cb >> 1);
     const uint32_t *p0 = reinterpret_cast<const uint32_t *>(block + dword_offset(l, d0));
     const uint32_t *p1 = reinterpret_cast<const uint32_t *>(block + dword_offset(l, d1));
-    // the odd dword of an 8-bit group lies in the same 16-byte chunk; narrower codes load the even one twice
     const int odd = kb == 8 ? 1 : 0;
-    st.c = u32x4{p0[0], p0[odd], p1[0], p1[odd]};
-    if (lv.kpt) {
-        // one (s, z) per token and channel group: index 32 * group + token
-        const int n = l & 15;
-        const int i0 = 32 * cb + n, i1 = i0 + 16;
-        st.s0 = u32x4{__builtin_bit_cast(uint32_t, narrow ? half_bits(meta_scales16(meta)[i0]) : meta[i0]),
-                      __builtin_bit_cast(uint32_t, narrow ? half_bits(meta_scales16(meta)[i1]) : meta[i1]), 0u, 0u};
-        st.s1 = u32x4{0u, 0u, 0u, 0u};
-        st.z = u32x4{__builtin_bit_cast(uint32_t, half_bits(meta_zeros(meta, narrow)[i0])),
-                     __builtin_bit_cast(uint32_t, half_bits(meta_zeros(meta, narrow)[i1])), 0u, 0u};
-    } else {
-        load_meta8(meta, narrow, 32 * cb + 8 * (l >> 4), st);
-    }
-}
-
-template <int BITS>
-__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, int tid, const Staged &st)
-{
-    const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
-    const bool kpt = lv.kpt != 0;
-    float s[8], z[8];
-    unpack_meta8(st, lv.narrow != 0, s, z);                  // (grouped per token: not used)
-#pragma unroll
-    for (int th = 0; th < 2; th++) {
-        const float st_ = __builtin_bit_cast(float, th == 0 ? st.s0[0] : st.s0[1]);
-        const float zt_ = __builtin_bit_cast(float, th == 0 ? st.z[0] : st.z[1]);
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++)      // m = 4 th + cb: m & 1 == cb & 1
-            x[e] = fmaf(code_of<BITS>(st.c[2 * th], st.c[2 * th + 1], cb, e), kpt ? st_ : s[e], kpt ? zt_ : z[e]);
-        *reinterpret_cast<u32x4 *>(&L.K[16 * th + n][32 * cb + 8 * kq]) = pack8(x);
-#pragma unroll
-        for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
-        *reinterpret_cast<u32x4 *>(&L.Klo[16 * th + n][32 * cb + 8 * kq]) = pack8(x);
-    }
+    return u32x4{p0[0], p0[odd], p1[0], p1[odd]};
 }
 
 // ---- quantized values: thread (lane l, channel group g = tid >> 6) takes the code groups m = 2 g, 2 g + 1
-// (channels 16 m + n), tokens 8 kq .. + 7; both share the metadata of group g
-__device__ __forceinline__ void load_value_codes(const LayerView &lv, size_t blk, int tid, Staged &st)
+// (channels 16 m + n), tokens 8 kq .. + 7.  8 bit: dwords 4 g .. 4 g + 3 (one chunk); 4 bit: dwords 2 g, 2 g + 1;
+// 2 bit: dword g; dwords beyond the width's own are loaded from the first again.
+__device__ __forceinline__ u32x4 load_value_codes(const LayerView &lv, size_t blk, int tid)
 {
     const int l = tid & 63, g = tid >> 6, vb = lv.vbits;
     const uint8_t *block = lv.vcode + blk * (size_t)block_code_bytes(vb);
-    const bool narrow = lv.narrow != 0;
-    const float *meta = lv.vmeta + blk * (size_t)meta_words(narrow);
-    // 8 bit: dwords 4 g .. 4 g + 3 (one chunk); 4 bit: dwords 2 g, 2 g + 1; 2 bit: dword g
     const uint32_t *p = reinterpret_cast<const uint32_t *>(block + dword_offset(l, vb == 8 ? 4 * g : vb == 4 ? 2 * g : g));
-    // dwords beyond the width's own are loaded from the first again, not from beyond the lane's chunk
-    st.c = u32x4{p[0], p[vb >= 4 ? 1 : 0], p[vb == 8 ? 2 : 0], p[vb == 8 ? 3 : 0]};
-    load_meta8(meta, narrow, 32 * g + 8 * (l >> 4), st);
+    return u32x4{p[0], p[vb >= 4 ? 1 : 0], p[vb == 8 ? 2 : 0], p[vb == 8 ? 3 : 0]};
 }
 
-template <int BITS>
-__device__ __forceinline__ void store_value_codes(const LayerView &lv, Tiles &L, int tid, const Staged &st)
+// ---- this lane's piece of the wave's metadata: lanes 0..11 keys, 12..23 values; of each, pieces 0..7 are the 32
+// scales of channel group w (fp16 scales: pieces 0..3 only) and 8..11 the 32 zero-points
+__device__ __forceinline__ u32x4 load_meta_piece(const LayerView &lv, size_t blk, int wave, int lane, bool kq, bool vq)
 {
-    const int l = tid & 63, g = tid >> 6, n = l & 15, kq = l >> 4;
-    float s[8], z[8];
-    unpack_meta8(st, lv.narrow != 0, s, z);
-#pragma unroll
-    for (int mm = 0; mm < 2; mm++) {
-        const uint32_t w0 = BITS == 8 ? st.c[2 * mm] : BITS == 4 ? st.c[mm] : st.c[0];
-        const uint32_t w1 = st.c[2 * mm + 1];
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = fmaf(code_of<BITS>(w0, w1, mm, e), s[e], z[e]);
-        *reinterpret_cast<u32x4 *>(&L.Vt[16 * (2 * g + mm) + n][8 * kq]) = pack8(x);
+    const bool narrow = lv.narrow != 0;
+    const int tensor = lane >= 12 ? 1 : 0, j = lane - 12 * tensor;
+    const float *meta = (tensor ? lv.vmeta : lv.kmeta) + blk * (size_t)meta_words(narrow);
+    const bool wanted = lane < 24 && (tensor ? vq : kq) && !(narrow && j >= 4 && j < 8);
+    const uint8_t *src = j < 8 ? reinterpret_cast<const uint8_t *>(meta) + (narrow ? 64 : 128) * wave + 16 * j
+                               : reinterpret_cast<const uint8_t *>(meta_zeros(meta, narrow)) + 64 * wave + 16 * (j - 8);
+    // lanes with nothing to fetch read the start of the key codes instead (the result is not used): one load per unit
+    // on every path
+    return ld16(wanted ? src : lv.kcode);
+}
+
+__device__ __forceinline__ void store_meta_piece(MetaSlab &M, int lane, u32x4 x)
+{
+    if (lane < 24) {
+        const int tensor = lane >= 12 ? 1 : 0, j = lane - 12 * tensor;
+        uint32_t *dst = j < 8 ? (tensor ? M.vs : M.ks) + 4 * j : reinterpret_cast<uint32_t *>(tensor ? M.vz : M.kz) + 4 * (j - 8);
+        *reinterpret_cast<u32x4 *>(dst) = x;
     }
 }
 
-// ---- one unit: memory -> registers, registers -> LDS
-struct Stage { Staged k, v; };
-
-__device__ __forceinline__ void load_unit(const PrefillArgs &a, int bh, int u, int T, int tid, Stage &st)
+// eight consecutive scales / zero-points of a slab, starting at index i0 (a multiple of 8), as fp32
+__device__ __forceinline__ void slab_meta8(const uint32_t *scales, const uint16_t *zeros, bool narrow, int i0, float *s, float *z)
 {
-    const bool packed = u < a.n_blocks;
-    const size_t blk = (size_t)bh * a.NB + u;
-    if (packed && a.lv.kbits < 16) load_key_codes(a.lv, blk, tid, st.k);
-    else if (packed) load_rows(reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD, 0, 32 * u, T, tid, st.k);
-    else load_rows(a.lv.kres + (size_t)bh * a.RC * kD, a.RC, 32 * u, T, tid, st.k);
-    if (packed && a.lv.vbits < 16) load_value_codes(a.lv, blk, tid, st.v);
-    else if (packed) load_rows(reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD, 0, 32 * u, T, tid, st.v);
-    else load_rows(a.lv.vres + (size_t)bh * a.RC * kD, a.RC, 32 * u, T, tid, st.v);
+    if (narrow) {
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(scales) + i0);
+#pragma unroll
+        for (int e = 0; e < 8; e++) s[e] = half_bits((e & 1) ? a[e >> 1] >> 16 : a[e >> 1] & 0xffffu);
+    } else {
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(scales + i0), b = *reinterpret_cast<const u32x4 *>(scales + i0 + 4);
+#pragma unroll
+        for (int e = 0; e < 8; e++) s[e] = __builtin_bit_cast(float, e < 4 ? a[e & 3] : b[e & 3]);
+    }
+    const u32x4 c = *reinterpret_cast<const u32x4 *>(zeros + i0);
+#pragma unroll
+    for (int e = 0; e < 8; e++) z[e] = half_bits((e & 1) ? c[e >> 1] >> 16 : c[e >> 1] & 0xffffu);
 }
 
-__device__ __forceinline__ void store_unit(const PrefillArgs &a, int u, int tid, const Stage &st, Tiles &L)
+template <int BITS, bool KPT>
+__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c)
 {
-    const bool packed = u < a.n_blocks;
-    if (packed && a.lv.kbits == 8) store_key_codes<8>(a.lv, L, tid, st.k);
-    else if (packed && a.lv.kbits == 4) store_key_codes<4>(a.lv, L, tid, st.k);
-    else if (packed && a.lv.kbits == 2) store_key_codes<2>(a.lv, L, tid, st.k);
-    else store_key_rows(L, tid, st.k);
-    if (packed && a.lv.vbits == 8) store_value_codes<8>(a.lv, L, tid, st.v);
-    else if (packed && a.lv.vbits == 4) store_value_codes<4>(a.lv, L, tid, st.v);
-    else if (packed && a.lv.vbits == 2) store_value_codes<2>(a.lv, L, tid, st.v);
-    else store_value_rows(L, tid, st.v);
+    const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
+    const bool narrow = lv.narrow != 0;
+    float s[8], z[8];
+    if constexpr (!KPT) slab_meta8(M.ks, M.kz, narrow, 8 * kq, s, z);          // one (s, z) per channel
+#pragma unroll
+    for (int th = 0; th < 2; th++) {
+        const int t = 16 * th + n;
+        if constexpr (KPT) {
+            // grouped per token: one (s, z) for this token and channel group
+            const float st_ = narrow ? half_bits(reinterpret_cast<const uint16_t *>(M.ks)[t]) : __builtin_bit_cast(float, M.ks[t]);
+            const float zt_ = half_bits(M.kz[t]);
+#pragma unroll
+            for (int e = 0; e < 8; e++) { s[e] = st_; z[e] = zt_; }
+        }
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++)      // m = 4 th + cb: m & 1 == cb & 1
+            x[e] = fmaf(code_of<BITS>(th == 0 ? c[0] : c[2], th == 0 ? c[1] : c[3], cb, e), s[e], z[e]);
+        *reinterpret_cast<u32x4 *>(&L.K[t][32 * cb + 8 * kq]) = pack8(x);
+#pragma unroll
+        for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
+        *reinterpret_cast<u32x4 *>(&L.Klo[t][32 * cb + 8 * kq]) = pack8(x);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void store_value_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c)
+{
+    const int l = tid & 63, g = tid >> 6, n = l & 15, kq = l >> 4;
+    float s[8], z[8];
+    slab_meta8(M.vs, M.vz, lv.narrow != 0, 8 * kq, s, z);
+#pragma unroll
+    for (int mm = 0; mm < 2; mm++) {
+        const uint32_t w0 = BITS == 8 ? (mm == 0 ? c[0] : c[2]) : BITS == 4 ? (mm == 0 ? c[0] : c[1]) : c[0];
+        const uint32_t w1 = mm == 0 ? c[1] : c[3];
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) x[e] = fmaf(code_of<BITS>(w0, w1, mm, e), s[e], z[e]);
+        const u32x4 h = pack8(x);                          // rows are 8-byte aligned only
+        uint2 *dst = reinterpret_cast<uint2 *>(&L.Vt[16 * (2 * g + mm) + n][8 * kq]);
+        dst[0] = make_uint2(h[0], h[1]);
+        dst[1] = make_uint2(h[2], h[3]);
+    }
+}
+
+// ---- one packed unit: memory -> registers, registers -> LDS.  KQ / VQ: the layer's keys / values are quantized
+// (else fp16 rows in the code area).  Nothing in load_packed branches around a load, so the compiler can count the
+// loads in flight exactly and wait for one register stage while the next stays in flight.
+template <bool KQ, bool VQ>
+__device__ __forceinline__ void load_packed(const PrefillArgs &a, int bh, int u, int T, int tid, Stage &st)
+{
+    const size_t blk = (size_t)bh * a.NB + u;
+    if constexpr (KQ) {
+        st.k0 = load_key_codes(a.lv, blk, tid);
+        st.k1 = zero4();
+    } else {
+        const uint16_t *rows = reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD;
+        st.k0 = load_row_piece(rows, 0, 32 * u, T, tid);
+        st.k1 = load_row_piece(rows, 0, 32 * u, T, tid + 256);
+    }
+    if constexpr (VQ) {
+        st.v0 = load_value_codes(a.lv, blk, tid);
+        st.v1 = zero4();
+    } else {
+        const uint16_t *rows = reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD;
+        st.v0 = load_value_row_piece(rows, 0, 32 * u, T, tid);
+        st.v1 = load_value_row_piece(rows, 0, 32 * u, T, tid + 256);
+    }
+    if constexpr (KQ || VQ) st.m = load_meta_piece(a.lv, blk, tid >> 6, tid & 63, KQ, VQ);
+    else st.m = zero4();
+}
+
+template <bool KQ, bool VQ>
+__device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, const Stage &st, Tiles &L, MetaSlab &M)
+{
+    if constexpr (KQ || VQ) {
+        wave_lds_sync();                                   // the slab's readers of the unit before are done
+        store_meta_piece(M, tid & 63, st.m);
+        wave_lds_sync();
+    }
+    if constexpr (KQ) {
+        if (a.lv.kpt) {
+            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0);
+            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0);
+            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0);
+        } else {
+            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0);
+            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0);
+            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0);
+        }
+    } else {
+        store_key_rows(L, tid, st.k0, st.k1);
+    }
+    if constexpr (VQ) {
+        if (a.lv.vbits == 8) store_value_codes<8>(a.lv, L, M, tid, st.v0);
+        else if (a.lv.vbits == 4) store_value_codes<4>(a.lv, L, M, tid, st.v0);
+        else store_value_codes<2>(a.lv, L, M, tid, st.v0);
+    } else {
+        store_value_piece(L, tid, st.v0, 0, 32);
+        store_value_piece(L, tid + 256, st.v1, 0, 32);
+    }
+}
+
+// ---- one chunk of the fp16 window (at most two per work-group: staged without overlap)
+__device__ __forceinline__ void stage_window(const PrefillArgs &a, int bh, int u, int T, int tid, Tiles &L)
+{
+    const uint16_t *krows = a.lv.kres + (size_t)bh * a.RC * kD, *vrows = a.lv.vres + (size_t)bh * a.RC * kD;
+    const u32x4 k0 = load_row_piece(krows, a.RC, 32 * u, T, tid), k1 = load_row_piece(krows, a.RC, 32 * u, T, tid + 256);
+    const u32x4 v0 = load_value_row_piece(vrows, a.RC, 32 * u, T, tid), v1 = load_value_row_piece(vrows, a.RC, 32 * u, T, tid + 256);
+    store_key_rows(L, tid, live_piece(k0, 32 * u, T, tid), live_piece(k1, 32 * u, T, tid + 256));
+    store_value_piece(L, tid, v0, 32 * u, T);
+    store_value_piece(L, tid + 256, v1, 32 * u, T);
 }
 
 __device__ __forceinline__ float xor_lanes(float x, int mask) { return __shfl_xor(x, mask, 64); }
 
+// One unit (32 tokens, in X) against the 32 queries of a wave: scores, online softmax, output accumulation.
+__device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X, int u, bool klo, int wmin, const int (&qpos)[2],
+                                            const half8 (&Qf)[2][4], float4v (&O)[8][2], float (&m)[2], float (&lsum)[2],
+                                            int n, int rq)
+{
+    // ---- S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt
+    float4v S[2][2];
+#pragma unroll
+    for (int tt = 0; tt < 2; tt++) { S[tt][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; S[tt][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
+#pragma unroll
+    for (int step = 0; step < 4; step++) {
+        const half8 A0 = *reinterpret_cast<const half8 *>(&X.K[n][32 * step + 8 * rq]);
+        const half8 A1 = *reinterpret_cast<const half8 *>(&X.K[16 + n][32 * step + 8 * rq]);
+#pragma unroll
+        for (int qt = 0; qt < 2; qt++) {
+            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
+            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
+        }
+    }
+    if (klo) {                                  // quantized keys: the remainders of the fp16 rounding
+#pragma unroll
+        for (int step = 0; step < 4; step++) {
+            const half8 A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
+            const half8 A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
+#pragma unroll
+            for (int qt = 0; qt < 2; qt++) {
+                S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
+                S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
+            }
+        }
+    }
+    const bool diag = 32 * u + 31 > wmin;                        // wave-uniform
+    half8 P[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3] * a.scale_log2e;
+        if (diag) {
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (32 * u + 16 * (e >> 2) + 4 * rq + (e & 3) > qpos[qt]) x[e] = -INFINITY;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = fmaxf(mx, xor_lanes(mx, 16));
+        mx = fmaxf(mx, xor_lanes(mx, 32));
+        // unit 0 holds token 0, which every query sees: the running maximum is finite from the start
+        const float mn = fmaxf(m[qt], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m[qt] - mn);
+        m[qt] = mn;
+        float ps = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(x[e] - mn); ps += x[e]; }
+        lsum[qt] = lsum[qt] * alpha + ps;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha;
+        }
+        P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
+                      (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
+    }
+    // ---- O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
+    // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}
+#pragma unroll
+    for (int ct = 0; ct < 8; ct++) {
+        const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
+        const half4 v1 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][16 + 4 * rq]);
+        const half8 A = half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        O[ct][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[0], O[ct][0], 0, 0, 0);
+        O[ct][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[1], O[ct][1], 0, 0, 0);
+    }
+}
+
+template <bool KQ, bool VQ>
 __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -270,6 +410,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
     const int wmin = p0 + iw;                                    // units that reach beyond it need the mask
 
     __shared__ __attribute__((aligned(16))) Tiles L[2];
+    __shared__ __attribute__((aligned(16))) MetaSlab M[kWaves];
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
     int qpos[2];
@@ -288,82 +429,36 @@ __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
     for (int ct = 0; ct < 8; ct++) { O[ct][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; O[ct][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
     float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};
 
-    Stage st;
-    load_unit(a, bh, 0, T, tid, st);
-    store_unit(a, 0, tid, st, L[0]);
-    __syncthreads();
-    for (int u = 0; u < units; u++) {
-        const Tiles &X = L[u & 1];
-        if (u + 1 < units) load_unit(a, bh, u + 1, T, tid, st);          // in flight while this unit is used
-        if (u <= wlast) {
-            // ---- S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt
-            float4v S[2][2];
-#pragma unroll
-            for (int tt = 0; tt < 2; tt++) { S[tt][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; S[tt][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
-#pragma unroll
-            for (int step = 0; step < 4; step++) {
-                const half8 A0 = *reinterpret_cast<const half8 *>(&X.K[n][32 * step + 8 * rq]);
-                const half8 A1 = *reinterpret_cast<const half8 *>(&X.K[16 + n][32 * step + 8 * rq]);
-#pragma unroll
-                for (int qt = 0; qt < 2; qt++) {
-                    S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
-                    S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
-                }
-            }
-            if (u < a.n_blocks && a.lv.kbits < 16) {
-#pragma unroll
-                for (int step = 0; step < 4; step++) {
-                    const half8 A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
-                    const half8 A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
-#pragma unroll
-                    for (int qt = 0; qt < 2; qt++) {
-                        S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
-                        S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
-                    }
-                }
-            }
-            const bool diag = 32 * u + 31 > wmin;                        // wave-uniform
-            half8 P[2];
-#pragma unroll
-            for (int qt = 0; qt < 2; qt++) {
-                float x[8];
-#pragma unroll
-                for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3] * a.scale_log2e;
-                if (diag) {
-#pragma unroll
-                    for (int e = 0; e < 8; e++)
-                        if (32 * u + 16 * (e >> 2) + 4 * rq + (e & 3) > qpos[qt]) x[e] = -INFINITY;
-                }
-                float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-                mx = fmaxf(mx, xor_lanes(mx, 16));
-                mx = fmaxf(mx, xor_lanes(mx, 32));
-                // unit 0 holds token 0, which every query sees: the running maximum is finite from the start
-                const float mn = fmaxf(m[qt], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m[qt] - mn);
-                m[qt] = mn;
-                float ps = 0.0f;
-#pragma unroll
-                for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(x[e] - mn); ps += x[e]; }
-                lsum[qt] = lsum[qt] * alpha + ps;
-                if (__any(alpha != 1.0f)) {
-#pragma unroll
-                    for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha;
-                }
-                P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
-                              (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
-            }
-            // ---- O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
-            // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}
-#pragma unroll
-            for (int ct = 0; ct < 8; ct++) {
-                const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
-                const half4 v1 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][16 + 4 * rq]);
-                const half8 A = half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                O[ct][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[0], O[ct][0], 0, 0, 0);
-                O[ct][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[1], O[ct][1], 0, 0, 0);
-            }
+    // ---- packed units [0, nb).  Two register stages: the loads of unit u + 2 are issued before unit u is used and are
+    // written to LDS after unit u + 1 has been, so that a load has two units' worth of arithmetic to arrive.  Loads and
+    // LDS writes are never skipped (past the end the last unit is staged again, into a buffer nobody reads any more).
+    const int nb = a.n_blocks < units ? a.n_blocks : units;
+    if (nb > 0) {
+        const int last = nb - 1;
+        auto clamp = [&](int u) { return u < last ? u : last; };
+        Stage sa, sb;
+        load_packed<KQ, VQ>(a, bh, 0, T, tid, sa);
+        load_packed<KQ, VQ>(a, bh, clamp(1), T, tid, sb);
+        store_packed<KQ, VQ>(a, tid, sa, L[0], M[wave]);
+        __syncthreads();
+        for (int u = 0; u < nb; u += 2) {
+            // even unit: stage sb holds unit u + 1, stage sa takes unit u + 2
+            load_packed<KQ, VQ>(a, bh, clamp(u + 2), T, tid, sa);
+            if (u <= wlast) attend_unit(a, L[0], u, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
+            store_packed<KQ, VQ>(a, tid, sb, L[1], M[wave]);
+            __syncthreads();
+            // odd unit: stage sa holds unit u + 2, stage sb takes unit u + 3
+            load_packed<KQ, VQ>(a, bh, clamp(u + 3), T, tid, sb);
+            if (u + 1 < nb && u + 1 <= wlast) attend_unit(a, L[1], u + 1, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
+            store_packed<KQ, VQ>(a, tid, sa, L[0], M[wave]);
+            __syncthreads();
         }
-        if (u + 1 < units) store_unit(a, u + 1, tid, st, L[(u + 1) & 1]);
+    }
+    // ---- chunks of the fp16 window
+    for (int u = nb; u < units; u++) {
+        stage_window(a, bh, u, T, tid, L[0]);
+        __syncthreads();
+        if (u <= wlast) attend_unit(a, L[0], u, false, wmin, qpos, Qf, O, m, lsum, n, rq);
         __syncthreads();
     }
 
@@ -392,8 +487,15 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
     const long long groups = tiles * a.B * a.Hq;
     if (groups < 1 || groups > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const dim3 grid((unsigned)groups), block(256);
-    if (ev_begin && ev_end) hipExtLaunchKernelGGL(prefill_attention, grid, block, 0, s, ev_begin, ev_end, 0, a);
-    else hipLaunchKernelGGL(prefill_attention, grid, block, 0, s, a);
+    const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
+    auto launch = [&](auto kernel) {
+        if (ev_begin && ev_end) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, a);
+        else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+    };
+    if (kq && vq) launch(prefill_attention<true, true>);
+    else if (kq) launch(prefill_attention<true, false>);
+    else if (vq) launch(prefill_attention<false, true>);
+    else launch(prefill_attention<false, false>);
     return hipGetLastError();
 }
 
