@@ -71,6 +71,8 @@ def _load():
     lib.kvo_tokens.argtypes = [c_void_p, c_int, POINTER(c_int), POINTER(c_int)]
     lib.kvo_decode_attention.restype = c_int
     lib.kvo_decode_attention.argtypes = [c_void_p, c_int, u16p, u16p, f64p, f64p]
+    lib.kvo_prefill_attention_at.restype = c_int
+    lib.kvo_prefill_attention_at.argtypes = [c_void_p, c_int, u16p, POINTER(c_int), c_int, u16p, f64p]
     lib.kvo_prefill_attention.restype = c_int
     lib.kvo_prefill_attention.argtypes = [c_void_p, c_int, u16p, c_int, u16p, f64p]
     lib.kvo_attention_exact.restype = None
@@ -217,6 +219,21 @@ class OracleCache:
         rc = _load().kvo_prefill_attention(self._h, layer, _ptr(qu, c_uint16), n_q, _ptr(out, c_uint16), _ptr(o64, c_double))
         if rc:
             raise ValueError("oracle prefill_attention failed (%d)" % rc)
+        return out.view(np.float16), o64
+
+    def prefill_attention_at(self, layer: int, q, positions):
+        """The same for queries at given absolute positions (shared by all heads): q fp16 [B, Hq, n, D], row i is
+        the query at positions[i].  Returns (out fp16, out fp64), both [B, Hq, n, D]."""
+        qu = _as_u16(q)
+        pos = np.ascontiguousarray(np.asarray(positions, dtype=np.int32))
+        assert qu.ndim == 4 and qu.shape[0] == self.B and qu.shape[1] == self.Hq and qu.shape[3] == self.D
+        assert pos.ndim == 1 and pos.shape[0] == qu.shape[2]
+        out = np.zeros(qu.shape, dtype=np.uint16)
+        o64 = np.zeros(qu.shape, dtype=np.float64)
+        rc = _load().kvo_prefill_attention_at(self._h, layer, _ptr(qu, c_uint16), _ptr(pos, c_int), pos.shape[0],
+                                              _ptr(out, c_uint16), _ptr(o64, c_double))
+        if rc:
+            raise ValueError("oracle prefill_attention_at failed (%d)" % rc)
         return out.view(np.float16), o64
 
     def reconstruct(self, layer: int):

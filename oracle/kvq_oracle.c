@@ -458,16 +458,21 @@ int kvo_decode_attention(const kvo_cache *c, int layer, const uint16_t *q, uint1
 /*
  * Prefill-stage attention of one layer over the cache as it stands.  The paper quantizes the cache in the
  * prefill stage as well as in decoding and lets the prompt's own attention read the dequantized K and V
- * (calibration design of Section 5.3, experimental-settings appendix).  Reading taken here: the queries are
- * the last n_q tokens appended; the query at absolute position p attends to positions 0..p (Eq. 1 under the
- * usual causal mask); a token enters as X^ (Eq. 2) if the cache holds it quantized now, else as its fp16 value.
- * q: fp16 [B, Hq, n_q, D];  out: fp16 [B, Hq, n_q, D];  out_f64 (nullable): the unrounded outputs.
+ * (calibration design of Section 5.3, experimental-settings appendix).  Reading taken here: a query at absolute
+ * position p attends to positions 0..p (Eq. 1 under the usual causal mask); a token enters as X^ (Eq. 2) if the
+ * cache holds it quantized now, else as its fp16 value.
+ * positions: n absolute positions (each in [0, T)), shared by all heads;
+ * q: fp16 [B, Hq, n, D], row i is the query at positions[i];  out: fp16 [B, Hq, n, D];
+ * out_f64 (nullable): the unrounded outputs.
  */
-int kvo_prefill_attention(const kvo_cache *c, int layer, const uint16_t *q, int n_q, uint16_t *out, double *out_f64)
+int kvo_prefill_attention_at(const kvo_cache *c, int layer, const uint16_t *q, const int *positions, int n,
+                             uint16_t *out, double *out_f64)
 {
     if (layer < 0 || layer >= c->L) return -1;
     const kvo_layer *y = &c->layer[layer];
-    if (y->T < 1 || n_q < 1 || n_q > y->T) return -2;
+    if (y->T < 1 || n < 1) return -2;
+    for (int i = 0; i < n; i++)
+        if (positions[i] < 0 || positions[i] >= y->T) return -2;
     const int D = c->D, T = y->T, gq = c->Hq / c->Hkv;
     const long BH = (long)c->B * c->Hkv;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -481,11 +486,10 @@ int kvo_prefill_attention(const kvo_cache *c, int layer, const uint16_t *q, int 
         const long b = bh / c->Hkv, h = bh % c->Hkv;
         for (int j = 0; j < gq; j++) {
             const size_t head = (size_t)b * c->Hq + (size_t)h * gq + j;
-            for (int i = 0; i < n_q; i++) {
-                const int pos = T - n_q + i;                       /* absolute position of this query */
-                const size_t row = head * (size_t)n_q + (size_t)i;
+            for (int i = 0; i < n; i++) {
+                const size_t row = head * (size_t)n + (size_t)i;
                 for (int d = 0; d < D; d++) qd[d] = half_to_double(q[row * D + d]);
-                attend_row(qd, Kh, Vh, pos + 1, D, p, o);          /* keys and values 0..pos */
+                attend_row(qd, Kh, Vh, positions[i] + 1, D, p, o);       /* keys and values 0..position */
                 for (int d = 0; d < D; d++) {
                     out[row * D + d] = double_to_half(o[d]);
                     if (out_f64) out_f64[row * D + d] = o[d];
@@ -495,6 +499,19 @@ int kvo_prefill_attention(const kvo_cache *c, int layer, const uint16_t *q, int 
         free(Kh); free(Vh); free(p); free(qd); free(o);
     }
     return 0;
+}
+
+/* The same with the last n_q tokens appended as the queries: positions T - n_q .. T - 1. */
+int kvo_prefill_attention(const kvo_cache *c, int layer, const uint16_t *q, int n_q, uint16_t *out, double *out_f64)
+{
+    if (layer < 0 || layer >= c->L) return -1;
+    const int T = c->layer[layer].T;
+    if (T < 1 || n_q < 1 || n_q > T) return -2;
+    int *positions = malloc(sizeof(int) * (size_t)n_q);
+    for (int i = 0; i < n_q; i++) positions[i] = T - n_q + i;
+    const int rc = kvo_prefill_attention_at(c, layer, q, positions, n_q, out, out_f64);
+    free(positions);
+    return rc;
 }
 
 /*

@@ -130,3 +130,41 @@ def test_argument_errors(kvq_mod):
     out = g.prefill_attention(0, q[:, :, :5].contiguous())
     assert torch.all(out == 0)
     g.close()
+
+
+def test_llama_shape_full_prompt_sampled_rows(kvq_mod, oracle_mod):
+    """The benchmark's prefill-attention shape (Llama-3.1-8B heads, batch 16, 8192-token prompt, every position a
+    query, K4V2 layer of the 3.25-bit mix), in the launch configuration bench.py times.  The oracle recomputes sampled
+    (batch, kv head) pairs at sampled positions one by one: the first tokens, block and query-tile boundaries, the
+    middle of the prompt, the window and the last token."""
+    w = W.config3(16, 8192)
+    layer = 16
+    kb, vb = w.kbits[layer], w.vbits[layer]
+    assert (kb, vb) == (4, 2)
+    T, gq = w.context, w.n_q_heads // w.n_kv_heads
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, T + 64, [kb], [vb])
+    for t0 in range(0, T, 2048):
+        K, V = W.kv_tokens(w, layer, t0, t0 + 2048, device="cuda:0")
+        g.quantize_append(0, K, V)
+    del K, V
+    q = torch.empty(w.batch, w.n_q_heads, T, w.head_dim, dtype=torch.float16, device="cuda:0")
+    for h0 in range(0, w.n_q_heads, gq):
+        q[:, h0:h0 + gq] = W.prefill_queries(w, layer, T, device="cuda:0", heads=(h0, gq))
+    out = g.prefill_attention(0, q)
+    torch.cuda.synchronize()
+    pos = [0, 1, 2, 15, 16, 31, 32, 33, 127, 128, 129, 255, 256, 1000, 2047, 2048, 4095, 4096, 5555, 8100, 8159, 8160, 8190, 8191]
+    worst = 0.0
+    for bh in (0, 45, 127):                         # (b, h) = (0, 0), (5, 5), (15, 7)
+        b, h = divmod(bh, w.n_kv_heads)
+        rows = torch.tensor([bh])
+        Kc, Vc = W.kv_tokens(w, layer, 0, T, bh=rows)
+        o = oracle_mod.OracleCache(1, 1, gq, 1, w.head_dim, [kb], [vb])
+        o.quantize_append(0, Kc.numpy()[None], Vc.numpy()[None])
+        assert o.tokens(0) == g.layer_tokens(0)
+        qs = q[b, h * gq:(h + 1) * gq][:, pos].cpu().numpy()[None]                 # [1, gq, n, D]
+        o16, o64 = o.prefill_attention_at(0, np.ascontiguousarray(qs), pos)
+        got = out[b, h * gq:(h + 1) * gq][:, pos][None]
+        worst = max(worst, assert_prefill_close(got, o64, "bh %d" % bh))
+        o.close()
+    g.close()
+    assert worst > 0

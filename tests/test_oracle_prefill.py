@@ -63,6 +63,12 @@ def test_quantized_layer_against_reconstruction_and_decode(oracle_mod, kb, vb, p
     # (d) fewer queries are the tail of the full call
     p16, p64 = oc.prefill_attention(0, q[:, :, -17:, :])
     assert np.array_equal(p64, o64[:, :, -17:, :])
+    # (d') queries at picked positions are the rows of the full call at those positions
+    pos = [0, 1, 31, 32, 95, 96, 97, 140]
+    a16, a64 = oc.prefill_attention_at(0, np.ascontiguousarray(q[:, :, pos, :]), pos)
+    assert np.array_equal(a64, o64[:, :, pos, :]) and np.array_equal(a16, o16[:, :, pos, :])
+    with pytest.raises(ValueError):
+        oc.prefill_attention_at(0, np.ascontiguousarray(q[:, :, :1, :]), [T])
     # (e) quantization is visible where it should be: rows that see quantized tokens differ from the fp16 result
     if kb <= 4 or vb <= 4:
         exact = _numpy_causal(q, K, V, T)
