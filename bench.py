@@ -201,6 +201,57 @@ def time_workload(torch, pkg, W, w, steps, warmup, variant=0, splits=0, per_kern
     return res
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0     # MI355X dense fp16 matrix-core peak
+
+
+def time_prefill_attention(torch, pkg, W, w, layer, reps=3, meta=None, keys=None):
+    """The prompt's own causal attention over the dequantized cache of one layer (every position a query), timed
+    between HIP events stamped by the kernel's own dispatch.  Algorithmic flops: 4 * head_dim per (query, visible
+    token) pair and query head."""
+    T = w.context
+    kw = {}
+    if meta is not None:
+        kw["meta_dtype"] = meta
+    if keys is not None:
+        kw["key_mode"] = keys
+    cache = pkg.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, T + w.group, [w.kbits[layer]], [w.vbits[layer]],
+                    group=w.group, residual=w.residual, **kw)
+    chunk = max(w.group, ((1 << 28) // (w.batch * w.n_kv_heads * w.head_dim)) // w.group * w.group)
+    for t0 in range(0, T, chunk):
+        K, V = W.kv_tokens(w, layer, t0, min(T, t0 + chunk), device="cuda:0")
+        cache.quantize_append(0, K, V)
+    del K, V
+    gq = w.n_q_heads // w.n_kv_heads
+    q = torch.empty(w.batch, w.n_q_heads, T, w.head_dim, dtype=torch.float16, device="cuda:0")
+    for h0 in range(0, w.n_q_heads, gq):
+        q[:, h0:h0 + gq] = W.prefill_queries(w, layer, T, device="cuda:0", heads=(h0, gq))
+    out = torch.empty_like(q)
+    cache.prefill_attention(0, q, out)
+    torch.cuda.synchronize()
+    hip = HipEvents()
+    evs = [(hip.create(), hip.create()) for _ in range(reps)]
+    for a, b in evs:
+        cache.set_kernel_events(a, b)
+        cache.prefill_attention(0, q, out)
+    cache.set_kernel_events(None, None)
+    torch.cuda.synchronize()
+    ms = [hip.elapsed_ms(a, b) for a, b in evs]
+    for a, b in evs:
+        hip.destroy(a)
+        hip.destroy(b)
+    avg = sum(ms) / len(ms)
+    flops = 4.0 * w.head_dim * (T * (T + 1) // 2) * w.batch * w.n_q_heads
+    res = {"kernel": "prefill_attention<K%dV%d>" % (w.kbits[layer], w.vbits[layer]), "layer": layer, "queries": T,
+           "launches_timed": reps, "avg_launch_ms": avg, "flops_per_launch": flops,
+           "roofline": {"bound": "mfma", "achieved": flops / (avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": flops / (avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None},
+           "prompt_tokens_per_s_per_layer": w.batch * T / (avg * 1e-3)}
+    cache.close()
+    del cache, q, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(W, w, budget_s=20.0):
     """The CPU oracle as it stands on a bounded sample: one layer per distinct precision pair, a slice of
     the batch, the full context; one decode step (append + attention) each, extrapolated linearly."""
@@ -274,6 +325,8 @@ def main():
                          "step kvq_append_decode_attention (same work, one more launch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv8", action="store_true")
+    ap.add_argument("--no-prefill-attn", action="store_true",
+                    help="skip the extra measurement of the prefill-stage attention kernel (one layer of the dominant pair)")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="first run 5 plain streaming kernels that read 1 GiB and write 1 GiB (torch.neg on fp32; "
@@ -360,6 +413,11 @@ def main():
                       "hbm_gbps": kv8["algorithmic_gbps"], "hbm_frac_of_peak": kv8["algorithmic_gbps"] / HBM_PEAK_GBPS,
                       "per_pair": kv8["per_pair"]}
         out["speedup_vs_kv8"] = mix["tokens_per_s"] / kv8["tokens_per_s"]
+    if not args.no_prefill_attn and not args.only:
+        dom_layers = [l for l in range(w_main.n_layers) if "K%dV%d" % (w_main.kbits[l], w_main.vbits[l]) == dom]
+        out["prefill_attention"] = time_prefill_attention(
+            torch, pkg, W, w_main, dom_layers[len(dom_layers) // 2],
+            meta=pkg.META_FP16 if args.meta == "fp16" else None, keys=pkg.KEYS_PER_TOKEN if KEYS_PER_TOKEN else None)
     out["paper_context"] = "paper reports +16.79%..+21.25% end-to-end tokens/s for its 3.25-bit schedule over KIVI-KV8 (GPU not named)"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W, w_main)
