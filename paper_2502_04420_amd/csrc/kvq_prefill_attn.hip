@@ -396,10 +396,23 @@ __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, rq = lane >> 4;
     const int tiles = (a.n_q + kQB - 1) / kQB;
-    const int head = blockIdx.x / tiles;                         // b * Hq + query head
-    const int tile = tiles - 1 - (int)(blockIdx.x % tiles);      // the longest rows of a head start first
-    const int b = head / a.Hq, hq = head % a.Hq;
-    const int bh = b * a.Hkv + hq / (a.Hq / a.Hkv);
+    const int gq = a.Hq / a.Hkv, BH = a.B * a.Hkv;
+    // Work-groups go to the 8 XCDs in turn by their index, and each XCD has an L2 of its own: all query heads and
+    // query tiles that read one (batch, kv head) cache are given to one XCD (when the counts divide), so that its
+    // packed blocks are fetched from memory once and then served by that L2.
+    int bh, jq, rank;                                            // cache, query head within its group, order within the head
+    if (BH % 8 == 0) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3, per = gq * tiles;
+        bh = 8 * (k / per) + xcd;
+        jq = (k % per) % gq;
+        rank = (k % per) / gq;
+    } else {
+        bh = blockIdx.x / (gq * tiles);
+        jq = (blockIdx.x / tiles) % gq;
+        rank = blockIdx.x % tiles;
+    }
+    const int tile = tiles - 1 - rank;                           // the longest rows start first
+    const int head = (bh / a.Hkv) * a.Hq + (bh % a.Hkv) * gq + jq;   // b * Hq + query head
     const int T = 32 * a.n_blocks + a.n_res;
     const int p0 = T - a.n_q;                                    // absolute position of query 0
     const int i0 = tile * kQB;
