@@ -29,6 +29,9 @@
  *   - 16 "bits" means the fp16 values are kept as they are.
  *   - key grouping: the KIVI mode above by default; a second mode groups keys per
  *     token like the values (the paper's per-token-asym mode).
+ *   - prefill-stage attention (the prompt's own attention reading the dequantized cache, Section 5.3 and the
+ *     experimental-settings appendix): evaluated over the cache as it stands when it is called; the query at
+ *     absolute position p sees positions 0..p; a token enters as X^ if it is held quantized at that moment.
  *   - metadata precision: s and z are fp32 by default.  A variant stores them as
  *     fp16 (z exactly, s rounded once); it encodes and decodes with the rounded s.
  *
