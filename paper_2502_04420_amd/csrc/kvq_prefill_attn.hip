@@ -19,6 +19,8 @@
 //     accumulation, one division at the end.
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -28,7 +30,8 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;                // waves of a work-group; all attend (32 queries each)
+constexpr int kStagers = 4;              // the first of them also stage the units (256 threads: the thread -> code maps below)
 constexpr int kQW = 32;                 // queries per wave
 constexpr int kQB = kQW * kWaves;       // queries per work-group
 constexpr int kKStride = kD + 8;        // halves per K^ row (272 bytes: the 16 rows of a 16-byte read fall on different banks)
@@ -390,7 +393,7 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
 }
 
 template <bool KQ, bool VQ>
-__global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
+__global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -423,7 +426,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
     const int wmin = p0 + iw;                                    // units that reach beyond it need the mask
 
     __shared__ __attribute__((aligned(16))) Tiles L[2];
-    __shared__ __attribute__((aligned(16))) MetaSlab M[kWaves];
+    __shared__ __attribute__((aligned(16))) MetaSlab M[kStagers];
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
     int qpos[2];
@@ -442,34 +445,44 @@ __global__ __launch_bounds__(256, 2) void prefill_attention(PrefillArgs a)
     for (int ct = 0; ct < 8; ct++) { O[ct][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; O[ct][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
     float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};
 
-    // ---- packed units [0, nb).  Two register stages: the loads of unit u + 2 are issued before unit u is used and are
-    // written to LDS after unit u + 1 has been, so that a load has two units' worth of arithmetic to arrive.  Loads and
-    // LDS writes are never skipped (past the end the last unit is staged again, into a buffer nobody reads any more).
+    // ---- packed units [0, nb).  Waves 0..3 stage the units (two register stages: the loads of unit u + 2 are issued
+    // before unit u is used and are written to LDS after unit u + 1 has been, so that a load has two units' worth of
+    // arithmetic to arrive; loads and LDS writes are never skipped: past the end the last unit is staged again, into
+    // a buffer nobody reads any more).  All 8 waves attend.  The loop exists twice, with and without the staging,
+    // so that in neither copy a branch lies between the issue of a load and its use.
     const int nb = a.n_blocks < units ? a.n_blocks : units;
-    if (nb > 0) {
+    auto packed_units = [&](auto staging) {
+        constexpr bool kStage = decltype(staging)::value;
         const int last = nb - 1;
         auto clamp = [&](int u) { return u < last ? u : last; };
+        const int sw = kStage ? wave : 0;
         Stage sa, sb;
-        load_packed<KQ, VQ>(a, bh, 0, T, tid, sa);
-        load_packed<KQ, VQ>(a, bh, clamp(1), T, tid, sb);
-        store_packed<KQ, VQ>(a, tid, sa, L[0], M[wave]);
+        if constexpr (kStage) {
+            load_packed<KQ, VQ>(a, bh, 0, T, tid, sa);
+            load_packed<KQ, VQ>(a, bh, clamp(1), T, tid, sb);
+            store_packed<KQ, VQ>(a, tid, sa, L[0], M[sw]);
+        }
         __syncthreads();
         for (int u = 0; u < nb; u += 2) {
             // even unit: stage sb holds unit u + 1, stage sa takes unit u + 2
-            load_packed<KQ, VQ>(a, bh, clamp(u + 2), T, tid, sa);
+            if constexpr (kStage) load_packed<KQ, VQ>(a, bh, clamp(u + 2), T, tid, sa);
             if (u <= wlast) attend_unit(a, L[0], u, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
-            store_packed<KQ, VQ>(a, tid, sb, L[1], M[wave]);
+            if constexpr (kStage) store_packed<KQ, VQ>(a, tid, sb, L[1], M[sw]);
             __syncthreads();
             // odd unit: stage sa holds unit u + 2, stage sb takes unit u + 3
-            load_packed<KQ, VQ>(a, bh, clamp(u + 3), T, tid, sb);
+            if constexpr (kStage) load_packed<KQ, VQ>(a, bh, clamp(u + 3), T, tid, sb);
             if (u + 1 < nb && u + 1 <= wlast) attend_unit(a, L[1], u + 1, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
-            store_packed<KQ, VQ>(a, tid, sa, L[0], M[wave]);
+            if constexpr (kStage) store_packed<KQ, VQ>(a, tid, sa, L[0], M[sw]);
             __syncthreads();
         }
+    };
+    if (nb > 0) {
+        if (wave < kStagers) packed_units(std::true_type{});
+        else packed_units(std::false_type{});
     }
     // ---- chunks of the fp16 window
     for (int u = nb; u < units; u++) {
-        stage_window(a, bh, u, T, tid, L[0]);
+        if (wave < kStagers) stage_window(a, bh, u, T, tid, L[0]);
         __syncthreads();
         if (u <= wlast) attend_unit(a, L[0], u, false, wmin, qpos, Qf, O, m, lsum, n, rq);
         __syncthreads();
@@ -499,7 +512,7 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
     const long long tiles = (a.n_q + kQB - 1) / kQB;
     const long long groups = tiles * a.B * a.Hq;
     if (groups < 1 || groups > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const dim3 grid((unsigned)groups), block(256);
+    const dim3 grid((unsigned)groups), block(64 * kWaves);
     const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
     auto launch = [&](auto kernel) {
         if (ev_begin && ev_end) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, a);
