@@ -4,8 +4,8 @@
 // design of Section 5.3): quantized tokens enter as X^ = Q(X) s + z (Eq. 2), window tokens as their fp16 values.
 //
 // This is a dense contraction (4 * D flops per query-token pair), so it runs on the matrix cores:
-//   * a work-group of 4 waves owns 128 consecutive queries of one query head, 32 per wave (two 16-query tiles);
-//   * the tokens arrive in units of 32 (a packed block or a chunk of the fp16 window).  All 256 threads dequantize
+//   * a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two 16-query tiles);
+//   * the tokens arrive in units of 32 (a packed block or a chunk of the fp16 window).  The first 4 waves dequantize
 //     the unit once, X^ = fma(code, s, z) in fp32, into LDS as fp16: K^ as [token][channel], V^ transposed as
 //     [channel][token].  Dequantized keys are kept as two fp16 numbers (the rounded value and the remainder) and
 //     multiplied twice: keys have a few channels of large magnitude, and one fp16 rounding of those, times a large
