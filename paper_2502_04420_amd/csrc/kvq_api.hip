@@ -16,6 +16,7 @@
 namespace {
 
 constexpr int kMaxSplits = 128;
+constexpr int kPrefillChunk = 16;   // caches dequantized per prefill-attention pass (two per XCD)
 constexpr int kWindowWeight = 4;   // cost of the fp16 window in a split's share, in packed blocks (measured: 2..8 alike, 0 slower)
 constexpr size_t kAlign = 256;
 
@@ -47,8 +48,9 @@ struct LayerPlan {
 
 struct Plan {
     std::vector<LayerPlan> layer;
-    size_t part_o, part_ml, total;
+    size_t part_o, part_ml, prefill_scratch, total;
     int NB, RC;
+    int prefill_chunk;      // (batch, kv head) caches whose dequantized units the prefill scratch holds at a time
 };
 
 Plan make_plan(const kvq_config *c)
@@ -74,6 +76,8 @@ Plan make_plan(const kvq_config *c)
     const size_t rows = (size_t)c->batch * c->n_q_heads;
     p.part_o = off; off = align_up(off + rows * kMaxSplits * kvq::kD * sizeof(float));
     p.part_ml = off; off = align_up(off + rows * kMaxSplits * 2 * sizeof(float));
+    p.prefill_chunk = BH < (size_t)kPrefillChunk ? (int)BH : kPrefillChunk;
+    p.prefill_scratch = off; off = align_up(off + (size_t)p.prefill_chunk * p.NB * kvq::prefill_unit_bytes());
     p.total = off;
     return p;
 }
@@ -325,9 +329,18 @@ int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32
     a.RC = c->plan.RC;
     a.n_q = n_q;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
+    a.scratch = c->ws + c->plan.prefill_scratch;
     const bool timed = c->ev_begin && c->ev_end;
-    const hipError_t e = kvq::launch_prefill_attention(a, c->stream, timed ? c->ev_begin : nullptr, timed ? c->ev_end : nullptr);
-    if (e != hipSuccess) return launch_failed("prefill attention kernel", e);
+    const int BH = a.B * a.Hkv, chunk = c->plan.prefill_chunk;
+    // the caches are taken a chunk at a time: dequantize the chunk's packed units into the scratch area, attend
+    for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
+        a.bh0 = bh0;
+        a.n_bh = BH - bh0 < chunk ? BH - bh0 : chunk;
+        const bool first = bh0 == 0, last = bh0 + chunk >= BH;
+        const hipError_t e = kvq::launch_prefill_attention(a, c->stream, timed && first ? c->ev_begin : nullptr,
+                                                           timed && last ? c->ev_end : nullptr);
+        if (e != hipSuccess) return launch_failed("prefill attention kernels", e);
+    }
     return KVQ_OK;
 }
 

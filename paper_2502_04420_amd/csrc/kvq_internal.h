@@ -79,6 +79,10 @@ struct PrefillArgs {
     int NB, RC;
     int n_q;               // 1 <= n_q <= 32*n_blocks + n_res
     float scale_log2e;     // log2(e) / sqrt(D)
+    // one launch covers the (batch, kv head) caches [bh0, bh0 + n_bh); their packed units are dequantized into
+    // scratch[n_bh][n_blocks][prefill_unit_bytes()] first
+    uint8_t *scratch;
+    int bh0, n_bh;
 };
 
 // Work units [u0, u1) of a split: units are the quantized blocks, then the chunks of <= 32 fp16 window tokens.  Every
@@ -98,6 +102,9 @@ hipError_t launch_export(const ExportArgs &a, hipStream_t s);
 hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s);
 // ev_begin / ev_end (both or neither): receive the start and stop time stamps of the kernel's own dispatch
 hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+size_t prefill_unit_bytes();     // scratch bytes per packed unit (32 tokens) of one (batch, kv head) cache
+// dequantizes the packed units of the caches [bh0, bh0 + n_bh) into the scratch area, then attends; ev_begin / ev_end
+// (either may be null) receive the start of the first and the end of the last kernel
 hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s);
 

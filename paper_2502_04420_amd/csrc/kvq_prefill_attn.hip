@@ -392,28 +392,72 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
     }
 }
 
+// ---- pass 1: every packed unit of the (batch, kv head) caches [bh0, bh0 + n_bh) is dequantized once into the scratch
+// area, in the very layout the attention kernel keeps a unit in LDS (struct Tiles), so that pass 2 stages plain copies.
+// KQ / VQ: the layer's keys / values are quantized (else fp16 rows in the code area).
 template <bool KQ, bool VQ>
+__global__ __launch_bounds__(256) void prefill_dequantize(PrefillArgs a)
+{
+    const int tid = threadIdx.x, u = blockIdx.x, local = blockIdx.y;
+    const int T = 32 * a.n_blocks + a.n_res;
+    __shared__ __attribute__((aligned(16))) MetaSlab M[4];
+    Stage st;
+    load_packed<KQ, VQ>(a, a.bh0 + local, u, T, tid, st);
+    Tiles &dst = *reinterpret_cast<Tiles *>(a.scratch + ((size_t)local * a.n_blocks + u) * sizeof(Tiles));
+    store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6]);
+}
+
+// 16-byte pieces of a unit in the scratch area, and how many each of the 512 threads copies
+constexpr int kUnitPieces = (int)(sizeof(Tiles) / 16);
+constexpr int kCopies = (kUnitPieces + 64 * kWaves - 1) / (64 * kWaves);
+static_assert(sizeof(Tiles) % 16 == 0, "a unit is copied in 16-byte pieces");
+
+struct Copy { u32x4 r[kCopies]; };
+
+// Loads are never skipped (a piece past the end reads the last one again): no branch between a load and its use.
+__device__ __forceinline__ void load_copy(const uint8_t *unit, int tid, Copy &c)
+{
+#pragma unroll
+    for (int i = 0; i < kCopies; i++) {
+        const int p = tid + 64 * kWaves * i;
+        c.r[i] = ld16(unit + 16 * (p < kUnitPieces ? p : kUnitPieces - 1));
+    }
+}
+
+__device__ __forceinline__ void store_copy(Tiles &L, int tid, const Copy &c)
+{
+    uint8_t *dst = reinterpret_cast<uint8_t *>(&L);
+#pragma unroll
+    for (int i = 0; i < kCopies; i++) {
+        const int p = tid + 64 * kWaves * i;
+        if (p < kUnitPieces) *reinterpret_cast<u32x4 *>(dst + 16 * p) = c.r[i];
+    }
+}
+
+// ---- pass 2: the attention itself.  One work-group per 256 consecutive queries of one query head; every wave attends
+// 32 queries and copies its share of each unit from the scratch area into LDS.
 __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, rq = lane >> 4;
     const int tiles = (a.n_q + kQB - 1) / kQB;
-    const int gq = a.Hq / a.Hkv, BH = a.B * a.Hkv;
+    const int gq = a.Hq / a.Hkv;
     // Work-groups go to the 8 XCDs in turn by their index, and each XCD has an L2 of its own: all query heads and
-    // query tiles that read one (batch, kv head) cache are given to one XCD (when the counts divide), so that its
-    // packed blocks are fetched from memory once and then served by that L2.
-    int bh, jq, rank;                                            // cache, query head within its group, order within the head
-    if (BH % 8 == 0) {
+    // query tiles that read one (batch, kv head) cache are given to one XCD (when the count divides), so that its
+    // units are fetched from memory once and then served by that L2.
+    int local, jq, rank;                                         // cache within this launch, query head within its group, order
+    if (a.n_bh % 8 == 0) {
         const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3, per = gq * tiles;
-        bh = 8 * (k / per) + xcd;
+        local = 8 * (k / per) + xcd;
         jq = (k % per) % gq;
         rank = (k % per) / gq;
     } else {
-        bh = blockIdx.x / (gq * tiles);
+        local = blockIdx.x / (gq * tiles);
         jq = (blockIdx.x / tiles) % gq;
         rank = blockIdx.x % tiles;
     }
+    const int bh = a.bh0 + local;
     const int tile = tiles - 1 - rank;                           // the longest rows start first
     const int head = (bh / a.Hkv) * a.Hq + (bh % a.Hkv) * gq + jq;   // b * Hq + query head
     const int T = 32 * a.n_blocks + a.n_res;
@@ -424,9 +468,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     const int iw = i0 + kQW * wave;                              // first query of this wave
     const int wlast = iw < a.n_q ? (p0 + (iw + kQW - 1 < a.n_q ? iw + kQW - 1 : a.n_q - 1)) / 32 : -1;
     const int wmin = p0 + iw;                                    // units that reach beyond it need the mask
+    const bool klo = a.lv.kbits < 16;                            // quantized keys come as two fp16 numbers
 
     __shared__ __attribute__((aligned(16))) Tiles L[2];
-    __shared__ __attribute__((aligned(16))) MetaSlab M[kStagers];
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
     int qpos[2];
@@ -445,44 +489,35 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     for (int ct = 0; ct < 8; ct++) { O[ct][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; O[ct][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
     float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};
 
-    // ---- packed units [0, nb).  Waves 0..3 stage the units (two register stages: the loads of unit u + 2 are issued
-    // before unit u is used and are written to LDS after unit u + 1 has been, so that a load has two units' worth of
-    // arithmetic to arrive; loads and LDS writes are never skipped: past the end the last unit is staged again, into
-    // a buffer nobody reads any more).  All 8 waves attend.  The loop exists twice, with and without the staging,
-    // so that in neither copy a branch lies between the issue of a load and its use.
+    // ---- packed units [0, nb).  Two register stages: the loads of unit u + 2 are issued before unit u is used and are
+    // written to LDS after unit u + 1 has been, so that a load has two units' worth of arithmetic to arrive.  Loads and
+    // LDS writes are never skipped (past the end the last unit is staged again, into a buffer nobody reads any more).
     const int nb = a.n_blocks < units ? a.n_blocks : units;
-    auto packed_units = [&](auto staging) {
-        constexpr bool kStage = decltype(staging)::value;
+    if (nb > 0) {
+        const uint8_t *mine = a.scratch + (size_t)local * a.n_blocks * sizeof(Tiles);
         const int last = nb - 1;
-        auto clamp = [&](int u) { return u < last ? u : last; };
-        const int sw = kStage ? wave : 0;
-        Stage sa, sb;
-        if constexpr (kStage) {
-            load_packed<KQ, VQ>(a, bh, 0, T, tid, sa);
-            load_packed<KQ, VQ>(a, bh, clamp(1), T, tid, sb);
-            store_packed<KQ, VQ>(a, tid, sa, L[0], M[sw]);
-        }
+        auto unit_at = [&](int u) { return mine + (size_t)(u < last ? u : last) * sizeof(Tiles); };
+        Copy ca, cb;
+        load_copy(unit_at(0), tid, ca);
+        load_copy(unit_at(1), tid, cb);
+        store_copy(L[0], tid, ca);
         __syncthreads();
         for (int u = 0; u < nb; u += 2) {
-            // even unit: stage sb holds unit u + 1, stage sa takes unit u + 2
-            if constexpr (kStage) load_packed<KQ, VQ>(a, bh, clamp(u + 2), T, tid, sa);
-            if (u <= wlast) attend_unit(a, L[0], u, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
-            if constexpr (kStage) store_packed<KQ, VQ>(a, tid, sb, L[1], M[sw]);
+            // even unit: stage cb holds unit u + 1, stage ca takes unit u + 2
+            load_copy(unit_at(u + 2), tid, ca);
+            if (u <= wlast) attend_unit(a, L[0], u, klo, wmin, qpos, Qf, O, m, lsum, n, rq);
+            store_copy(L[1], tid, cb);
             __syncthreads();
-            // odd unit: stage sa holds unit u + 2, stage sb takes unit u + 3
-            if constexpr (kStage) load_packed<KQ, VQ>(a, bh, clamp(u + 3), T, tid, sb);
-            if (u + 1 < nb && u + 1 <= wlast) attend_unit(a, L[1], u + 1, KQ, wmin, qpos, Qf, O, m, lsum, n, rq);
-            if constexpr (kStage) store_packed<KQ, VQ>(a, tid, sa, L[0], M[sw]);
+            // odd unit: stage ca holds unit u + 2, stage cb takes unit u + 3
+            load_copy(unit_at(u + 3), tid, cb);
+            if (u + 1 < nb && u + 1 <= wlast) attend_unit(a, L[1], u + 1, klo, wmin, qpos, Qf, O, m, lsum, n, rq);
+            store_copy(L[0], tid, ca);
             __syncthreads();
         }
-    };
-    if (nb > 0) {
-        if (wave < kStagers) packed_units(std::true_type{});
-        else packed_units(std::false_type{});
     }
-    // ---- chunks of the fp16 window
+    // ---- chunks of the fp16 window, staged by the first four waves straight from the ring
     for (int u = nb; u < units; u++) {
-        if (wave < kStagers) stage_window(a, bh, u, T, tid, L[0]);
+        if (wave < 4) stage_window(a, bh, u, T, tid, L[0]);
         __syncthreads();
         if (u <= wlast) attend_unit(a, L[0], u, false, wmin, qpos, Qf, O, m, lsum, n, rq);
         __syncthreads();
@@ -507,21 +542,33 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
 
 }  // namespace
 
+size_t prefill_unit_bytes() { return sizeof(Tiles); }
+
 hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end)
 {
     const long long tiles = (a.n_q + kQB - 1) / kQB;
-    const long long groups = tiles * a.B * a.Hq;
-    if (groups < 1 || groups > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const long long groups = tiles * a.n_bh * (a.Hq / a.Hkv);
+    if (groups < 1 || groups > 0x7fffffffLL || a.n_bh < 1 || a.n_bh > 65535) return hipErrorInvalidConfiguration;
+    // pass 1 (its start stamps ev_begin when there is one; without packed units pass 2 does)
+    if (a.n_blocks > 0) {
+        const dim3 grid((unsigned)a.n_blocks, (unsigned)a.n_bh), block(256);
+        const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
+        auto launch = [&](auto kernel) {
+            if (ev_begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, nullptr, 0, a);
+            else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+        };
+        if (kq && vq) launch(prefill_dequantize<true, true>);
+        else if (kq) launch(prefill_dequantize<true, false>);
+        else if (vq) launch(prefill_dequantize<false, true>);
+        else launch(prefill_dequantize<false, false>);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    // pass 2
     const dim3 grid((unsigned)groups), block(64 * kWaves);
-    const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
-    auto launch = [&](auto kernel) {
-        if (ev_begin && ev_end) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, a);
-        else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
-    };
-    if (kq && vq) launch(prefill_attention<true, true>);
-    else if (kq) launch(prefill_attention<true, false>);
-    else if (vq) launch(prefill_attention<false, true>);
-    else launch(prefill_attention<false, false>);
+    hipEvent_t b2 = a.n_blocks > 0 ? nullptr : ev_begin;
+    if (b2 || ev_end) hipExtLaunchKernelGGL(prefill_attention, grid, block, 0, s, b2, ev_end, 0, a);
+    else hipLaunchKernelGGL(prefill_attention, grid, block, 0, s, a);
     return hipGetLastError();
 }
 
