@@ -152,8 +152,13 @@ int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_devic
  *   out_device : fp16 [batch, n_q_heads, n_q, head_dim], device, written.
  *   n_q        : 1 .. tokens held by the layer (else KVQ_EINVAL; KVQ_ESTATE for an empty layer).
  * Query head h attends kv head h / (n_q_heads / n_kv_heads).  The dequantized operands and the
- * softmax weights are rounded to fp16 for the matrix cores; accumulation is fp32.  The cache
- * is not modified.  With n_q = 1 the result is that of kvq_decode_attention up to rounding.
+ * softmax weights are rounded to fp16 for the matrix cores (keys as the sum of two fp16
+ * numbers); accumulation is fp32.  The cache is not modified.  With n_q = 1 the result is that
+ * of kvq_decode_attention up to rounding.  The call enqueues two kernels per 16 (batch, kv head)
+ * caches: one dequantizes their packed tokens once into a scratch area inside the workspace
+ * (16 * floor(max_tokens / 32) * 26 KiB, counted by kvq_workspace_bytes), one attends.  With
+ * kernel events set (kvq_set_kernel_events) they receive the start of the first and the end of
+ * the last of these kernels.
  */
 int kvq_prefill_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, int32_t n_q, void *out_device);
 
@@ -195,7 +200,8 @@ int kvq_set_decode_options(kvq_ctx *ctx, int32_t variant, int32_t splits);
  * every decode call makes its main kernel (the fused dequantize-and-attend kernel) stamp
  * begin_event with the start and end_event with the end of that kernel's own execution on the
  * context's stream (the small kernel that merges the token-range splits runs after end_event);
- * the caller synchronises and reads hipEventElapsedTime.  The events must outlive the hook.
+ * a kvq_prefill_attention call stamps them with the start of its first and the end of its last
+ * kernel; the caller synchronises and reads hipEventElapsedTime.  The events must outlive the hook.
  * Returns KVQ_EINVAL when exactly one of the two is NULL.
  */
 int kvq_set_kernel_events(kvq_ctx *ctx, void *begin_event, void *end_event);

@@ -3,20 +3,23 @@
 // the cache in the prefill stage too and lets the prompt's own attention read the dequantized K and V (calibration
 // design of Section 5.3): quantized tokens enter as X^ = Q(X) s + z (Eq. 2), window tokens as their fp16 values.
 //
-// This is a dense contraction (4 * D flops per query-token pair), so it runs on the matrix cores:
-//   * a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two 16-query tiles);
-//   * the tokens arrive in units of 32 (a packed block or a chunk of the fp16 window).  The first 4 waves dequantize
-//     the unit once, X^ = fma(code, s, z) in fp32, into LDS as fp16: K^ as [token][channel], V^ transposed as
-//     [channel][token].  Dequantized keys are kept as two fp16 numbers (the rounded value and the remainder) and
-//     multiplied twice: keys have a few channels of large magnitude, and one fp16 rounding of those, times a large
-//     query entry, moves a logit by several 1e-3.  The unit after the current one is fetched into registers while
-//     the current one is used;
-//   * scores are computed transposed, S^T = K^ Q^T (16x16x32 f16 instructions, tokens along the rows): a lane then
-//     holds, for its query, the scores of tokens {4 rq .. 4 rq + 3} and {16 + 4 rq ..}, which is exactly a B operand
-//     of O^T += V^T P^T when the A operand (V^T from LDS) lists its tokens in the same order.  The softmax weights
-//     therefore go from the accumulator of one product into the operand of the next without leaving the registers;
-//   * online softmax in base 2 per query (running maximum shared by the four lanes that hold a query), fp32
-//     accumulation, one division at the end.
+// This is a dense contraction (4 * D flops per query-token pair), so it runs on the matrix cores, in two passes over a
+// chunk of (batch, kv head) caches at a time:
+//   1. prefill_dequantize: every packed unit (32 tokens) of the chunk is dequantized once, X^ = fma(code, s, z) in
+//      fp32, into a scratch area as fp16, in the layout the attention kernel keeps a unit in LDS: K^ as
+//      [token][channel], V^ transposed as [channel][token].  Dequantized keys are kept as two fp16 numbers (the rounded
+//      value and the remainder) and multiplied twice: keys have a few channels of large magnitude, and one fp16
+//      rounding of those, times a large query entry, moves a logit by several 1e-3.  Dequantizing inside the attention
+//      kernel instead repeats this work for every query head of the group and every query tile (256 times per unit at
+//      8192 queries) and made that kernel bound by its vector instructions.
+//   2. prefill_attention: a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two
+//      16-query tiles).  The units are copied from the scratch area (fp16 window chunks: from the ring) into double
+//      buffered LDS tiles, two register stages ahead of their use.  Scores are computed transposed, S^T = K^ Q^T
+//      (16x16x32 f16 instructions, tokens along the rows): a lane then holds, for its query, the scores of tokens
+//      {4 rq .. 4 rq + 3} and {16 + 4 rq ..}, which is exactly a B operand of O^T += V^T P^T when the A operand (V^T
+//      from LDS) lists its tokens in the same order.  The softmax weights therefore go from the accumulator of one
+//      product into the operand of the next without leaving the registers.  Online softmax in base 2 per query (running
+//      maximum shared by the four lanes that hold a query), fp32 accumulation, one division at the end.
 #include <hip/hip_ext.h>
 
 #include <type_traits>
@@ -30,8 +33,8 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;                // waves of a work-group; all attend (32 queries each)
-constexpr int kStagers = 4;              // the first of them also stage the units (256 threads: the thread -> code maps below)
+constexpr int kWaves = 8;                // waves of an attention work-group (32 queries each)
+constexpr int kStagers = 4;              // waves that turn a unit into tiles (256 threads: the thread -> code maps below)
 constexpr int kQW = 32;                 // queries per wave
 constexpr int kQB = kQW * kWaves;       // queries per work-group
 constexpr int kKStride = kD + 8;        // halves per K^ row (272 bytes: the 16 rows of a 16-byte read fall on different banks)
@@ -396,11 +399,11 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
 // area, in the very layout the attention kernel keeps a unit in LDS (struct Tiles), so that pass 2 stages plain copies.
 // KQ / VQ: the layer's keys / values are quantized (else fp16 rows in the code area).
 template <bool KQ, bool VQ>
-__global__ __launch_bounds__(256) void prefill_dequantize(PrefillArgs a)
+__global__ __launch_bounds__(64 * kStagers) void prefill_dequantize(PrefillArgs a)
 {
     const int tid = threadIdx.x, u = blockIdx.x, local = blockIdx.y;
     const int T = 32 * a.n_blocks + a.n_res;
-    __shared__ __attribute__((aligned(16))) MetaSlab M[4];
+    __shared__ __attribute__((aligned(16))) MetaSlab M[kStagers];
     Stage st;
     load_packed<KQ, VQ>(a, a.bh0 + local, u, T, tid, st);
     Tiles &dst = *reinterpret_cast<Tiles *>(a.scratch + ((size_t)local * a.n_blocks + u) * sizeof(Tiles));
@@ -517,7 +520,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     }
     // ---- chunks of the fp16 window, staged by the first four waves straight from the ring
     for (int u = nb; u < units; u++) {
-        if (wave < 4) stage_window(a, bh, u, T, tid, L[0]);
+        if (wave < kStagers) stage_window(a, bh, u, T, tid, L[0]);
         __syncthreads();
         if (u <= wlast) attend_unit(a, L[0], u, false, wmin, qpos, Qf, O, m, lsum, n, rq);
         __syncthreads();
@@ -551,7 +554,7 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
     if (groups < 1 || groups > 0x7fffffffLL || a.n_bh < 1 || a.n_bh > 65535) return hipErrorInvalidConfiguration;
     // pass 1 (its start stamps ev_begin when there is one; without packed units pass 2 does)
     if (a.n_blocks > 0) {
-        const dim3 grid((unsigned)a.n_blocks, (unsigned)a.n_bh), block(256);
+        const dim3 grid((unsigned)a.n_blocks, (unsigned)a.n_bh), block(64 * kStagers);
         const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
         auto launch = [&](auto kernel) {
             if (ev_begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, nullptr, 0, a);
