@@ -359,7 +359,7 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
     for (int qt = 0; qt < 2; qt++) {
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3] * a.scale_log2e;
+        for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3];      // raw scores; the running maximum is kept raw too
         if (diag) {
 #pragma unroll
             for (int e = 0; e < 8; e++)
@@ -370,11 +370,12 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
         mx = fmaxf(mx, xor_lanes(mx, 32));
         // unit 0 holds token 0, which every query sees: the running maximum is finite from the start
         const float mn = fmaxf(m[qt], mx);
-        const float alpha = __builtin_amdgcn_exp2f(m[qt] - mn);
+        const float alpha = __builtin_amdgcn_exp2f((m[qt] - mn) * a.scale_log2e);
         m[qt] = mn;
+        const float shift = -mn * a.scale_log2e;                       // the softmax constant rides on the exponent's fma
         float ps = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(x[e] - mn); ps += x[e]; }
+        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], a.scale_log2e, shift)); ps += x[e]; }
         lsum[qt] = lsum[qt] * alpha + ps;
         if (__any(alpha != 1.0f)) {
 #pragma unroll
