@@ -48,7 +48,7 @@ struct Tiles {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Metadata of the unit being dequantized, one slab per wave (wave w dequantizes channel group w of the keys and of the
+// Metadata of the unit being dequantized (in LDS), one slab per wave (wave w dequantizes channel group w of the keys and of the
 // values, so it needs 32 scales and 32 zero-points of each tensor and nobody else's): written and read by the same
 // wave, no work-group barrier in between.
 struct MetaSlab {
@@ -58,7 +58,7 @@ struct MetaSlab {
     uint16_t vz[32];     // value zero-points
 };
 
-// Registers of a unit on its way from memory to LDS.  Quantized tensor: k0 / v0 = the dwords of the thread's two code
+// Registers of a unit on its way from the packed cache to the tiles.  Quantized tensor: k0 / v0 = the dwords of the thread's two code
 // groups; fp16 rows (16-bit tensor or window): k0, k1 / v0, v1 = two 16-byte row pieces.  m = this lane's 16-byte
 // piece of the wave's metadata (lanes 0..23).
 struct Stage { u32x4 k0, k1, v0, v1, m; };
@@ -251,9 +251,8 @@ __device__ __forceinline__ void store_value_codes(const LayerView &lv, Tiles &L,
     }
 }
 
-// ---- one packed unit: memory -> registers, registers -> LDS.  KQ / VQ: the layer's keys / values are quantized
-// (else fp16 rows in the code area).  Nothing in load_packed branches around a load, so the compiler can count the
-// loads in flight exactly and wait for one register stage while the next stays in flight.
+// ---- one packed unit: packed cache -> registers, registers -> tiles (LDS or the scratch area: the stores below only
+// see a reference).  KQ / VQ: the layer's keys / values are quantized (else fp16 rows in the code area).
 template <bool KQ, bool VQ>
 __device__ __forceinline__ void load_packed(const PrefillArgs &a, int bh, int u, int T, int tid, Stage &st)
 {
@@ -309,7 +308,7 @@ __device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, cons
     }
 }
 
-// ---- one chunk of the fp16 window (at most two per work-group: staged without overlap)
+// ---- one chunk of the fp16 window, ring -> LDS tiles (at most two chunks per work-group: staged without overlap)
 __device__ __forceinline__ void stage_window(const PrefillArgs &a, int bh, int u, int T, int tid, Tiles &L)
 {
     const uint16_t *krows = a.lv.kres + (size_t)bh * a.RC * kD, *vrows = a.lv.vres + (size_t)bh * a.RC * kD;
