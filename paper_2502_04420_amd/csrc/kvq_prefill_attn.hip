@@ -37,7 +37,8 @@ constexpr int kWaves = 8;                // waves of an attention work-group (32
 constexpr int kStagers = 4;              // waves that turn a unit into tiles (256 threads: the thread -> code maps below)
 constexpr int kQW = 32;                 // queries per wave
 constexpr int kQB = kQW * kWaves;       // queries per work-group
-constexpr int kKStride = kD + 8;        // halves per K^ row (272 bytes: the 16 rows of a 16-byte read fall on different banks)
+constexpr int kKStride = kD + 16;       // halves per K^ row: 288 bytes.  Measured with a probe kernel: the 16-byte operand reads of a wave
+                                        // (16 rows x 4 pieces) take 3.9 LDS cycles at this stride, like a linear read; 7.8 + 3.9 conflict cycles at 272
 constexpr int kVStride = 32 + 4;        // halves per V^ channel row (72 bytes = 18 banks: the 16 rows of an 8-byte read fall on different banks)
 
 struct Tiles {
@@ -321,13 +322,13 @@ __device__ __forceinline__ void stage_window(const PrefillArgs &a, int bh, int u
 
 __device__ __forceinline__ float xor_lanes(float x, int mask) { return __shfl_xor(x, mask, 64); }
 
-// One unit (32 tokens, in X) against the 32 queries of a wave: scores, online softmax, output accumulation.
-__device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X, int u, bool klo, int wmin, const int (&qpos)[2],
-                                            const half8 (&Qf)[2][4], float4v (&O)[8][2], float (&m)[2], float (&lsum)[2],
-                                            int n, int rq)
+// ---- the three phases of one unit (32 tokens, in X) against the 32 queries of a wave
+
+// S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt.  KLO: quantized keys, whose fp16 rounding
+// remainders are multiplied as well.
+template <bool KLO>
+__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[2][4], float4v (&S)[2][2], int n, int rq)
 {
-    // ---- S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt
-    float4v S[2][2];
 #pragma unroll
     for (int tt = 0; tt < 2; tt++) { S[tt][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; S[tt][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
 #pragma unroll
@@ -340,7 +341,7 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
             S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
         }
     }
-    if (klo) {                                  // quantized keys: the remainders of the fp16 rounding
+    if constexpr (KLO) {
 #pragma unroll
         for (int step = 0; step < 4; step++) {
             const half8 A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
@@ -352,14 +353,21 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
             }
         }
     }
-    const bool diag = 32 * u + 31 > wmin;                        // wave-uniform
-    half8 P[2];
+}
+
+// Online softmax in base 2 of the unit's scores: weights P (fp16, already in the operand order of the output product),
+// running maximum m (raw scores), partial sums lsum, and the factors alpha by which the accumulators shrink.
+// MASK: the unit reaches beyond some query's position.
+template <bool MASK>
+__device__ __forceinline__ void softmax_unit(const float4v (&S)[2][2], float c, int u, const int (&qpos)[2], float (&m)[2],
+                                             float (&lsum)[2], half8 (&P)[2], float (&alpha)[2], int rq)
+{
 #pragma unroll
     for (int qt = 0; qt < 2; qt++) {
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3];      // raw scores; the running maximum is kept raw too
-        if (diag) {
+        if constexpr (MASK) {
 #pragma unroll
             for (int e = 0; e < 8; e++)
                 if (32 * u + 16 * (e >> 2) + 4 * rq + (e & 3) > qpos[qt]) x[e] = -INFINITY;
@@ -369,22 +377,54 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
         mx = fmaxf(mx, xor_lanes(mx, 32));
         // unit 0 holds token 0, which every query sees: the running maximum is finite from the start
         const float mn = fmaxf(m[qt], mx);
-        const float alpha = __builtin_amdgcn_exp2f((m[qt] - mn) * a.scale_log2e);
+        alpha[qt] = __builtin_amdgcn_exp2f((m[qt] - mn) * c);
         m[qt] = mn;
-        const float shift = -mn * a.scale_log2e;                       // the softmax constant rides on the exponent's fma
+        const float shift = -mn * c;                                   // the softmax constant rides on the exponent's fma
         float ps = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], a.scale_log2e, shift)); ps += x[e]; }
-        lsum[qt] = lsum[qt] * alpha + ps;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha;
-        }
+        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], c, shift)); ps += x[e]; }
+        lsum[qt] = lsum[qt] * alpha[qt] + ps;
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
                       (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
     }
-    // ---- O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
-    // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}
+}
+
+// The running maximum only has to be a reference that keeps the weights in range, not the exact maximum: as long as no
+// score of the unit exceeds it by more than kCalm (in the exponent's units), the unit can be added with the reference
+// unchanged: no maximum across lanes, no rescaling, weights <= 2^kCalm (fp16 holds them, the accumulators are fp32).
+constexpr float kCalm = 8.0f;
+
+// true if some score of the unit (no mask) exceeds its query's reference by more than kCalm, in any lane of the wave
+__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][2], float c, const float (&m)[2])
+{
+    bool over = false;
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+        const float4v a = S[0][qt], b = S[1][qt];
+        const float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
+        over |= (mx - m[qt]) * c > kCalm;                  // m = -inf at the start: always over
+    }
+    return __any(over);
+}
+
+// softmax weights of a unit against the unchanged reference (no mask)
+__device__ __forceinline__ void softmax_calm(const float4v (&S)[2][2], float c, const float (&m)[2], float (&lsum)[2], half8 (&P)[2])
+{
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+        const float shift = -m[qt] * c;
+        float x[8], ps = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(S[e >> 2][qt][e & 3], c, shift)); ps += x[e]; }
+        lsum[qt] += ps;
+        P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
+                      (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
+    }
+}
+
+// O^T += V^T P^T
+__device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[2], float4v (&O)[8][2], int n, int rq)
+{
 #pragma unroll
     for (int ct = 0; ct < 8; ct++) {
         const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
@@ -393,6 +433,20 @@ __device__ __forceinline__ void attend_unit(const PrefillArgs &a, const Tiles &X
         O[ct][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[0], O[ct][0], 0, 0, 0);
         O[ct][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[1], O[ct][1], 0, 0, 0);
     }
+}
+
+// O^T = alpha O^T + V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
+// {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.  The accumulators are rescaled only when some maximum moved.
+__device__ __forceinline__ void output_unit(const Tiles &X, const half8 (&P)[2], const float (&alpha)[2], float4v (&O)[8][2], int n, int rq)
+{
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+        if (__any(alpha[qt] != 1.0f)) {
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha[qt];
+        }
+    }
+    output_add(X, P, O, n, rq);
 }
 
 // ---- pass 1: every packed unit of the (batch, kv head) caches [bh0, bh0 + n_bh) is dequantized once into the scratch
@@ -438,7 +492,15 @@ __device__ __forceinline__ void store_copy(Tiles &L, int tid, const Copy &c)
 }
 
 // ---- pass 2: the attention itself.  One work-group per 256 consecutive queries of one query head; every wave attends
-// 32 queries and copies its share of each unit from the scratch area into LDS.
+// 32 queries and copies its share of each unit from the scratch area into LDS.  KLO: the keys are quantized (they come
+// as two fp16 numbers).
+//
+// Three LDS buffers: while unit u is being used, unit u + 1 is already there and unit u + 2 is being written.  That
+// lets a wave issue the score products of unit u + 1 in the same stretch of code as the softmax of unit u (matrix
+// and vector instructions that do not depend on each other), instead of waiting for each product's result in turn.
+constexpr int kBuffers = 3;
+
+template <bool KLO>
 __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -470,10 +532,12 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     const int units = (p0 + ilast) / 32 + 1;                     // units the work-group walks through
     const int iw = i0 + kQW * wave;                              // first query of this wave
     const int wlast = iw < a.n_q ? (p0 + (iw + kQW - 1 < a.n_q ? iw + kQW - 1 : a.n_q - 1)) / 32 : -1;
-    const int wmin = p0 + iw;                                    // units that reach beyond it need the mask
-    const bool klo = a.lv.kbits < 16;                            // quantized keys come as two fp16 numbers
+    const int wmin = p0 + iw;                                    // position of the wave's first query
+    const int open_units = iw < a.n_q ? (wmin + 1) / 32 : 0;     // units [0, open_units) lie before it: no mask needed
+    const float c = a.scale_log2e;
 
-    __shared__ __attribute__((aligned(16))) Tiles L[2];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    Tiles *L = reinterpret_cast<Tiles *>(lds_raw);
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
     int qpos[2];
@@ -492,37 +556,64 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     for (int ct = 0; ct < 8; ct++) { O[ct][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; O[ct][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
     float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};
 
-    // ---- packed units [0, nb).  Two register stages: the loads of unit u + 2 are issued before unit u is used and are
-    // written to LDS after unit u + 1 has been, so that a load has two units' worth of arithmetic to arrive.  Loads and
-    // LDS writes are never skipped (past the end the last unit is staged again, into a buffer nobody reads any more).
+    // ---- packed units [0, nb).  Unit u lives in buffer u % 3.  Per trip: the wave uses unit u (and takes the scores of
+    // unit u + 1 ahead), writes unit u + 2 from its registers and issues the loads of unit u + 3, which stay in flight
+    // across the barrier.  Loads and LDS writes are never skipped (past the end the last unit is staged again, into a
+    // buffer nobody reads any more): no branch lies between the issue of a load and its use.
     const int nb = a.n_blocks < units ? a.n_blocks : units;
     if (nb > 0) {
         const uint8_t *mine = a.scratch + (size_t)local * a.n_blocks * sizeof(Tiles);
         const int last = nb - 1;
         auto unit_at = [&](int u) { return mine + (size_t)(u < last ? u : last) * sizeof(Tiles); };
-        Copy ca, cb;
-        load_copy(unit_at(0), tid, ca);
-        load_copy(unit_at(1), tid, cb);
-        store_copy(L[0], tid, ca);
+        Copy cp;
+        load_copy(unit_at(0), tid, cp);
+        store_copy(L[0], tid, cp);
+        load_copy(unit_at(1), tid, cp);
+        store_copy(L[1], tid, cp);
+        load_copy(unit_at(2), tid, cp);
         __syncthreads();
-        for (int u = 0; u < nb; u += 2) {
-            // even unit: stage cb holds unit u + 1, stage ca takes unit u + 2
-            load_copy(unit_at(u + 2), tid, ca);
-            if (u <= wlast) attend_unit(a, L[0], u, klo, wmin, qpos, Qf, O, m, lsum, n, rq);
-            store_copy(L[1], tid, cb);
+        float4v S[2][2], Sn[2][2];
+        if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq);
+        int b0 = 0;                                              // buffer of unit u
+        for (int u = 0; u < nb; u++) {
+            const int b1 = b0 + 1 < kBuffers ? b0 + 1 : 0, b2 = b1 + 1 < kBuffers ? b1 + 1 : 0;
+            if (u <= wlast) {
+                const bool ahead = u + 1 < nb && u + 1 <= wlast;
+                half8 P[2];
+                if (ahead && u < open_units && !unit_exceeds(S, c, m)) {
+                    // the common trip, one stretch of straight-line code: score products of the next unit, weights of
+                    // this one against the unchanged reference, output products of this one
+                    score_unit<KLO>(L[b1], Qf, Sn, n, rq);
+                    softmax_calm(S, c, m, lsum, P);
+                    output_add(L[b0], P, O, n, rq);
+                } else {
+                    float alpha[2];
+                    if (ahead) score_unit<KLO>(L[b1], Qf, Sn, n, rq);
+                    if (u < open_units) softmax_unit<false>(S, c, u, qpos, m, lsum, P, alpha, rq);
+                    else softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
+                    output_unit(L[b0], P, alpha, O, n, rq);
+                }
+#pragma unroll
+                for (int tt = 0; tt < 2; tt++) { S[tt][0] = Sn[tt][0]; S[tt][1] = Sn[tt][1]; }
+            }
+            store_copy(L[b2], tid, cp);                          // unit u + 2
+            load_copy(unit_at(u + 3), tid, cp);
             __syncthreads();
-            // odd unit: stage ca holds unit u + 2, stage cb takes unit u + 3
-            load_copy(unit_at(u + 3), tid, cb);
-            if (u + 1 < nb && u + 1 <= wlast) attend_unit(a, L[1], u + 1, klo, wmin, qpos, Qf, O, m, lsum, n, rq);
-            store_copy(L[0], tid, ca);
-            __syncthreads();
+            b0 = b1;
         }
     }
     // ---- chunks of the fp16 window, staged by the first four waves straight from the ring
     for (int u = nb; u < units; u++) {
         if (wave < kStagers) stage_window(a, bh, u, T, tid, L[0]);
         __syncthreads();
-        if (u <= wlast) attend_unit(a, L[0], u, false, wmin, qpos, Qf, O, m, lsum, n, rq);
+        if (u <= wlast) {
+            float4v S[2][2];
+            half8 P[2];
+            float alpha[2];
+            score_unit<false>(L[0], Qf, S, n, rq);
+            softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
+            output_unit(L[0], P, alpha, O, n, rq);
+        }
         __syncthreads();
     }
 
@@ -544,6 +635,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
 }
 
 }  // namespace
+
 
 size_t prefill_unit_bytes() { return sizeof(Tiles); }
 
@@ -567,11 +659,19 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // pass 2
+    // pass 2 (three tile buffers: more LDS than a kernel may declare statically)
     const dim3 grid((unsigned)groups), block(64 * kWaves);
+    const size_t lds = kBuffers * sizeof(Tiles);
     hipEvent_t b2 = a.n_blocks > 0 ? nullptr : ev_begin;
-    if (b2 || ev_end) hipExtLaunchKernelGGL(prefill_attention, grid, block, 0, s, b2, ev_end, 0, a);
-    else hipLaunchKernelGGL(prefill_attention, grid, block, 0, s, a);
+    auto attend = [&](auto kernel) -> hipError_t {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        if (b2 || ev_end) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, b2, ev_end, 0, a);
+        else hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
+        return hipSuccess;
+    };
+    const hipError_t e2 = a.lv.kbits < 16 ? attend(prefill_attention<true>) : attend(prefill_attention<false>);
+    if (e2 != hipSuccess) return e2;
     return hipGetLastError();
 }
 
