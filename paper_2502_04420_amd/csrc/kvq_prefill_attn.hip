@@ -13,13 +13,15 @@
 //      kernel instead repeats this work for every query head of the group and every query tile (256 times per unit at
 //      8192 queries) and made that kernel bound by its vector instructions.
 //   2. prefill_attention: a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two
-//      16-query tiles).  The units are copied from the scratch area (fp16 window chunks: from the ring) into double
-//      buffered LDS tiles, two register stages ahead of their use.  Scores are computed transposed, S^T = K^ Q^T
+//      16-query tiles).  The units are copied from the scratch area (fp16 window chunks: from the ring) into three
+//      LDS tile buffers, so that the score products of the next unit can be issued next to the softmax weights of the
+//      current one.  Scores are computed transposed, S^T = K^ Q^T
 //      (16x16x32 f16 instructions, tokens along the rows): a lane then holds, for its query, the scores of tokens
 //      {4 rq .. 4 rq + 3} and {16 + 4 rq ..}, which is exactly a B operand of O^T += V^T P^T when the A operand (V^T
 //      from LDS) lists its tokens in the same order.  The softmax weights therefore go from the accumulator of one
-//      product into the operand of the next without leaving the registers.  Online softmax in base 2 per query (running
-//      maximum shared by the four lanes that hold a query), fp32 accumulation, one division at the end.
+//      product into the operand of the next without leaving the registers.  Online softmax in base 2 per query (the
+//      reference maximum is shared by the four lanes that hold a query and only moves when a score exceeds it by more
+//      than 2^8), fp32 accumulation, one division at the end.
 #include <hip/hip_ext.h>
 
 #include <type_traits>
