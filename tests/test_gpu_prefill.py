@@ -168,3 +168,13 @@ def test_llama_shape_full_prompt_sampled_rows(kvq_mod, oracle_mod):
         o.close()
     g.close()
     assert worst > 0
+
+
+@pytest.mark.parametrize("batch,hkv", [(5, 4), (3, 8), (17, 1)])
+def test_more_caches_than_one_pass_holds(kvq_mod, oracle_mod, batch, hkv):
+    """The call takes 16 (batch, kv head) caches per pass: 20 = 16 + 4, 24 = 16 + 8 and 17 = 16 + 1 exercise the second
+    pass with a count that is and is not a multiple of the 8 XCDs; queries are a proper tail of the prompt."""
+    w = W.Workload("chunks", 1, batch, 2 * hkv, hkv, 128, 32 * 9 + 5, [4], [2], seed=700 + batch, outlier_channels=2)
+    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, 270)
+    assert_prefill_close(out, o64, "B%d Hkv%d" % (batch, hkv))
+    g.close()
