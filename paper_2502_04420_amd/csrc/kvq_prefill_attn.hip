@@ -666,8 +666,12 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
     const size_t lds = kBuffers * sizeof(Tiles);
     hipEvent_t b2 = a.n_blocks > 0 ? nullptr : ev_begin;
     auto attend = [&](auto kernel) -> hipError_t {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static bool allowed = false;                   // per instantiation: the larger dynamic LDS size is granted once
+        if (!allowed) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            allowed = true;
+        }
         if (b2 || ev_end) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, b2, ev_end, 0, a);
         else hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
         return hipSuccess;
