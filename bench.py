@@ -33,7 +33,8 @@ FUSED_STEP = True               # False with --separate-calls (kvq_quantize_appe
 
 
 def layer_bytes(w, kb, vb, n_packed, n_res):
-    """Algorithmic HBM bytes of one decode_attention launch on one layer."""
+    """Algorithmic HBM bytes of one decode_attention launch on one layer: codes, fp32 scales and fp16 zero-points of the
+    packed tokens of both tensors, the fp16 window rows, the queries and the outputs."""
     from paper_2502_04420_amd import bytes_per_token
 
     per_tok = bytes_per_token(kb, vb, w.head_dim, w.group, scale_bytes=SCALE_BYTES)
@@ -326,8 +327,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv8", action="store_true")
     ap.add_argument("--no-32k", action="store_true",
-                    help="skip the extra point at 32768 tokens of context (same family and schedule, batch 32, 16 steps; "
-                         "the north star's target is stated at that context length)")
+                    help="skip the extra point at 32768 tokens of context (same family and schedule, batch 32, 16 steps: "
+                         "enough bytes per launch for the kernels' steady state)")
     ap.add_argument("--no-prefill-attn", action="store_true",
                     help="skip the extra measurement of the prefill-stage attention kernel (one layer of the dominant pair)")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")

@@ -70,7 +70,7 @@ def _check_layer(kvq_mod, oracle_mod, w, layer, extra_tokens, samples, meta16=Fa
 
 
 def test_llama_shape_batch16_context8192_mix_and_kv8(kvq_mod, oracle_mod):
-    """BASELINE configuration 3 (3.25-bit mix: K4V4 and K4V2 layers) and the uniform K8V8 baseline at the same shape."""
+    """The benchmark's Llama-3.1-8B shape (3.25-bit mix: K4V4 and K4V2 layers) and uniform K8V8 at the same shape."""
     w = W.config3(16, 8192)
     samples = [0, 37, 77, 127]                      # (b, h) = (0,0), (4,5), (9,5), (15,7)
     _check_layer(kvq_mod, oracle_mod, w, 0, 3, samples[:2])            # K4V4 layer
@@ -81,7 +81,7 @@ def test_llama_shape_batch16_context8192_mix_and_kv8(kvq_mod, oracle_mod):
 
 
 def test_qwen_shape_batch8_context32768_biased_keys(kvq_mod, oracle_mod):
-    """BASELINE configuration 4: g_q = 7, keys with a large per-channel offset, 32K context (K8V2 and K4V2 layers)."""
+    """The Qwen2.5-7B shape: g_q = 7, keys with a large per-channel offset, 32K context (K8V2 and K4V2 layers)."""
     w = W.config4(8, 32768)
     _check_layer(kvq_mod, oracle_mod, w, 0, 1, [3, 30])                # K8V2 layer
     _check_layer(kvq_mod, oracle_mod, w, 1, 33, [17])                  # K4V2 layer
