@@ -45,6 +45,10 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError("%s is not built; run `python -m paper_2502_04420_amd.build` "
                           "(or __graft_entry__.build())" % _LIB_PATH)
+    # torch first: it brings the HIP runtime it was built with, and the library must bind to that same copy (the one
+    # that owns torch's streams and allocations), not pull in a second runtime of its own
+    import torch  # noqa: F401
+
     lib = ctypes.CDLL(_LIB_PATH)
     lib.kvq_workspace_bytes.restype = c_size_t
     lib.kvq_workspace_bytes.argtypes = [POINTER(_Config)]

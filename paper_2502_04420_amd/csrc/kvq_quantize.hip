@@ -61,43 +61,43 @@ __device__ __forceinline__ float round_exact(float d, float s)
 // Eight elements at once, codes returned as floats.  d * (1 / s) with the hardware reciprocal (1 ulp) differs
 // from the correctly rounded quotient by less than 2^-22 of its value, so both round to the same integer
 // unless the product lies that close to a tie; the test below uses twice that distance.  If it fires for any
-// lane of the wave (rare for real data, always for exact ties) the eight elements are redone with the
-// defining division.  d >= 0 and rs >= 0 (rs is 0 where s is 0, giving code 0), so the fast result needs no clamp
-// from below, and none from above either while s is the fp32 scale: d / s <= (2^B - 1)(1 + 2^-23).  CLAMP is for
-// the narrow-metadata variant, whose rounded scale can be too small.
+// lane of the wave (rare for real data, always for exact ties) the caller redoes the eight elements with the
+// defining division (redo8; only then are the scales themselves fetched).  d >= 0 and rs >= 0 (rs is 0 where s
+// is 0, giving code 0), so the fast result needs no clamp from below, and none from above either while s is the
+// fp32 scale: d / s <= (2^B - 1)(1 + 2^-23).  CLAMP is for the narrow-metadata variant, whose rounded scale can
+// be too small.  Returns true if the redo is needed; d = x - z is handed back for it.
+//
+// x and z come as fp16 pairs.  d = fma(x, one, -z) with both widened exactly is the one IEEE subtraction of the
+// definition; `one` is 1.0 in a register the compiler cannot see through, so that the widenings and the
+// subtraction stay one mixed-precision instruction instead of three.
+// The distance of t = d * rs from the nearest tie is 1/2 - |t - rint(t)| (both differences are exact).
 template <int BITS, bool CLAMP>
-__device__ __forceinline__ void encode8(const uint32_t (&xw)[4], const float (&s8)[8], const float (&z8)[8], const float (&r8)[8],
-                                        float (&c8)[8])
+__device__ __forceinline__ bool encode8(const uint32_t (&xw)[4], const uint32_t (&zw)[4], const float (&r8)[8], float one,
+                                        float (&d)[8], float (&c8)[8])
 {
-    float d[8], u[8];
-    bool redo;
-    if constexpr (!CLAMP && BITS <= 4) {
-        // few levels: one margin for all, 2^-21 times an upper bound 2^B of the quotient; u = distance to the nearest tie
+    float u[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
-            const float t = d[e] * r8[e];
-            c8[e] = rintf(t);
-            u[e] = fabsf(__builtin_amdgcn_fractf(t) - 0.5f);
-        }
-        const float nearest = fminf(fminf(fminf(u[0], u[1]), fminf(u[2], u[3])), fminf(fminf(u[4], u[5]), fminf(u[6], u[7])));
-        redo = __any(nearest <= (float)(1 << BITS) * 4.76837158203125e-07f);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            d[e] = half_bits_to_float((xw[e >> 1] >> (16 * (e & 1))) & 0xffffu) - z8[e];
-            const float t = d[e] * r8[e];
-            c8[e] = CLAMP ? fminf(rintf(t), (float)((1 << BITS) - 1)) : rintf(t);
-            u[e] = fmaf(t, 4.76837158203125e-07f, -fabsf(__builtin_amdgcn_fractf(t) - 0.5f));    // 2^-21 t - |frac(t) - 1/2|
-        }
-        // some element is within its margin of a tie <=> the largest u is >= 0
-        const float worst = fmaxf(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])), fmaxf(fmaxf(u[4], u[5]), fmaxf(u[6], u[7])));
-        redo = __any(worst >= 0.0f);
+    for (int e = 0; e < 8; e++) {
+        const half2v xh = __builtin_bit_cast(half2v, xw[e >> 1]), zh = __builtin_bit_cast(half2v, zw[e >> 1]);
+        d[e] = __builtin_fmaf((float)xh[e & 1], one, -(float)zh[e & 1]);
+        const float t = d[e] * r8[e];
+        const float c = rintf(t);
+        c8[e] = CLAMP ? fminf(c, (float)((1 << BITS) - 1)) : c;
+        const float res = fabsf(t - c);
+        // few levels: one margin for all, 2^-21 times an upper bound 2^B of the quotient; else 2^-21 t
+        if constexpr (!CLAMP && BITS <= 4) u[e] = res;
+        else u[e] = __builtin_fmaf(t, 4.76837158203125e-07f, res);
     }
-    if (redo) {
+    const float worst = fmaxf(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])), fmaxf(fmaxf(u[4], u[5]), fmaxf(u[6], u[7])));
+    if constexpr (!CLAMP && BITS <= 4) return __any(worst >= 0.5f - (float)(1 << BITS) * 4.76837158203125e-07f);
+    else return __any(worst >= 0.5f);
+}
+
+template <int BITS>
+__device__ __forceinline__ void redo8(const float (&d)[8], const float (&s8)[8], float (&c8)[8])
+{
 #pragma unroll
-        for (int e = 0; e < 8; e++) c8[e] = round_exact<BITS>(d[e], s8[e]);
-    }
+    for (int e = 0; e < 8; e++) c8[e] = round_exact<BITS>(d[e], s8[e]);
 }
 
 // The lane's codes 8*m .. 8*m + 7 (as floats) into their dwords.  The fields of a dword are assembled in
@@ -153,6 +153,29 @@ __device__ __forceinline__ void load8(const float *p, float (&v)[8])
     *reinterpret_cast<float4 *>(&v[4]) = *reinterpret_cast<const float4 *>(p + 4);
 }
 
+// eight zero-points as they are kept (fp16, minima of fp16 inputs): one 16-byte read
+__device__ __forceinline__ void load8_half(const uint16_t *p, uint32_t (&v)[4])
+{
+    const uint4 w = *reinterpret_cast<const uint4 *>(p);
+    v[0] = w.x; v[1] = w.y; v[2] = w.z; v[3] = w.w;
+}
+
+// the value held by lane ^ 1 / lane ^ 2: exchanges inside a group of four lanes are done by the vector unit
+// itself (data-parallel primitive, quad permutation), not through the LDS crossbar
+__device__ __forceinline__ uint32_t from_lane_xor1(uint32_t x) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t from_lane_xor2(uint32_t x) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true); }
+
+// Exchanges with lane ^ 16 and lane ^ 32, for symmetric uses only (min, max): the swap instructions exchange the
+// odd rows of 16 lanes (the upper 32 lanes) of their first operand with the even rows (the lower 32 lanes) of their
+// second.  Fed the same register twice, every lane ends up with its own value in one result and its partner's
+// in the other (which is which depends on the lane).
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 pair_xor16(uint32_t x) { return __builtin_amdgcn_permlane16_swap(x, x, false, false); }
+__device__ __forceinline__ u32x2 pair_xor32(uint32_t x) { return __builtin_amdgcn_permlane32_swap(x, x, false, false); }
+// lane 7 - i of each 8 / lane 15 - i of each 16 (row mirrors): complete a reduction once the lanes of a quad agree
+__device__ __forceinline__ uint32_t from_half_row_mirror(uint32_t x) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t from_row_mirror(uint32_t x) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x140, 0xF, 0xF, true); }
+
 // 16-bit half of the block-exponent word: exponent e of max = f * 2^e, f in [0.5, 1), biased by 32768
 // (32768 itself for an all-constant block or an fp16 tensor)
 __device__ __forceinline__ uint16_t biased_exponent(float wave_max)
@@ -162,11 +185,18 @@ __device__ __forceinline__ uint16_t biased_exponent(float wave_max)
     return (uint16_t)(e + 32768);
 }
 
-__device__ __forceinline__ float wave_max64(float x)
+// maximum over the wave of non-negative numbers (their bit patterns order like the numbers), in every lane
+__device__ __forceinline__ float wave_max64(float xf)
 {
-#pragma unroll
-    for (int sft = 1; sft < 64; sft <<= 1) x = fmaxf(x, __shfl_xor(x, sft));
-    return x;
+    uint32_t x = __builtin_bit_cast(uint32_t, xf);
+    x = max(x, from_lane_xor1(x));
+    x = max(x, from_lane_xor2(x));
+    x = max(x, from_half_row_mirror(x));
+    x = max(x, from_row_mirror(x));
+    u32x2 w = pair_xor16(x);
+    x = max(w.x, w.y);
+    w = pair_xor32(x);
+    return __builtin_bit_cast(float, max(w.x, w.y));
 }
 
 // Row of channel ch in the transposed value tile.  Rows are 80 bytes (32 tokens + 16 bytes of padding); the
@@ -190,18 +220,31 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
 
     // keys [token][channel] with rows of kD + 8 halves, or values [row of channel][token] with rows of 32 + 8 halves
     __shared__ __attribute__((aligned(16))) uint16_t tile[kD * (32 + 8)];
-    __shared__ __attribute__((aligned(16))) float sc[kD], zp[kD], rsc[kD];    // scale, zero-point, 1 / scale
+    __shared__ __attribute__((aligned(16))) float sc[kD], rsc[kD];            // scale (read only when a redo is needed), 1 / scale
+    __shared__ __attribute__((aligned(16))) uint16_t zp[kD];                  // zero-point, fp16 as stored
     static_assert(kD * (32 + 8) >= 32 * (kD + 8), "one buffer serves both arrangements");
 
     // keys: lane = 16*r + c16 holds tokens r, r+4, .., r+28; values: tokens 8*r .. 8*r+7 (8 channels 8*c16.. each)
     const uint16_t *in = values ? a.v_in : a.k_in, *ring = values ? a.lv.vres : a.lv.kres;
     uint32_t x[8][4];
+    if (blk * kG >= a.t_old) {
+        // the whole block comes from the caller's tensor (always so in a prompt's first append): one row address, fixed steps
+        const uint16_t *row0 = in + ((size_t)bh * a.n_in + (blk * kG - a.t_old) + (values ? 8 * r : r)) * kD + 8 * c16;
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const int pos = blk * kG + (values ? 8 * r + i : r + 4 * i);
-        const uint4 w = *reinterpret_cast<const uint4 *>(token_row(in, ring, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
-        x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
+        for (int i = 0; i < 8; i++) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(row0 + (values ? i : 4 * i) * kD);
+            x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int pos = blk * kG + (values ? 8 * r + i : r + 4 * i);
+            const uint4 w = *reinterpret_cast<const uint4 *>(token_row(in, ring, bh, pos, a.t_old, a.n_in, a.RC) + 8 * c16);
+            x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
+        }
     }
+    float one;                                                   // 1.0, opaque to the compiler (see encode8)
+    asm("s_mov_b32 %0, 1.0" : "=s"(one));
     const size_t blk_index = (size_t)bh * a.NB + blk;
     uint16_t *bexp16 = reinterpret_cast<uint16_t *>(a.lv.bexp + blk_index);    // [0] keys, [1] values
 
@@ -228,8 +271,10 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     for (int p = 0; p < 4; p++) { mnp[p] = pk_min(mnp[p], x[i][p]); mxp[p] = pk_max(mxp[p], x[i][p]); }
 #pragma unroll
                 for (int p = 0; p < 4; p++) {
-                    mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 16)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 16));
-                    mnp[p] = pk_min(mnp[p], __shfl_xor(mnp[p], 32)); mxp[p] = pk_max(mxp[p], __shfl_xor(mxp[p], 32));
+                    u32x2 w = pair_xor16(mnp[p]); mnp[p] = pk_min(w.x, w.y);
+                    w = pair_xor16(mxp[p]); mxp[p] = pk_max(w.x, w.y);
+                    w = pair_xor32(mnp[p]); mnp[p] = pk_min(w.x, w.y);
+                    w = pair_xor32(mxp[p]); mxp[p] = pk_max(w.x, w.y);
                 }
                 // every lane row now holds the statistics of all 8 channels: row r finishes channels 2r and 2r + 1
                 const uint32_t mn2 = r == 0 ? mnp[0] : r == 1 ? mnp[1] : r == 2 ? mnp[2] : mnp[3];
@@ -241,7 +286,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mx2 >> (16 * h)) & 0xffffu);
                     const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
                     s_max = fmaxf(s_max, s);
-                    sc[ch] = s; zp[ch] = mn; rsc[ch] = recip_or_zero(s);
+                    sc[ch] = s; zp[ch] = (uint16_t)mnb; rsc[ch] = recip_or_zero(s);
                     store_scale<NARROW>(meta, ch, s); meta_zeros(meta, NARROW)[ch] = (uint16_t)mnb;
                 }
             } else {
@@ -252,16 +297,17 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     const int t = r + 4 * i;
                     uint32_t mnp = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
                     uint32_t mxp = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
-                    mnp = pk_min(mnp, __shfl_xor(mnp, 1)); mxp = pk_max(mxp, __shfl_xor(mxp, 1));
-                    mnp = pk_min(mnp, __shfl_xor(mnp, 2)); mxp = pk_max(mxp, __shfl_xor(mxp, 2));
+                    mnp = pk_min(mnp, from_lane_xor1(mnp)); mxp = pk_max(mxp, from_lane_xor1(mxp));
+                    mnp = pk_min(mnp, from_lane_xor2(mnp)); mxp = pk_max(mxp, from_lane_xor2(mxp));
                     const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
                     const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
                     const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
                     s_max = fmaxf(s_max, s);
                     if ((c16 & 3) == 0) {
                         const int gd = c16 >> 2;
-                        sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
-                        store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
+                        const uint16_t zb = float_to_half_bits_exact(mn);
+                        sc[32 * gd + t] = s; zp[32 * gd + t] = zb; rsc[32 * gd + t] = recip_or_zero(s);
+                        store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = zb;
                     }
                 }
             }
@@ -271,23 +317,42 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             s_max = wave_max64(s_max);
             if (lane == 0) bexp16[0] = biased_exponent(s_max);
             __syncthreads();
-            // codes in the lane layout of kvq_layout.h
+            // codes in the lane layout of kvq_layout.h: dword group m = 4*th + cb holds token 16*th + n, channels
+            // 32*cb + 8*kq ..; the metadata of a channel set serves both token halves
             uint32_t dw[2 * KB];
 #pragma unroll
-            for (int m = 0; m < 8; m++) {
-                const int token = 16 * (m >> 2) + n, ch0 = 32 * (m & 3) + 8 * kq;
-                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[token * (kD + 8) + ch0]);
-                const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-                float s8[8], z8[8], r8[8], c8[8];
-                if (!kpt) {
-                    load8(&sc[ch0], s8); load8(&zp[ch0], z8); load8(&rsc[ch0], r8);
-                } else {
-                    const int gi = 32 * (m & 3) + token;          // one (s, z) for the 8 channels of this token and group
+            for (int cb = 0; cb < 4; cb++) {
+                const int ch0 = 32 * cb + 8 * kq;
+                uint32_t zw[4];
+                float r8[8];
+                if (!kpt) { load8_half(&zp[ch0], zw); load8(&rsc[ch0], r8); }
 #pragma unroll
-                    for (int e = 0; e < 8; e++) { s8[e] = sc[gi]; z8[e] = zp[gi]; r8[e] = rsc[gi]; }
+                for (int th = 0; th < 2; th++) {
+                    const int m = 4 * th + cb, token = 16 * th + n;
+                    const int gi = 32 * cb + token;               // per-token keys: one (s, z) for the 8 channels of this token and group
+                    const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[token * (kD + 8) + ch0]);
+                    const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
+                    if (kpt) {
+                        const uint32_t zb = zp[gi];
+                        const float rr = rsc[gi];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) zw[e] = zb | (zb << 16);
+#pragma unroll
+                        for (int e = 0; e < 8; e++) r8[e] = rr;
+                    }
+                    float d[8], c8[8];
+                    if (encode8<KB, NARROW>(xw, zw, r8, one, d, c8)) {
+                        float s8[8];
+                        if (!kpt) {
+                            load8(&sc[ch0], s8);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; e++) s8[e] = sc[gi];
+                        }
+                        redo8<KB>(d, s8, c8);
+                    }
+                    pack8<KB>(c8, m, dw);
                 }
-                encode8<KB, NARROW>(xw, s8, z8, r8, c8);
-                pack8<KB>(c8, m, dw);
             }
             uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
 #pragma unroll
@@ -312,8 +377,8 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             for (int i = 0; i < 8; i++) {
                 mnp[i] = pk_min(pk_min(x[i][0], x[i][1]), pk_min(x[i][2], x[i][3]));
                 mxp[i] = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
-                mnp[i] = pk_min(mnp[i], __shfl_xor(mnp[i], 1)); mxp[i] = pk_max(mxp[i], __shfl_xor(mxp[i], 1));
-                mnp[i] = pk_min(mnp[i], __shfl_xor(mnp[i], 2)); mxp[i] = pk_max(mxp[i], __shfl_xor(mxp[i], 2));
+                mnp[i] = pk_min(mnp[i], from_lane_xor1(mnp[i])); mxp[i] = pk_max(mxp[i], from_lane_xor1(mxp[i]));
+                mnp[i] = pk_min(mnp[i], from_lane_xor2(mnp[i])); mxp[i] = pk_max(mxp[i], from_lane_xor2(mxp[i]));
             }
             // the 4 lanes of a group hold the same 8 results: lane q = c16 & 3 finishes tokens q and q + 4 of its row
             const int q4 = c16 & 3, gd = c16 >> 2;
@@ -326,8 +391,9 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 const float mx = fmaxf(half_bits_to_float(mxb & 0xffffu), half_bits_to_float(mxb >> 16));
                 const float s = stored_scale<NARROW>(scale_of(mn, mx, VB));
                 s_max = fmaxf(s_max, s);
-                sc[32 * gd + t] = s; zp[32 * gd + t] = mn; rsc[32 * gd + t] = recip_or_zero(s);
-                store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = float_to_half_bits_exact(mn);
+                const uint16_t zb = float_to_half_bits_exact(mn);
+                sc[32 * gd + t] = s; zp[32 * gd + t] = zb; rsc[32 * gd + t] = recip_or_zero(s);
+                store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = zb;
             }
             // 8 x 8 transpose in registers: channel 8*c16 + e gets its 8 tokens as one 16-byte chunk
             const int krow = (c16 & 7) | (((c16 ^ (c16 >> 3)) & 1) << 3);      // value_row(8*c16 + e) = (c16 >> 1) << 4 | (krow ^ e)
@@ -345,14 +411,24 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             uint32_t dw[2 * VB];
             const int nrow = (n ^ (n >> 3)) & 15;                               // value_row(16*m + n) = m << 4 | (nrow ^ 2*m)
 #pragma unroll
-            for (int m = 0; m < 8; m++) {
-                const int gd = m >> 1, row = (m << 4) | (nrow ^ ((2 * m) & 15));
-                const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[row * (32 + 8) + 8 * kq]);
-                const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
-                float s8[8], z8[8], r8[8], c8[8];
-                load8(&sc[32 * gd + 8 * kq], s8); load8(&zp[32 * gd + 8 * kq], z8); load8(&rsc[32 * gd + 8 * kq], r8);
-                encode8<VB, NARROW>(xw, s8, z8, r8, c8);
-                pack8<VB>(c8, m, dw);
+            for (int gd = 0; gd < 4; gd++) {
+                // the lane's tokens 8*kq .. 8*kq + 7 of channel group gd: one set of metadata for two dword groups
+                uint32_t zw[4];
+                float r8[8];
+                load8_half(&zp[32 * gd + 8 * kq], zw); load8(&rsc[32 * gd + 8 * kq], r8);
+#pragma unroll
+                for (int j = 0; j < 2; j++) {
+                    const int m = 2 * gd + j, row = (m << 4) | (nrow ^ ((2 * m) & 15));
+                    const uint4 xx = *reinterpret_cast<const uint4 *>(&tile[row * (32 + 8) + 8 * kq]);
+                    const uint32_t xw[4] = {xx.x, xx.y, xx.z, xx.w};
+                    float d[8], c8[8];
+                    if (encode8<VB, NARROW>(xw, zw, r8, one, d, c8)) {
+                        float s8[8];
+                        load8(&sc[32 * gd + 8 * kq], s8);
+                        redo8<VB>(d, s8, c8);
+                    }
+                    pack8<VB>(c8, m, dw);
+                }
             }
             uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
 #pragma unroll
