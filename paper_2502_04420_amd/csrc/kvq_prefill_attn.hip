@@ -50,6 +50,7 @@ struct Tiles {
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Metadata of the unit being dequantized (in LDS), one slab per wave (wave w dequantizes channel group w of the keys and of the
 // values, so it needs 32 scales and 32 zero-points of each tensor and nobody else's): written and read by the same
@@ -550,7 +551,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         qpos[qt] = p0 + ic;
         const uint16_t *row = a.q + ((size_t)head * a.n_q + ic) * kD;
 #pragma unroll
-        for (int step = 0; step < 4; step++) Qf[qt][step] = *reinterpret_cast<const half8 *>(row + 32 * step + 8 * rq);
+        for (int step = 0; step < 4; step++) Qf[qt][step] = __builtin_nontemporal_load(reinterpret_cast<const half8 *>(row + 32 * step + 8 * rq));
     }
 
     float4v O[8][2];
@@ -630,8 +631,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             uint16_t *row = a.out + ((size_t)head * a.n_q + i) * kD;
 #pragma unroll
             for (int ct = 0; ct < 8; ct++)
-                *reinterpret_cast<uint2 *>(row + 16 * ct + 4 * rq) =
-                    make_uint2(pack2(O[ct][qt][0] * inv, O[ct][qt][1] * inv), pack2(O[ct][qt][2] * inv, O[ct][qt][3] * inv));
+                __builtin_nontemporal_store(u32x2{pack2(O[ct][qt][0] * inv, O[ct][qt][1] * inv), pack2(O[ct][qt][2] * inv, O[ct][qt][3] * inv)},
+                                            reinterpret_cast<u32x2 *>(row + 16 * ct + 4 * rq));
         }
     }
 }

@@ -33,6 +33,7 @@ __device__ __forceinline__ const uint16_t *token_row(const uint16_t *in, const u
 }
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // element-wise minimum / maximum of two fp16 pairs (exact; the statistics need no widening).  Written as
 // single instructions: the generic vector builtins add a quieting pass over every loaded operand.
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
         const uint16_t *row0 = in + ((size_t)bh * a.n_in + (blk * kG - a.t_old) + (values ? 8 * r : r)) * kD + 8 * c16;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            const uint4 w = *reinterpret_cast<const uint4 *>(row0 + (values ? i : 4 * i) * kD);
+            const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row0 + (values ? i : 4 * i) * kD));
             x[i][0] = w.x; x[i][1] = w.y; x[i][2] = w.z; x[i][3] = w.w;
         }
     } else {
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             uint8_t *dst = a.lv.kcode + blk_index * block_code_bytes(KB);
 #pragma unroll
             for (int c = 0; c < KB / 2; c++)
-                *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
+                __builtin_nontemporal_store(u32x4{dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]}, reinterpret_cast<u32x4 *>(dst + c * 1024 + lane * 16));
         }
     } else {
         // ================================================================= values
@@ -433,7 +434,7 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             uint8_t *dst = a.lv.vcode + blk_index * block_code_bytes(VB);
 #pragma unroll
             for (int c = 0; c < VB / 2; c++)
-                *reinterpret_cast<uint4 *>(dst + c * 1024 + lane * 16) = make_uint4(dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]);
+                __builtin_nontemporal_store(u32x4{dw[4 * c], dw[4 * c + 1], dw[4 * c + 2], dw[4 * c + 3]}, reinterpret_cast<u32x4 *>(dst + c * 1024 + lane * 16));
         }
     }
 }
