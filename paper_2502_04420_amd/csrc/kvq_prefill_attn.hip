@@ -35,9 +35,10 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;                // waves of an attention work-group (32 queries each)
+constexpr int kWaves = 8;                // waves of an attention work-group
 constexpr int kStagers = 4;              // waves that turn a unit into tiles (256 threads: the thread -> code maps below)
-constexpr int kQW = 32;                 // queries per wave
+constexpr int kQT = 2;                   // tiles of 16 queries per wave
+constexpr int kQW = 16 * kQT;            // queries per wave
 constexpr int kQB = kQW * kWaves;       // queries per work-group
 constexpr int kKStride = kD + 16;       // halves per K^ row: 288 bytes.  Measured with a probe kernel: the 16-byte operand reads of a wave
                                         // (16 rows x 4 pieces) take 3.9 LDS cycles at this stride, like a linear read; 7.8 + 3.9 conflict cycles at 272
@@ -330,16 +331,18 @@ __device__ __forceinline__ float xor_lanes(float x, int mask) { return __shfl_xo
 // S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt.  KLO: quantized keys, whose fp16 rounding
 // remainders are multiplied as well.
 template <bool KLO>
-__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[2][4], float4v (&S)[2][2], int n, int rq)
+__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq)
 {
 #pragma unroll
-    for (int tt = 0; tt < 2; tt++) { S[tt][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; S[tt][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
+    for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+        for (int qt = 0; qt < kQT; qt++) S[tt][qt] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int step = 0; step < 4; step++) {
         const half8 A0 = *reinterpret_cast<const half8 *>(&X.K[n][32 * step + 8 * rq]);
         const half8 A1 = *reinterpret_cast<const half8 *>(&X.K[16 + n][32 * step + 8 * rq]);
 #pragma unroll
-        for (int qt = 0; qt < 2; qt++) {
+        for (int qt = 0; qt < kQT; qt++) {
             S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
             S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
         }
@@ -350,7 +353,7 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[2][
             const half8 A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
             const half8 A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
 #pragma unroll
-            for (int qt = 0; qt < 2; qt++) {
+            for (int qt = 0; qt < kQT; qt++) {
                 S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
                 S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
             }
@@ -362,11 +365,11 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[2][
 // running maximum m (raw scores), partial sums lsum, and the factors alpha by which the accumulators shrink.
 // MASK: the unit reaches beyond some query's position.
 template <bool MASK>
-__device__ __forceinline__ void softmax_unit(const float4v (&S)[2][2], float c, int u, const int (&qpos)[2], float (&m)[2],
-                                             float (&lsum)[2], half8 (&P)[2], float (&alpha)[2], int rq)
+__device__ __forceinline__ void softmax_unit(const float4v (&S)[2][kQT], float c, int u, const int (&qpos)[kQT], float (&m)[kQT],
+                                             float (&lsum)[kQT], half8 (&P)[kQT], float (&alpha)[kQT], int rq)
 {
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3];      // raw scores; the running maximum is kept raw too
@@ -398,11 +401,11 @@ __device__ __forceinline__ void softmax_unit(const float4v (&S)[2][2], float c, 
 constexpr float kCalm = 8.0f;
 
 // true if some score of the unit (no mask) exceeds its query's reference by more than kCalm, in any lane of the wave
-__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][2], float c, const float (&m)[2])
+__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float c, const float (&m)[kQT])
 {
     bool over = false;
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         const float4v a = S[0][qt], b = S[1][qt];
         const float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
         over |= (mx - m[qt]) * c > kCalm;                  // m = -inf at the start: always over
@@ -411,10 +414,10 @@ __device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][2], float c, 
 }
 
 // softmax weights of a unit against the unchanged reference (no mask)
-__device__ __forceinline__ void softmax_calm(const float4v (&S)[2][2], float c, const float (&m)[2], float (&lsum)[2], half8 (&P)[2])
+__device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c, const float (&m)[kQT], float (&lsum)[kQT], half8 (&P)[kQT])
 {
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         const float shift = -m[qt] * c;
         float x[8], ps = 0.0f;
 #pragma unroll
@@ -426,24 +429,24 @@ __device__ __forceinline__ void softmax_calm(const float4v (&S)[2][2], float c, 
 }
 
 // O^T += V^T P^T
-__device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[2], float4v (&O)[8][2], int n, int rq)
+__device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[kQT], float4v (&O)[8][kQT], int n, int rq)
 {
 #pragma unroll
     for (int ct = 0; ct < 8; ct++) {
         const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
         const half4 v1 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][16 + 4 * rq]);
         const half8 A = half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-        O[ct][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[0], O[ct][0], 0, 0, 0);
-        O[ct][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[1], O[ct][1], 0, 0, 0);
+#pragma unroll
+        for (int qt = 0; qt < kQT; qt++) O[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[qt], O[ct][qt], 0, 0, 0);
     }
 }
 
 // O^T = alpha O^T + V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
 // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.  The accumulators are rescaled only when some maximum moved.
-__device__ __forceinline__ void output_unit(const Tiles &X, const half8 (&P)[2], const float (&alpha)[2], float4v (&O)[8][2], int n, int rq)
+__device__ __forceinline__ void output_unit(const Tiles &X, const half8 (&P)[kQT], const float (&alpha)[kQT], float4v (&O)[8][kQT], int n, int rq)
 {
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         if (__any(alpha[qt] != 1.0f)) {
 #pragma unroll
             for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha[qt];
@@ -467,41 +470,49 @@ __global__ __launch_bounds__(64 * kStagers) void prefill_dequantize(PrefillArgs 
     store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6]);
 }
 
-// 16-byte pieces of a unit in the scratch area, and how many each of the 512 threads copies
-constexpr int kUnitPieces = (int)(sizeof(Tiles) / 16);
-constexpr int kCopies = (kUnitPieces + 64 * kWaves - 1) / (64 * kWaves);
-static_assert(sizeof(Tiles) % 16 == 0, "a unit is copied in 16-byte pieces");
+// A unit goes from the scratch area into an LDS buffer without passing through registers: a wave issues
+// global-to-LDS loads of 1 KiB each (64 lanes x 16 bytes, which land at consecutive LDS addresses from the base
+// that M0 holds).  The three tiles of a unit are 9 KiB each, so a piece never straddles two of them.
+constexpr int kTileKiB = 9;
+static_assert(sizeof(_Float16) * 32 * kKStride == kTileKiB * 1024 && sizeof(_Float16) * kD * kVStride == kTileKiB * 1024 &&
+              sizeof(Tiles) == 3 * kTileKiB * 1024, "tiles of a unit are whole KiB");
 
-struct Copy { u32x4 r[kCopies]; };
-
-// Loads are never skipped (a piece past the end reads the last one again): no branch between a load and its use.
-__device__ __forceinline__ void load_copy(const uint8_t *unit, int tid, Copy &c)
+__device__ __forceinline__ void fetch_piece(const uint8_t *src_of_lane, uint32_t lds_base)
 {
+    // The compiler does not see this load: the waits for it are written out below (wait_fetches).  Loads it does not
+    // know of can only make its own waits longer, never too short.  M0 is a register the compiler reserves and sets
+    // itself right before an instruction of its own that reads it; nothing else in these kernels does.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src_of_lane) : "memory");
+}
+
+// Wave `wave` fetches the pieces wave, wave + 8, ... of a unit; without low parts of the keys that tile is left out.
+template <bool KLO>
+__device__ __forceinline__ void fetch_unit(const uint8_t *unit, Tiles &L, int wave, int lane)
+{
+    constexpr int pieces = (KLO ? 3 : 2) * kTileKiB;
+    const uint32_t lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)reinterpret_cast<uint8_t *>(&L);
 #pragma unroll
-    for (int i = 0; i < kCopies; i++) {
-        const int p = tid + 64 * kWaves * i;
-        c.r[i] = ld16(unit + 16 * (p < kUnitPieces ? p : kUnitPieces - 1));
+    for (int i = 0; i < (pieces + kWaves - 1) / kWaves; i++) {
+        const int p = wave + kWaves * i;                          // the same for all lanes of the wave
+        if (p < pieces) {
+            const int off = 1024 * (KLO || p < kTileKiB ? p : p + kTileKiB);
+            fetch_piece(unit + off + 16 * lane, lds + off);
+        }
     }
 }
 
-__device__ __forceinline__ void store_copy(Tiles &L, int tid, const Copy &c)
-{
-    uint8_t *dst = reinterpret_cast<uint8_t *>(&L);
-#pragma unroll
-    for (int i = 0; i < kCopies; i++) {
-        const int p = tid + 64 * kWaves * i;
-        if (p < kUnitPieces) *reinterpret_cast<u32x4 *>(dst + 16 * p) = c.r[i];
-    }
-}
+// Returns once all fetches of this wave have landed in LDS.
+__device__ __forceinline__ void wait_fetches() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- pass 2: the attention itself.  One work-group per 256 consecutive queries of one query head; every wave attends
-// 32 queries and copies its share of each unit from the scratch area into LDS.  KLO: the keys are quantized (they come
+// 32 queries and fetches its share of each unit from the scratch area into LDS.  KLO: the keys are quantized (they come
 // as two fp16 numbers).
 //
-// Three LDS buffers: while unit u is being used, unit u + 1 is already there and unit u + 2 is being written.  That
-// lets a wave issue the score products of unit u + 1 in the same stretch of code as the softmax of unit u (matrix
-// and vector instructions that do not depend on each other), instead of waiting for each product's result in turn.
-constexpr int kBuffers = 3;
+// Five LDS buffers and two units per trip: while units u and u + 1 are being used, unit u + 2 is already there and units
+// u + 3 and u + 4 are on their way; one barrier per trip.  With the next unit present, a wave issues the score products
+// of unit u + 1 in the same stretch of code as the softmax of unit u (matrix and vector instructions that do not depend
+// on each other), instead of waiting for each product's result in turn.
+constexpr int kBuffers = 5;
 
 template <bool KLO>
 __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
@@ -543,10 +554,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     Tiles *L = reinterpret_cast<Tiles *>(lds_raw);
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
-    int qpos[2];
-    half8 Qf[2][4];
+    int qpos[kQT];
+    half8 Qf[kQT][4];
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         const int i = iw + 16 * qt + n, ic = i < a.n_q ? i : a.n_q - 1;
         qpos[qt] = p0 + ic;
         const uint16_t *row = a.q + ((size_t)head * a.n_q + ic) * kD;
@@ -554,55 +565,70 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         for (int step = 0; step < 4; step++) Qf[qt][step] = __builtin_nontemporal_load(reinterpret_cast<const half8 *>(row + 32 * step + 8 * rq));
     }
 
-    float4v O[8][2];
+    float4v O[8][kQT];
+    float m[kQT], lsum[kQT];
 #pragma unroll
-    for (int ct = 0; ct < 8; ct++) { O[ct][0] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; O[ct][1] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; }
-    float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};
+    for (int qt = 0; qt < kQT; qt++) {
+        m[qt] = -INFINITY;
+        lsum[qt] = 0.0f;
+#pragma unroll
+        for (int ct = 0; ct < 8; ct++) O[ct][qt] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+    }
 
-    // ---- packed units [0, nb).  Unit u lives in buffer u % 3.  Per trip: the wave uses unit u (and takes the scores of
-    // unit u + 1 ahead), writes unit u + 2 from its registers and issues the loads of unit u + 3, which stay in flight
-    // across the barrier.  Loads and LDS writes are never skipped (past the end the last unit is staged again, into a
-    // buffer nobody reads any more): no branch lies between the issue of a load and its use.
+    // ---- packed units [0, nb).  Unit u lives in buffer u % 5.  Per trip: the wave issues its fetches of units u + 3 and
+    // u + 4 (into the buffers of units u - 2 and u - 1, which everybody left at the last barrier), uses units u and u + 1
+    // (taking the scores of the following unit ahead each time), then waits until its fetches have landed, and the
+    // barrier makes everybody's visible.  Past the end the last unit is fetched again, into a buffer nobody reads.
     const int nb = a.n_blocks < units ? a.n_blocks : units;
     if (nb > 0) {
         const uint8_t *mine = a.scratch + (size_t)local * a.n_blocks * sizeof(Tiles);
         const int last = nb - 1;
         auto unit_at = [&](int u) { return mine + (size_t)(u < last ? u : last) * sizeof(Tiles); };
-        Copy cp;
-        load_copy(unit_at(0), tid, cp);
-        store_copy(L[0], tid, cp);
-        load_copy(unit_at(1), tid, cp);
-        store_copy(L[1], tid, cp);
-        load_copy(unit_at(2), tid, cp);
+        fetch_unit<KLO>(unit_at(0), L[0], wave, lane);
+        fetch_unit<KLO>(unit_at(1), L[1], wave, lane);
+        fetch_unit<KLO>(unit_at(2), L[2], wave, lane);
+        // The queries are first used under a condition; without this the compiler would keep their loads on its list
+        // of pending ones inside the loop and wait there for everything in flight, the fetches just issued included.
+#pragma unroll
+        for (int qt = 0; qt < kQT; qt++)
+#pragma unroll
+            for (int step = 0; step < 4; step++) asm volatile("" ::"v"(Qf[qt][step]));
+        wait_fetches();                                         // units 0, 1 and 2 are there
         __syncthreads();
-        float4v S[2][2], Sn[2][2];
+        float4v S[2][kQT], Sn[2][kQT];
         if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq);
-        int b0 = 0;                                              // buffer of unit u
-        for (int u = 0; u < nb; u++) {
-            const int b1 = b0 + 1 < kBuffers ? b0 + 1 : 0, b2 = b1 + 1 < kBuffers ? b1 + 1 : 0;
+        auto step = [&](int u, const Tiles &X0, const Tiles &X1) {
             if (u <= wlast) {
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
-                half8 P[2];
+                half8 P[kQT];
                 if (ahead && u < open_units && !unit_exceeds(S, c, m)) {
-                    // the common trip, one stretch of straight-line code: score products of the next unit, weights of
-                    // this one against the unchanged reference, output products of this one
-                    score_unit<KLO>(L[b1], Qf, Sn, n, rq);
+                    score_unit<KLO>(X1, Qf, Sn, n, rq);
                     softmax_calm(S, c, m, lsum, P);
-                    output_add(L[b0], P, O, n, rq);
+                    output_add(X0, P, O, n, rq);
                 } else {
-                    float alpha[2];
-                    if (ahead) score_unit<KLO>(L[b1], Qf, Sn, n, rq);
+                    float alpha[kQT];
+                    if (ahead) score_unit<KLO>(X1, Qf, Sn, n, rq);
                     if (u < open_units) softmax_unit<false>(S, c, u, qpos, m, lsum, P, alpha, rq);
                     else softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
-                    output_unit(L[b0], P, alpha, O, n, rq);
+                    output_unit(X0, P, alpha, O, n, rq);
                 }
 #pragma unroll
-                for (int tt = 0; tt < 2; tt++) { S[tt][0] = Sn[tt][0]; S[tt][1] = Sn[tt][1]; }
+                for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+                    for (int qt = 0; qt < kQT; qt++) S[tt][qt] = Sn[tt][qt];
             }
-            store_copy(L[b2], tid, cp);                          // unit u + 2
-            load_copy(unit_at(u + 3), tid, cp);
+        };
+        auto after = [](int x) { return x + 1 < kBuffers ? x + 1 : 0; };
+        int b0 = 0;                                              // buffer of unit u
+        for (int u = 0; u < nb; u += 2) {
+            const int b1 = after(b0), b2 = after(b1), b3 = after(b2), b4 = after(b3);
+            fetch_unit<KLO>(unit_at(u + 3), L[b3], wave, lane);  // buffers of units u - 2 and u - 1: all are done with them
+            fetch_unit<KLO>(unit_at(u + 4), L[b4], wave, lane);
+            step(u, L[b0], L[b1]);
+            if (u + 1 < nb) step(u + 1, L[b1], L[b2]);
+            wait_fetches();                                     // units u + 3 and u + 4 are there
             __syncthreads();
-            b0 = b1;
+            b0 = b2;
         }
     }
     // ---- chunks of the fp16 window, staged by the first four waves straight from the ring
@@ -610,9 +636,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         if (wave < kStagers) stage_window(a, bh, u, T, tid, L[0]);
         __syncthreads();
         if (u <= wlast) {
-            float4v S[2][2];
-            half8 P[2];
-            float alpha[2];
+            float4v S[2][kQT];
+            half8 P[kQT];
+            float alpha[kQT];
             score_unit<false>(L[0], Qf, S, n, rq);
             softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
             output_unit(L[0], P, alpha, O, n, rq);
@@ -621,7 +647,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     }
 
 #pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
+    for (int qt = 0; qt < kQT; qt++) {
         float l = lsum[qt];
         l += xor_lanes(l, 16);
         l += xor_lanes(l, 32);
