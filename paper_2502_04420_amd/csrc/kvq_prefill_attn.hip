@@ -13,9 +13,9 @@
 //      kernel instead repeats this work for every query head of the group and every query tile (256 times per unit at
 //      8192 queries) and made that kernel bound by its vector instructions.
 //   2. prefill_attention: a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two
-//      16-query tiles).  The units are copied from the scratch area (fp16 window chunks: from the ring) into three
-//      LDS tile buffers, so that the score products of the next unit can be issued next to the softmax weights of the
-//      current one.  Scores are computed transposed, S^T = K^ Q^T
+//      16-query tiles).  The units are fetched from the scratch area straight into LDS (fp16 window chunks: from the
+//      ring, through registers), five tile buffers, two units per barrier, so that the score products of the next
+//      unit can be issued next to the softmax weights of the current one.  Scores are computed transposed, S^T = K^ Q^T
 //      (16x16x32 f16 instructions, tokens along the rows): a lane then holds, for its query, the scores of tokens
 //      {4 rq .. 4 rq + 3} and {16 + 4 rq ..}, which is exactly a B operand of O^T += V^T P^T when the A operand (V^T
 //      from LDS) lists its tokens in the same order.  The softmax weights therefore go from the accumulator of one
@@ -456,7 +456,7 @@ __device__ __forceinline__ void output_unit(const Tiles &X, const half8 (&P)[kQT
 }
 
 // ---- pass 1: every packed unit of the (batch, kv head) caches [bh0, bh0 + n_bh) is dequantized once into the scratch
-// area, in the very layout the attention kernel keeps a unit in LDS (struct Tiles), so that pass 2 stages plain copies.
+// area, in the very layout the attention kernel keeps a unit in LDS (struct Tiles), so that pass 2 fetches plain copies.
 // KQ / VQ: the layer's keys / values are quantized (else fp16 rows in the code area).
 template <bool KQ, bool VQ>
 __global__ __launch_bounds__(64 * kStagers) void prefill_dequantize(PrefillArgs a)
