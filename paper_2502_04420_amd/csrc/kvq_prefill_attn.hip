@@ -597,25 +597,24 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         __syncthreads();
         float4v S[2][kQT], Sn[2][kQT];
         if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq);
-        auto step = [&](int u, const Tiles &X0, const Tiles &X1) {
+        // one unit: its scores come in Sin, those of the next unit leave in Sout (the two arrays swap roles from unit to unit)
+        auto step = [&](int u, const Tiles &X0, const Tiles &X1, const float4v (&Sin)[2][kQT], float4v (&Sout)[2][kQT]) {
             if (u <= wlast) {
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
                 half8 P[kQT];
-                if (ahead && u < open_units && !unit_exceeds(S, c, m)) {
-                    score_unit<KLO>(X1, Qf, Sn, n, rq);
-                    softmax_calm(S, c, m, lsum, P);
+                if (ahead && u < open_units && !unit_exceeds(Sin, c, m)) {
+                    // the common case, one stretch of straight-line code: score products of the next unit, weights of
+                    // this one against the unchanged reference, output products of this one
+                    score_unit<KLO>(X1, Qf, Sout, n, rq);
+                    softmax_calm(Sin, c, m, lsum, P);
                     output_add(X0, P, O, n, rq);
                 } else {
                     float alpha[kQT];
-                    if (ahead) score_unit<KLO>(X1, Qf, Sn, n, rq);
-                    if (u < open_units) softmax_unit<false>(S, c, u, qpos, m, lsum, P, alpha, rq);
-                    else softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
+                    if (ahead) score_unit<KLO>(X1, Qf, Sout, n, rq);
+                    if (u < open_units) softmax_unit<false>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
+                    else softmax_unit<true>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
                     output_unit(X0, P, alpha, O, n, rq);
                 }
-#pragma unroll
-                for (int tt = 0; tt < 2; tt++)
-#pragma unroll
-                    for (int qt = 0; qt < kQT; qt++) S[tt][qt] = Sn[tt][qt];
             }
         };
         auto after = [](int x) { return x + 1 < kBuffers ? x + 1 : 0; };
@@ -624,8 +623,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             const int b1 = after(b0), b2 = after(b1), b3 = after(b2), b4 = after(b3);
             fetch_unit<KLO>(unit_at(u + 3), L[b3], wave, lane);  // buffers of units u - 2 and u - 1: all are done with them
             fetch_unit<KLO>(unit_at(u + 4), L[b4], wave, lane);
-            step(u, L[b0], L[b1]);
-            if (u + 1 < nb) step(u + 1, L[b1], L[b2]);
+            step(u, L[b0], L[b1], S, Sn);
+            if (u + 1 < nb) step(u + 1, L[b1], L[b2], Sn, S);
             wait_fetches();                                     // units u + 3 and u + 4 are there
             __syncthreads();
             b0 = b2;
