@@ -99,6 +99,19 @@ def test_configure_and_call_errors_without_gpu(lib):
     assert lib.kvq_last_error() is not None
 
 
+def test_library_load_brings_torch_first():
+    """The library must bind to the HIP runtime that torch ships (the one that owns torch's streams and allocations):
+    loading it in a fresh interpreter, before anything imported torch, has to import torch on the way."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r); import paper_2502_04420_amd as p; "
+            "assert 'torch' not in sys.modules; p.load_library(); assert 'torch' in sys.modules" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+
+
 def test_binding_refuses_cpu_device(lib):
     import paper_2502_04420_amd as pkg
 
