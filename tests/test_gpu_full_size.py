@@ -85,3 +85,19 @@ def test_qwen_shape_batch8_context32768_biased_keys(kvq_mod, oracle_mod):
     w = W.config4(8, 32768)
     _check_layer(kvq_mod, oracle_mod, w, 0, 1, [3, 30])                # K8V2 layer
     _check_layer(kvq_mod, oracle_mod, w, 1, 33, [17])                  # K4V2 layer
+
+
+def test_llama_shape_batch16_context4096_uniform_kv8(kvq_mod, oracle_mod):
+    """Uniform K8V8 at batch 16, context 4096 (the benchmark's second configuration), one decode step."""
+    w = W.named("llama8b", "K8V8", 16, 4096)
+    _check_layer(kvq_mod, oracle_mod, w, 0, 1, [5, 90])
+    _check_layer(kvq_mod, oracle_mod, w, 31, 1, [127])
+
+
+def test_llama_shape_batch32_context32768(kvq_mod, oracle_mod):
+    """The 32K point that bench.py also times (batch 32): a K8V8 layer, which the planner serves with half as many
+    groups as the narrow pairs, and a K4V2 layer."""
+    w8 = W.named("llama8b", "K8V8", 32, 32768)
+    _check_layer(kvq_mod, oracle_mod, w8, 3, 1, [200])
+    w = W.config3(32, 32768)
+    _check_layer(kvq_mod, oracle_mod, w, 16, 2, [11])
