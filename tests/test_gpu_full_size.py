@@ -101,3 +101,12 @@ def test_llama_shape_batch32_context32768(kvq_mod, oracle_mod):
     _check_layer(kvq_mod, oracle_mod, w8, 3, 1, [200])
     w = W.config3(32, 32768)
     _check_layer(kvq_mod, oracle_mod, w, 16, 2, [11])
+
+
+def test_llama_shape_batch64_context32768_one_bulk_append(kvq_mod, oracle_mod):
+    """The largest point of the sweep, the whole prompt in one append: 2^31 elements per input tensor, so every index
+    that is not computed in 64 bits would show."""
+    w = W.config3(64, 32768)
+    _check_layer(kvq_mod, oracle_mod, w, 16, 2, [511, 256])            # K4V2 layer: last and a middle (batch, kv head)
+    w8 = W.named("llama8b", "K8V8", 64, 32768)
+    _check_layer(kvq_mod, oracle_mod, w8, 3, 1, [300])
