@@ -170,6 +170,35 @@ def test_llama_shape_full_prompt_sampled_rows(kvq_mod, oracle_mod):
     assert worst > 0
 
 
+def test_llama_heads_32k_prompt_sampled_rows(kvq_mod, oracle_mod):
+    """A 32768-token prompt (Llama-3.1-8B heads, batch 3 = 24 caches, i.e. two passes; K8V4 layer): 1023 packed units per
+    cache and 128 query tiles per head.  Sampled (batch, kv head) pairs at sampled positions against the oracle."""
+    w = W.Workload("prefill32k", 1, 3, 32, 8, 128, 32768, [8], [4], seed=911, outlier_channels=3)
+    T, gq = w.context, w.n_q_heads // w.n_kv_heads
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, T + 64, w.kbits, w.vbits)
+    for t0 in range(0, T, 8192):
+        K, V = W.kv_tokens(w, 0, t0, t0 + 8192, device="cuda:0")
+        g.quantize_append(0, K, V)
+    del K, V
+    q = torch.empty(w.batch, w.n_q_heads, T, w.head_dim, dtype=torch.float16, device="cuda:0")
+    for h0 in range(0, w.n_q_heads, gq):
+        q[:, h0:h0 + gq] = W.prefill_queries(w, 0, T, device="cuda:0", heads=(h0, gq))
+    out = g.prefill_attention(0, q)
+    torch.cuda.synchronize()
+    pos = [0, 31, 32, 255, 256, 8191, 8192, 16383, 16384, 20000, 32511, 32512, 32735, 32736, 32766, 32767]
+    for bh in (0, 13, 23):                          # first pass, first pass, second pass
+        b, h = divmod(bh, w.n_kv_heads)
+        Kc, Vc = W.kv_tokens(w, 0, 0, T, bh=torch.tensor([bh]))
+        o = oracle_mod.OracleCache(1, 1, gq, 1, w.head_dim, w.kbits, w.vbits)
+        o.quantize_append(0, Kc.numpy()[None], Vc.numpy()[None])
+        assert o.tokens(0) == g.layer_tokens(0)
+        qs = q[b, h * gq:(h + 1) * gq][:, pos].cpu().numpy()[None]
+        o16, o64 = o.prefill_attention_at(0, np.ascontiguousarray(qs), pos)
+        assert_prefill_close(out[b, h * gq:(h + 1) * gq][:, pos][None], o64, "bh %d" % bh)
+        o.close()
+    g.close()
+
+
 @pytest.mark.parametrize("batch,hkv", [(5, 4), (3, 8), (17, 1)])
 def test_more_caches_than_one_pass_holds(kvq_mod, oracle_mod, batch, hkv):
     """The call takes 16 (batch, kv head) caches per pass: 20 = 16 + 4, 24 = 16 + 8 and 17 = 16 + 1 exercise the second
