@@ -154,9 +154,10 @@ int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_devic
  * Query head h attends kv head h / (n_q_heads / n_kv_heads).  The dequantized operands and the
  * softmax weights are rounded to fp16 for the matrix cores (keys as the sum of two fp16
  * numbers); accumulation is fp32.  The cache is not modified.  With n_q = 1 the result is that
- * of kvq_decode_attention up to rounding.  The call enqueues two kernels per 16 (batch, kv head)
- * caches: one dequantizes their packed tokens once into a scratch area inside the workspace
- * (16 * floor(max_tokens / 32) * 27 KiB, counted by kvq_workspace_bytes), one attends.  With
+ * of kvq_decode_attention up to rounding.  The call enqueues two kernels per pass over a group
+ * of (batch, kv head) caches: one dequantizes their packed tokens once into a scratch area
+ * inside the workspace (16 * floor(max_tokens / 32) * 27 KiB, counted by kvq_workspace_bytes:
+ * 16 caches per pass at full length, more when the layer holds fewer tokens), one attends.  With
  * kernel events set (kvq_set_kernel_events) they receive the start of the first and the end of
  * the last of these kernels.
  */

@@ -336,8 +336,18 @@ int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
     a.scratch = c->ws + c->plan.prefill_scratch;
     const bool timed = c->ev_begin && c->ev_end;
-    const int BH = a.B * a.Hkv, chunk = c->plan.prefill_chunk;
-    // the caches are taken a chunk at a time: dequantize the chunk's packed units into the scratch area, attend
+    const int BH = a.B * a.Hkv;
+    // The caches are taken a chunk at a time: dequantize the chunk's packed units into the scratch area, attend.
+    // The scratch area holds prefill_chunk caches of NB units; a shorter prompt leaves room for more caches per
+    // pass (kept a multiple of the 8 XCDs, which the attention kernel's placement wants): fewer, larger launches.
+    int chunk = c->plan.prefill_chunk;
+    if (a.n_blocks > 0 && chunk < BH) {
+        const long long fit = (long long)c->plan.prefill_chunk * c->plan.NB / a.n_blocks;
+        if (fit >= BH) chunk = BH;
+        else if (fit / 8 * 8 > chunk) chunk = (int)(fit / 8 * 8);
+    } else if (a.n_blocks == 0) {
+        chunk = BH;                                             // window only: nothing goes through the scratch area
+    }
     for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
         a.bh0 = bh0;
         a.n_bh = BH - bh0 < chunk ? BH - bh0 : chunk;

@@ -199,11 +199,13 @@ def test_llama_heads_32k_prompt_sampled_rows(kvq_mod, oracle_mod):
     g.close()
 
 
-@pytest.mark.parametrize("batch,hkv", [(5, 4), (3, 8), (17, 1)])
-def test_more_caches_than_one_pass_holds(kvq_mod, oracle_mod, batch, hkv):
-    """The call takes 16 (batch, kv head) caches per pass: 20 = 16 + 4, 24 = 16 + 8 and 17 = 16 + 1 exercise the second
-    pass with a count that is and is not a multiple of the 8 XCDs; queries are a proper tail of the prompt."""
+@pytest.mark.parametrize("batch,hkv,room", [(5, 4, 1), (3, 8, 1), (17, 1, 1), (7, 8, 3), (5, 8, 4)])
+def test_more_caches_than_one_pass_holds(kvq_mod, oracle_mod, batch, hkv, room):
+    """The scratch area holds 16 caches of max_tokens each; a pass takes as many caches as fit (a multiple of 8 when
+    not all).  Prompt of 293 tokens (8 packed units): with max_tokens = 293 (9 units of room per cache) 18 caches fit:
+    20 = 16 + 4 and 24 = 16 + 8 caches take two passes, 17 take one whose count is no multiple of the 8 XCDs; with
+    three times the room 54 fit: 56 = 48 + 8; with four times 72 fit: 40 in one pass.  Queries are a proper tail."""
     w = W.Workload("chunks", 1, batch, 2 * hkv, hkv, 128, 32 * 9 + 5, [4], [2], seed=700 + batch, outlier_channels=2)
-    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, 270)
+    out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, 270, max_tokens=room * w.context)
     assert_prefill_close(out, o64, "B%d Hkv%d" % (batch, hkv))
     g.close()
