@@ -400,15 +400,19 @@ __device__ __forceinline__ void softmax_unit(const float4v (&S)[2][kQT], float c
 // unchanged: no maximum across lanes, no rescaling, weights <= 2^kCalm (fp16 holds them, the accumulators are fp32).
 constexpr float kCalm = 8.0f;
 
-// true if some score of the unit (no mask) exceeds its query's reference by more than kCalm, in any lane of the wave
-__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float c, const float (&m)[kQT])
+// true if some score of the unit (no mask) exceeds its query's reference by more than kCalm (in the exponent's units),
+// in any lane of the wave.  calm_over_c = kCalm / c: the comparison is made on the raw scores.
+__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float calm_over_c, const float (&m)[kQT])
 {
     bool over = false;
 #pragma unroll
     for (int qt = 0; qt < kQT; qt++) {
         const float4v a = S[0][qt], b = S[1][qt];
-        const float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
-        over |= (mx - m[qt]) * c > kCalm;                  // m = -inf at the start: always over
+        float mx = fmaxf(fmaxf(a[0], a[1]), a[2]);          // chains of three-operand maxima
+        mx = fmaxf(fmaxf(mx, a[3]), b[0]);
+        mx = fmaxf(fmaxf(mx, b[1]), b[2]);
+        mx = fmaxf(mx, b[3]);
+        over |= mx > m[qt] + calm_over_c;                   // m = -inf at the start: always over
     }
     return __any(over);
 }
@@ -549,6 +553,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     const int wmin = p0 + iw;                                    // position of the wave's first query
     const int open_units = iw < a.n_q ? (wmin + 1) / 32 : 0;     // units [0, open_units) lie before it: no mask needed
     const float c = a.scale_log2e;
+    const float calm_over_c = kCalm / c;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     Tiles *L = reinterpret_cast<Tiles *>(lds_raw);
@@ -602,7 +607,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             if (u <= wlast) {
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
                 half8 P[kQT];
-                if (ahead && u < open_units && !unit_exceeds(Sin, c, m)) {
+                if (ahead && u < open_units && !unit_exceeds(Sin, calm_over_c, m)) {
                     // the common case, one stretch of straight-line code: score products of the next unit, weights of
                     // this one against the unchanged reference, output products of this one
                     score_unit<KLO>(X1, Qf, Sout, n, rq);
