@@ -361,6 +361,17 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
     }
 }
 
+// acc + the sum of the eight weights as they enter the output product (rounded to fp16), in fp32: four two-element dot
+// products.  The denominator then matches the numerators exactly.
+__device__ __forceinline__ float add_weights(float acc, half8 P)
+{
+    typedef _Float16 half2 __attribute__((ext_vector_type(2)));
+    const half2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+    for (int k = 0; k < 4; k++) acc = __builtin_amdgcn_fdot2(half2{P[2 * k], P[2 * k + 1]}, ones, acc, false);
+    return acc;
+}
+
 // Online softmax in base 2 of the unit's scores: weights P (fp16, already in the operand order of the output product),
 // running maximum m (raw scores), partial sums lsum, and the factors alpha by which the accumulators shrink.
 // MASK: the unit reaches beyond some query's position.
@@ -386,12 +397,11 @@ __device__ __forceinline__ void softmax_unit(const float4v (&S)[2][kQT], float c
         alpha[qt] = __builtin_amdgcn_exp2f((m[qt] - mn) * c);
         m[qt] = mn;
         const float shift = -mn * c;                                   // the softmax constant rides on the exponent's fma
-        float ps = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], c, shift)); ps += x[e]; }
-        lsum[qt] = lsum[qt] * alpha[qt] + ps;
+        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], c, shift));
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
                       (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
+        lsum[qt] = add_weights(lsum[qt] * alpha[qt], P[qt]);
     }
 }
 
@@ -423,12 +433,12 @@ __device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c
 #pragma unroll
     for (int qt = 0; qt < kQT; qt++) {
         const float shift = -m[qt] * c;
-        float x[8], ps = 0.0f;
+        float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) { x[e] = __builtin_amdgcn_exp2f(fmaf(S[e >> 2][qt][e & 3], c, shift)); ps += x[e]; }
-        lsum[qt] += ps;
+        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(fmaf(S[e >> 2][qt][e & 3], c, shift));
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
                       (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
+        lsum[qt] = add_weights(lsum[qt], P[qt]);
     }
 }
 
