@@ -442,7 +442,8 @@ __device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c
     }
 }
 
-// O^T += V^T P^T
+// O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
+// {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.
 __device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[kQT], float4v (&O)[8][kQT], int n, int rq)
 {
 #pragma unroll
@@ -455,18 +456,13 @@ __device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[kQT]
     }
 }
 
-// O^T = alpha O^T + V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
-// {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.  The accumulators are rescaled only when some maximum moved.
-__device__ __forceinline__ void output_unit(const Tiles &X, const half8 (&P)[kQT], const float (&alpha)[kQT], float4v (&O)[8][kQT], int n, int rq)
+// O^T *= alpha per query, before the unit's product is added (on the exact path only, which is the rare one).
+__device__ __forceinline__ void output_rescale(const float (&alpha)[kQT], float4v (&O)[8][kQT])
 {
 #pragma unroll
-    for (int qt = 0; qt < kQT; qt++) {
-        if (__any(alpha[qt] != 1.0f)) {
+    for (int qt = 0; qt < kQT; qt++)
 #pragma unroll
-            for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha[qt];
-        }
-    }
-    output_add(X, P, O, n, rq);
+        for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha[qt];
 }
 
 // ---- pass 1: every packed unit of the (batch, kv head) caches [bh0, bh0 + n_bh) is dequantized once into the scratch
@@ -618,18 +614,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
                 half8 P[kQT];
                 if (ahead && u < open_units && !unit_exceeds(Sin, calm_over_c, m)) {
-                    // the common case, one stretch of straight-line code: score products of the next unit, weights of
-                    // this one against the unchanged reference, output products of this one
+                    // the common case, one stretch of straight-line code: score products of the next unit next to the
+                    // weights of this one against the unchanged reference
                     score_unit<KLO>(X1, Qf, Sout, n, rq);
                     softmax_calm(Sin, c, m, lsum, P);
-                    output_add(X0, P, O, n, rq);
                 } else {
                     float alpha[kQT];
                     if (ahead) score_unit<KLO>(X1, Qf, Sout, n, rq);
                     if (u < open_units) softmax_unit<false>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
                     else softmax_unit<true>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
-                    output_unit(X0, P, alpha, O, n, rq);
+                    output_rescale(alpha, O);
                 }
+                // one place adds to the accumulators on every path: they stay in the same registers (with a product
+                // on each path the compiler copied all 64 of them after every unit)
+                output_add(X0, P, O, n, rq);
             }
         };
         auto after = [](int x) { return x + 1 < kBuffers ? x + 1 : 0; };
@@ -655,7 +653,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             float alpha[kQT];
             score_unit<false>(L[0], Qf, S, n, rq);
             softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
-            output_unit(L[0], P, alpha, O, n, rq);
+            output_rescale(alpha, O);
+            output_add(L[0], P, O, n, rq);
         }
         __syncthreads();
     }
