@@ -146,6 +146,18 @@ __device__ __forceinline__ void store_scale(float *meta, int idx, float s)
     else meta[idx] = s;
 }
 
+// two neighbouring scales (even index first) as one store
+template <bool NARROW>
+__device__ __forceinline__ void store_scale_pair(float *meta, int idx, float s0, float s1)
+{
+    if constexpr (NARROW) {
+        const uint32_t lo = __builtin_bit_cast(uint16_t, (_Float16)s0), hi = __builtin_bit_cast(uint16_t, (_Float16)s1);
+        *reinterpret_cast<uint32_t *>(meta_scales16(meta) + idx) = lo | (hi << 16);
+    } else {
+        *reinterpret_cast<float2 *>(meta + idx) = make_float2(s0, s1);
+    }
+}
+
 __device__ __forceinline__ float recip_or_zero(float s) { return s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f; }
 
 __device__ __forceinline__ void load8(const float *p, float (&v)[8])
@@ -280,16 +292,21 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 // every lane row now holds the statistics of all 8 channels: row r finishes channels 2r and 2r + 1
                 const uint32_t mn2 = r == 0 ? mnp[0] : r == 1 ? mnp[1] : r == 2 ? mnp[2] : mnp[3];
                 const uint32_t mx2 = r == 0 ? mxp[0] : r == 1 ? mxp[1] : r == 2 ? mxp[2] : mxp[3];
+                // the pair goes out as one store per array (scales, zero-points; LDS copies likewise)
+                const int ch = 8 * c16 + 2 * r;
+                float s2[2], r2[2];
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
-                    const int ch = 8 * c16 + 2 * r + h;
-                    const uint32_t mnb = (mn2 >> (16 * h)) & 0xffffu;
-                    const float mn = half_bits_to_float(mnb), mx = half_bits_to_float((mx2 >> (16 * h)) & 0xffffu);
-                    const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
-                    s_max = fmaxf(s_max, s);
-                    sc[ch] = s; zp[ch] = (uint16_t)mnb; rsc[ch] = recip_or_zero(s);
-                    store_scale<NARROW>(meta, ch, s); meta_zeros(meta, NARROW)[ch] = (uint16_t)mnb;
+                    const float mn = half_bits_to_float((mn2 >> (16 * h)) & 0xffffu), mx = half_bits_to_float((mx2 >> (16 * h)) & 0xffffu);
+                    s2[h] = stored_scale<NARROW>(scale_of(mn, mx, KB));
+                    r2[h] = recip_or_zero(s2[h]);
+                    s_max = fmaxf(s_max, s2[h]);
                 }
+                *reinterpret_cast<float2 *>(&sc[ch]) = make_float2(s2[0], s2[1]);
+                *reinterpret_cast<float2 *>(&rsc[ch]) = make_float2(r2[0], r2[1]);
+                *reinterpret_cast<uint32_t *>(&zp[ch]) = mn2;
+                store_scale_pair<NARROW>(meta, ch, s2[0], s2[1]);
+                *reinterpret_cast<uint32_t *>(meta_zeros(meta, NARROW) + ch) = mn2;
             } else {
                 // min / max per token over the lane's 8 channels, then over the 4 lanes c16 = 4*gd .. 4*gd+3 of group gd;
                 // metadata index 32*gd + token, as for values
@@ -381,21 +398,28 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                 mnp[i] = pk_min(mnp[i], from_lane_xor1(mnp[i])); mxp[i] = pk_max(mxp[i], from_lane_xor1(mxp[i]));
                 mnp[i] = pk_min(mnp[i], from_lane_xor2(mnp[i])); mxp[i] = pk_max(mxp[i], from_lane_xor2(mxp[i]));
             }
-            // the 4 lanes of a group hold the same 8 results: lane q = c16 & 3 finishes tokens q and q + 4 of its row
+            // the 4 lanes of a group hold the same 8 results: lane q = c16 & 3 finishes tokens 2q and 2q + 1 of its row,
+            // a pair that goes out as one store per array
             const int q4 = c16 & 3, gd = c16 >> 2;
+            const int t0 = 32 * gd + 8 * r + 2 * q4;
+            float s2[2], r2[2];
+            uint32_t z2 = 0;
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t mnb = q4 == 0 ? mnp[4 * h] : q4 == 1 ? mnp[4 * h + 1] : q4 == 2 ? mnp[4 * h + 2] : mnp[4 * h + 3];
-                const uint32_t mxb = q4 == 0 ? mxp[4 * h] : q4 == 1 ? mxp[4 * h + 1] : q4 == 2 ? mxp[4 * h + 2] : mxp[4 * h + 3];
-                const int t = 8 * r + 4 * h + q4;
+                const uint32_t mnb = q4 == 0 ? mnp[h] : q4 == 1 ? mnp[2 + h] : q4 == 2 ? mnp[4 + h] : mnp[6 + h];
+                const uint32_t mxb = q4 == 0 ? mxp[h] : q4 == 1 ? mxp[2 + h] : q4 == 2 ? mxp[4 + h] : mxp[6 + h];
                 const float mn = fminf(half_bits_to_float(mnb & 0xffffu), half_bits_to_float(mnb >> 16));
                 const float mx = fmaxf(half_bits_to_float(mxb & 0xffffu), half_bits_to_float(mxb >> 16));
-                const float s = stored_scale<NARROW>(scale_of(mn, mx, VB));
-                s_max = fmaxf(s_max, s);
-                const uint16_t zb = float_to_half_bits_exact(mn);
-                sc[32 * gd + t] = s; zp[32 * gd + t] = zb; rsc[32 * gd + t] = recip_or_zero(s);
-                store_scale<NARROW>(meta, 32 * gd + t, s); meta_zeros(meta, NARROW)[32 * gd + t] = zb;
+                s2[h] = stored_scale<NARROW>(scale_of(mn, mx, VB));
+                r2[h] = recip_or_zero(s2[h]);
+                s_max = fmaxf(s_max, s2[h]);
+                z2 |= (uint32_t)float_to_half_bits_exact(mn) << (16 * h);
             }
+            *reinterpret_cast<float2 *>(&sc[t0]) = make_float2(s2[0], s2[1]);
+            *reinterpret_cast<float2 *>(&rsc[t0]) = make_float2(r2[0], r2[1]);
+            *reinterpret_cast<uint32_t *>(&zp[t0]) = z2;
+            store_scale_pair<NARROW>(meta, t0, s2[0], s2[1]);
+            *reinterpret_cast<uint32_t *>(meta_zeros(meta, NARROW) + t0) = z2;
             // 8 x 8 transpose in registers: channel 8*c16 + e gets its 8 tokens as one 16-byte chunk
             const int krow = (c16 & 7) | (((c16 ^ (c16 >> 3)) & 1) << 3);      // value_row(8*c16 + e) = (c16 >> 1) << 4 | (krow ^ e)
 #pragma unroll
