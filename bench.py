@@ -407,8 +407,12 @@ def main():
         "achieved": pk["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": pk["kernel_gbps"] / HBM_PEAK_GBPS,
         "avg_launch_ms": pk["kernel_ms"], "bytes_per_launch": pk["bytes"], "launches_timed": pk["launches"],
         "timed": "inside the timed region, layer %d of every step, between HIP events stamped by the kernel's own dispatch" % pk["probed_layer"],
-        "traffic": read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else "")),
     }
+    # HBM bytes per launch measured with the counters (fetch + write), or null when this configuration was not profiled
+    detail = read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else ""))
+    roofline["traffic"] = detail["total_bytes"] if detail else None
+    if detail:
+        roofline["traffic_detail"] = detail
     from paper_2502_04420_amd import equivalent_precision
 
     eq_bits = equivalent_precision(w_main.kbits, w_main.vbits)
