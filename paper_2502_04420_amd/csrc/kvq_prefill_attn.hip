@@ -608,14 +608,17 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         __syncthreads();
         float4v S[2][kQT], Sn[2][kQT];
         if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq);
-        // one unit: its scores come in Sin, those of the next unit leave in Sout (the two arrays swap roles from unit to unit)
+        // one unit: its scores come in Sin, those of the next unit leave in Sout (the two arrays swap roles from unit to
+        // unit).  Whether a unit may take the calm form is decided one unit ahead, right after its scores were issued:
+        // the test then sits next to the output products of the unit before, which need nothing from it.
+        bool calm = false;                                       // unit 0 never is: the references start at -inf
         auto step = [&](int u, const Tiles &X0, const Tiles &X1, const float4v (&Sin)[2][kQT], float4v (&Sout)[2][kQT]) {
             if (u <= wlast) {
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
                 half8 P[kQT];
-                if (ahead && u < open_units && !unit_exceeds(Sin, calm_over_c, m)) {
+                if (calm) {
                     // the common case, one stretch of straight-line code: score products of the next unit next to the
-                    // weights of this one against the unchanged reference
+                    // weights of this one against the unchanged reference (calm implies that there is a next unit)
                     score_unit<KLO>(X1, Qf, Sout, n, rq);
                     softmax_calm(Sin, c, m, lsum, P);
                 } else {
@@ -628,6 +631,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                 // one place adds to the accumulators on every path: they stay in the same registers (with a product
                 // on each path the compiler copied all 64 of them after every unit)
                 output_add(X0, P, O, n, rq);
+                // the next unit is calm if it needs no mask, has a unit after it to look ahead to, and none of its
+                // scores exceeds its query's reference (as it stands now) by more than kCalm
+                calm = ahead && u + 2 < nb && u + 2 <= wlast && u + 1 < open_units && !unit_exceeds(Sout, calm_over_c, m);
             }
         };
         auto after = [](int x) { return x + 1 < kBuffers ? x + 1 : 0; };
