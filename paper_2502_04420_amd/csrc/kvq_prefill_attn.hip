@@ -487,12 +487,13 @@ constexpr int kTileKiB = 9;
 static_assert(sizeof(_Float16) * 32 * kKStride == kTileKiB * 1024 && sizeof(_Float16) * kD * kVStride == kTileKiB * 1024 &&
               sizeof(Tiles) == 3 * kTileKiB * 1024, "tiles of a unit are whole KiB");
 
-__device__ __forceinline__ void fetch_piece(const uint8_t *src_of_lane, uint32_t lds_base)
+__device__ __forceinline__ void fetch_piece(const uint8_t *unit, uint32_t offset_of_lane, uint32_t lds_base)
 {
     // The compiler does not see this load: the waits for it are written out below (wait_fetches).  Loads it does not
     // know of can only make its own waits longer, never too short.  M0 is a register the compiler reserves and sets
     // itself right before an instruction of its own that reads it; nothing else in these kernels does.
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src_of_lane) : "memory");
+    // Address = the unit's (wave-uniform, scalar registers) + a 32-bit offset per lane that is the same for every unit.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(offset_of_lane), "s"(unit) : "memory");
 }
 
 // Wave `wave` fetches the pieces wave, wave + 8, ... of a unit; without low parts of the keys that tile is left out.
@@ -506,7 +507,7 @@ __device__ __forceinline__ void fetch_unit(const uint8_t *unit, Tiles &L, int wa
         const int p = wave + kWaves * i;                          // the same for all lanes of the wave
         if (p < pieces) {
             const int off = 1024 * (KLO || p < kTileKiB ? p : p + kTileKiB);
-            fetch_piece(unit + off + 16 * lane, lds + off);
+            fetch_piece(unit, (uint32_t)(off + 16 * lane), lds + off);
         }
     }
 }
