@@ -22,8 +22,12 @@
  *     passed as void*, NULL = the default stream).  No call synchronises the device.
  *   - Calls on one context are not thread-safe; serialise them.
  *   - fp16 means IEEE binary16.  All sequences of the batch have the same length.
- *   - Functions returning int return KVQ_OK (0) or a negative kvq_status; nothing is
- *     enqueued when an error is returned.
+ *   - Functions returning int return KVQ_OK (0) or a negative kvq_status.  Argument, state and
+ *     capacity errors are found before anything is enqueued.  KVQ_ELAUNCH means the HIP runtime
+ *     refused one of a call's launches; launches before it may have been enqueued (each call says
+ *     what state that leaves).
+ *   - This build supports head_dim = 128 and group = 32 only (kvq_workspace_bytes returns 0 and
+ *     kvq_configure KVQ_EINVAL for anything else): the packed layout is built on 32 x 128 blocks.
  */
 #ifndef KVQ_H
 #define KVQ_H
@@ -114,6 +118,9 @@ int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, 
  * values per token over each G channels) and the newest T - N_p stay in fp16.  The result
  * depends only on the concatenated token sequence, not on how it was split into calls.
  * The inputs may be reused once the enqueued work has run.  Inputs must be finite.
+ * A zero minimum or maximum of a group counts as +0 whatever the signs of the zeros it holds
+ * (z and s have one bit pattern per group).  On any error the layer holds the same tokens as
+ * before the call.
  */
 int kvq_quantize_append(kvq_ctx *ctx, int32_t layer, const void *k_device, const void *v_device,
                         int32_t n_tokens);
@@ -135,8 +142,10 @@ int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void
  * kvq_decode_attention; the difference is that the decode kernel itself takes the new rows
  * from k_device / v_device and stores them into the fp16 window, which saves the separate
  * window-copy launch.  k_device / v_device must stay unchanged until the enqueued work has
- * run (as for every other call).  Errors as for the two calls it replaces; nothing is changed
- * when KVQ_ECAPACITY is returned.
+ * run (as for every other call).  Errors as for the two calls it replaces.  Whatever error is
+ * returned, the layer holds the same tokens as before the call (on KVQ_ELAUNCH the token is
+ * not appended even if the refused launch was the second one; kernels enqueued before the
+ * refusal only write what a repeat of the call writes again, identically).
  */
 int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_device, const void *v_device,
                                 const void *q_device, void *out_device);

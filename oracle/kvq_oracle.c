@@ -32,6 +32,8 @@
  *   - prefill-stage attention (the prompt's own attention reading the dequantized cache, Section 5.3 and the
  *     experimental-settings appendix): evaluated over the cache as it stands when it is called; the query at
  *     absolute position p sees positions 0..p; a token enters as X^ if it is held quantized at that moment.
+ *   - signed zeros: min(X) and max(X) are numbers; a zero minimum or maximum is stored as +0 whichever of +0 / -0
+ *     the group holds and in whichever order (z and s then have one bit pattern per group).
  *   - metadata precision: s and z are fp32 by default.  A variant stores them as
  *     fp16 (z exactly, s rounded once); it encodes and decodes with the rounded s.
  *
@@ -116,6 +118,11 @@ void kvo_quantize_group_ex(const float *x, int n, int bits, int scale_fp16, floa
         if (x[i] < mn) mn = x[i];
         if (x[i] > mx) mx = x[i];
     }
+    /* Eq. 2 takes the minimum and maximum as numbers.  The number zero has two fp32 encodings; which of them a scan
+     * meets first depends on the element order, which Eq. 2 does not know.  Reading: a zero extreme is stored as +0
+     * (so z and s have one bit pattern per group whatever the order; codes and X^ are the same either way). */
+    if (mn == 0.0f) mn = 0.0f;
+    if (mx == 0.0f) mx = 0.0f;
     const int qmax = (1 << bits) - 1;
     const float z = mn;
     const float range = mx - mn;

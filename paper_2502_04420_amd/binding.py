@@ -58,6 +58,8 @@ def load_library():
     lib.kvq_quantize_append.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32]
     lib.kvq_decode_attention.restype = c_int32
     lib.kvq_decode_attention.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
+    lib.kvq_append_decode_attention.restype = c_int32
+    lib.kvq_append_decode_attention.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.kvq_prefill_attention.restype = c_int32
     lib.kvq_prefill_attention.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
     lib.kvq_layer_tokens.restype = c_int32

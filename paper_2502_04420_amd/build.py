@@ -8,6 +8,7 @@ paper_2502_04420_amd/_build/.  hipcc cross-compiles, so no GPU is needed to buil
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -21,7 +22,9 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-
           # packed fp32 instructions are kept out of the generated code on purpose
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the encode path must not contract or reassociate anything: its results are compared bit for bit
-PER_FILE = {"kvq_quantize.hip": ["-ffp-contract=off"]}
+PER_FILE = {"kvq_quantize.hip": ["-ffp-contract=off"],
+            # M0 is named as clobbered by the global-to-LDS fetch; the compiler notes that it reserves that register
+            "kvq_prefill_attn.hip": ["-Wno-inline-asm"]}
 
 
 def sources():
@@ -40,11 +43,59 @@ def _compile(src: str) -> str:
     return obj
 
 
+def device_assembly(src: str, extra=()) -> str:
+    """The gfx950 assembly hipcc generates for one source file with the library's flags."""
+    out = os.path.join(OBJ, src.replace(".hip", ".s"))
+    cmd = (["hipcc"] + COMMON + ["-w"] + PER_FILE.get(src, []) + list(extra)
+           + ["-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", out])
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode:
+        raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stderr[-2000:]))
+    with open(out) as f:
+        return f.read()
+
+
+def kernel_bodies(asm: str, name: str):
+    """(mangled name, text) of the kernels whose mangled name contains `name`."""
+    return [(m.group(1), m.group(0)) for m in re.finditer(r"^(_Z\w*%s\w*):.*?^\.Lfunc_end\d+:" % name, asm, re.S | re.M)]
+
+
+def check_prefill_attention_code(asm: str) -> None:
+    """The prefill attention kernels set M0 in inline assembly (LDS base of their global-to-LDS fetches).  The library
+    is only linked if, in the generated code, every M0 write is the one in front of such a fetch, nothing else reads or
+    writes M0, and no kernel of the file spills registers (two waves per SIMD is what its pipelining assumes)."""
+    kernels = kernel_bodies(asm, "prefill_attention")
+    if len(kernels) != 2:                                                  # keys quantized / fp16
+        raise RuntimeError("expected 2 prefill_attention kernels in the generated code, found %d" % len(kernels))
+    for name, body in kernels:
+        lines = [l.strip() for l in body.splitlines()]
+        code = [l for l in lines if l and not l.startswith((";", ".", "_Z")) and not l.endswith(":")]
+        writes = [i for i, l in enumerate(code) if re.match(r"s_mov_b32 m0,", l)]
+        fetches = [i for i, l in enumerate(code) if l.startswith("global_load_lds_dwordx4")]
+        if not fetches or len(writes) != len(fetches):
+            raise RuntimeError("%s: %d writes of M0 for %d fetches" % (name, len(writes), len(fetches)))
+        for w, f in zip(writes, fetches):
+            if not w < f <= w + 3:                                         # s_mov m0 ; s_nop ; load
+                raise RuntimeError("%s: M0 write not in front of a fetch: %s" % (name, code[w:w + 4]))
+        others = [l for l in code if re.search(r"\bm0\b", l) and not re.match(r"s_mov_b32 m0,", l)]
+        if others:
+            raise RuntimeError("%s: M0 used outside the fetches: %s" % (name, others[:3]))
+    spills = re.findall(r"\.vgpr_spill_count:\s+(\d+)", asm)
+    if not spills or any(int(x) for x in spills):
+        raise RuntimeError("kvq_prefill_attn.hip: register spills %s" % spills)
+
+
+def _check_generated_code() -> None:
+    check_prefill_attention_code(device_assembly("kvq_prefill_attn.hip"))
+
+
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     srcs = sources()
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
+        checked = ex.submit(_check_generated_code)          # alongside the compiles; a failure refuses the link
         objs = list(ex.map(_compile, srcs))
+        checked.result()
     tmp = OUT + ".tmp.%d" % os.getpid()
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs,
                        capture_output=True, text=True)

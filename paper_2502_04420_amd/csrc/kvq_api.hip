@@ -304,11 +304,16 @@ int kvq_append_decode_attention(kvq_ctx *c, int32_t layer, const void *k_device,
 {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_device || !v_device || !q_device || !out_device) return KVQ_EINVAL;
     // the matrix-core kernel takes the new token along (if it stays in the fp16 window); otherwise copy it first
-    const int t_new = c->tokens[layer] + 1;
+    const int t_old = c->tokens[layer], t_new = t_old + 1;
     const bool fused = decode_variant(c) == 2 && t_new <= c->cfg.max_tokens && t_new > packed_tokens(c, t_new);
-    const int rc = append_tokens(c, layer, k_device, v_device, 1, !fused);
+    int rc = append_tokens(c, layer, k_device, v_device, 1, !fused);
     if (rc != KVQ_OK) return rc;
-    return decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr);
+    rc = decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr);
+    // A refused decode launch must not leave a token counted whose window rows the decode kernel was to store: the
+    // layer goes back to its length before the call.  What was enqueued before the refusal (a flush of the oldest
+    // window group, a window copy) only writes what a repeat of the call writes again, identically.
+    if (rc != KVQ_OK) c->tokens[layer] = t_old;
+    return rc;
 }
 
 int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32_t n_q, void *out_device)

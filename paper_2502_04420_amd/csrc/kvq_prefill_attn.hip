@@ -490,10 +490,10 @@ static_assert(sizeof(_Float16) * 32 * kKStride == kTileKiB * 1024 && sizeof(_Flo
 __device__ __forceinline__ void fetch_piece(const uint8_t *unit, uint32_t offset_of_lane, uint32_t lds_base)
 {
     // The compiler does not see this load: the waits for it are written out below (wait_fetches).  Loads it does not
-    // know of can only make its own waits longer, never too short.  M0 is a register the compiler reserves and sets
-    // itself right before an instruction of its own that reads it; nothing else in these kernels does.
+    // know of can only make its own waits longer, never too short.  M0 is declared as clobbered, so a use of its own the compiler
+    // might make of M0 (it sets M0 right before an instruction that reads it) stays correct.
     // Address = the unit's (wave-uniform, scalar registers) + a 32-bit offset per lane that is the same for every unit.
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(offset_of_lane), "s"(unit) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(offset_of_lane), "s"(unit) : "memory", "m0");
 }
 
 // Wave `wave` fetches the pieces wave, wave + 8, ... of a unit; without low parts of the keys that tile is left out.
@@ -708,17 +708,15 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // pass 2 (three tile buffers: more LDS than a kernel may declare statically)
+    // pass 2 (kBuffers tile buffers: more LDS than a kernel may declare statically)
     const dim3 grid((unsigned)groups), block(64 * kWaves);
     const size_t lds = kBuffers * sizeof(Tiles);
     hipEvent_t b2 = a.n_blocks > 0 ? nullptr : ev_begin;
     auto attend = [&](auto kernel) -> hipError_t {
-        static bool allowed = false;                   // per instantiation: the larger dynamic LDS size is granted once
-        if (!allowed) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            allowed = true;
-        }
+        // the larger dynamic LDS size is asked for at every launch of either kernel, on whichever device is current:
+        // a host-side setting, negligible next to a launch of milliseconds, and no process-wide state to keep
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
         if (b2 || ev_end) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, b2, ev_end, 0, a);
         else hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
         return hipSuccess;

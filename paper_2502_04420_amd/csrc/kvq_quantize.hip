@@ -50,6 +50,16 @@ __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
     return d;
 }
 
+// Eq. 2 takes min(X) and max(X) as numbers, and the number zero has two encodings.  A zero extreme is stored as +0
+// whichever zeros the group holds and in whichever order the reduction met them, so that z and s have one bit pattern.
+__device__ __forceinline__ uint32_t plus_zero_pair(uint32_t w)
+{
+    if ((w & 0x00007fffu) == 0) w &= 0xffff0000u;
+    if ((w & 0x7fff0000u) == 0) w &= 0x0000ffffu;
+    return w;
+}
+__device__ __forceinline__ float plus_zero(float x) { return x == 0.0f ? 0.0f : x; }
+
 // Eq. 2 for one element, the defining sequence: (one IEEE subtraction, done by the caller,) one IEEE
 // division, round half to even, clamp.  Returns the code as a float.
 template <int BITS>
@@ -290,8 +300,8 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     w = pair_xor32(mxp[p]); mxp[p] = pk_max(w.x, w.y);
                 }
                 // every lane row now holds the statistics of all 8 channels: row r finishes channels 2r and 2r + 1
-                const uint32_t mn2 = r == 0 ? mnp[0] : r == 1 ? mnp[1] : r == 2 ? mnp[2] : mnp[3];
-                const uint32_t mx2 = r == 0 ? mxp[0] : r == 1 ? mxp[1] : r == 2 ? mxp[2] : mxp[3];
+                const uint32_t mn2 = plus_zero_pair(r == 0 ? mnp[0] : r == 1 ? mnp[1] : r == 2 ? mnp[2] : mnp[3]);
+                const uint32_t mx2 = plus_zero_pair(r == 0 ? mxp[0] : r == 1 ? mxp[1] : r == 2 ? mxp[2] : mxp[3]);
                 // the pair goes out as one store per array (scales, zero-points; LDS copies likewise)
                 const int ch = 8 * c16 + 2 * r;
                 float s2[2], r2[2];
@@ -317,8 +327,8 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
                     uint32_t mxp = pk_max(pk_max(x[i][0], x[i][1]), pk_max(x[i][2], x[i][3]));
                     mnp = pk_min(mnp, from_lane_xor1(mnp)); mxp = pk_max(mxp, from_lane_xor1(mxp));
                     mnp = pk_min(mnp, from_lane_xor2(mnp)); mxp = pk_max(mxp, from_lane_xor2(mxp));
-                    const float mn = fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16));
-                    const float mx = fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16));
+                    const float mn = plus_zero(fminf(half_bits_to_float(mnp & 0xffffu), half_bits_to_float(mnp >> 16)));
+                    const float mx = plus_zero(fmaxf(half_bits_to_float(mxp & 0xffffu), half_bits_to_float(mxp >> 16)));
                     const float s = stored_scale<NARROW>(scale_of(mn, mx, KB));
                     s_max = fmaxf(s_max, s);
                     if ((c16 & 3) == 0) {
@@ -408,8 +418,8 @@ __global__ __launch_bounds__(64) void quantize_blocks(QuantArgs a)
             for (int h = 0; h < 2; h++) {
                 const uint32_t mnb = q4 == 0 ? mnp[h] : q4 == 1 ? mnp[2 + h] : q4 == 2 ? mnp[4 + h] : mnp[6 + h];
                 const uint32_t mxb = q4 == 0 ? mxp[h] : q4 == 1 ? mxp[2 + h] : q4 == 2 ? mxp[4 + h] : mxp[6 + h];
-                const float mn = fminf(half_bits_to_float(mnb & 0xffffu), half_bits_to_float(mnb >> 16));
-                const float mx = fmaxf(half_bits_to_float(mxb & 0xffffu), half_bits_to_float(mxb >> 16));
+                const float mn = plus_zero(fminf(half_bits_to_float(mnb & 0xffffu), half_bits_to_float(mnb >> 16)));
+                const float mx = plus_zero(fmaxf(half_bits_to_float(mxb & 0xffffu), half_bits_to_float(mxb >> 16)));
                 s2[h] = stored_scale<NARROW>(scale_of(mn, mx, VB));
                 r2[h] = recip_or_zero(s2[h]);
                 s_max = fmaxf(s_max, s2[h]);

@@ -24,7 +24,9 @@ def kvq_mod():
     return pkg
 
 
-def _check_layer(kvq_mod, oracle_mod, w, layer, extra_tokens, samples, meta16=False):
+def _check_layer(kvq_mod, oracle_mod, w, layer, extra_tokens, samples, meta16=False, fused=False):
+    """fused: the extra tokens arrive through kvq_append_decode_attention, the one-call decode step bench.py times (its
+    last call's output is the one compared); else through kvq_quantize_append, followed by one kvq_decode_attention."""
     kb, vb = w.kbits[layer], w.vbits[layer]
     g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.context + 64, [kb], [vb],
                     meta_dtype=kvq_mod.META_FP16 if meta16 else kvq_mod.META_FP32)
@@ -33,10 +35,18 @@ def _check_layer(kvq_mod, oracle_mod, w, layer, extra_tokens, samples, meta16=Fa
     del K, V
     # a few single-token appends as in the decode loop (they land in the fp16 window, possibly after a flush)
     Kn, Vn = W.kv_tokens(w, layer, 0, extra_tokens, device="cuda:0", stream=1, total=extra_tokens)
-    for t in range(extra_tokens):
-        g.quantize_append(0, Kn[:, :, t:t + 1].contiguous(), Vn[:, :, t:t + 1].contiguous())
     q = W.query(w, layer, 0, device="cuda:0")
-    out = g.decode_attention(0, q).float().cpu().numpy().astype(np.float64)
+    if fused:
+        assert extra_tokens >= 1
+        scratch_q = W.query(w, layer, 1, device="cuda:0")
+        for t in range(extra_tokens):
+            out_t = g.append_decode_attention(0, Kn[:, :, t:t + 1].contiguous(), Vn[:, :, t:t + 1].contiguous(),
+                                              q if t == extra_tokens - 1 else scratch_q)
+        out = out_t.float().cpu().numpy().astype(np.float64)
+    else:
+        for t in range(extra_tokens):
+            g.quantize_append(0, Kn[:, :, t:t + 1].contiguous(), Vn[:, :, t:t + 1].contiguous())
+        out = g.decode_attention(0, q).float().cpu().numpy().astype(np.float64)
     dump = g.debug_export(0)
     gq = w.n_q_heads // w.n_kv_heads
     worst = 0.0
@@ -80,6 +90,19 @@ def test_llama_shape_batch16_context8192_mix_and_kv8(kvq_mod, oracle_mod):
     _check_layer(kvq_mod, oracle_mod, w, 16, 2, samples[2:], meta16=True)   # the narrow-metadata variant at full size
 
 
+def test_llama_shape_fused_decode_steps_across_a_flush(kvq_mod, oracle_mod):
+    """The call bench.py times, in its launch configuration: kvq_append_decode_attention at batch 16, context 8192
+    (automatic splits: the new token is read from the caller's tensor by the last split of every cache), 40 steps, so
+    that a window flush of 32 tokens falls inside; cache state bit for bit and the last step's output within the bars."""
+    w = W.config3(16, 8192)
+    _check_layer(kvq_mod, oracle_mod, w, 16, 40, [0, 61, 127], fused=True)     # K4V2 layer
+    _check_layer(kvq_mod, oracle_mod, w, 30, 33, [5, 100], fused=True)         # K4V4 layer
+    w8 = W.named("llama8b", "K8V8", 16, 8192)
+    _check_layer(kvq_mod, oracle_mod, w8, 7, 34, [64], fused=True)
+    wq = W.config4(8, 32768)
+    _check_layer(kvq_mod, oracle_mod, wq, 1, 35, [9], fused=True)              # Qwen shape (g_q = 7), K4V2 layer
+
+
 def test_qwen_shape_batch8_context32768_biased_keys(kvq_mod, oracle_mod):
     """The Qwen2.5-7B shape: g_q = 7, keys with a large per-channel offset, 32K context (K8V2 and K4V2 layers)."""
     w = W.config4(8, 32768)
@@ -110,3 +133,4 @@ def test_llama_shape_batch64_context32768_one_bulk_append(kvq_mod, oracle_mod):
     _check_layer(kvq_mod, oracle_mod, w, 16, 2, [511, 256])            # K4V2 layer: last and a middle (batch, kv head)
     w8 = W.named("llama8b", "K8V8", 64, 32768)
     _check_layer(kvq_mod, oracle_mod, w8, 3, 1, [300])
+    _check_layer(kvq_mod, oracle_mod, w, 1, 2, [129], fused=True)      # K4V4 layer of the mix at the largest sweep point

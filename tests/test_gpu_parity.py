@@ -381,3 +381,85 @@ def test_reset_and_reuse(kvq_mod, oracle_mod):
     assert_export_equal(g.debug_export(0), o.export(0), "after reset")
     with pytest.raises(kvq_mod.KVQError):
         g.quantize_append(0, K.cuda(), V.cuda())       # 70 + 80 > 128 tokens
+
+
+@pytest.mark.parametrize("meta16", [False, True], ids=["fp32scales", "fp16scales"])
+@pytest.mark.parametrize("per_token", [False, True], ids=["keys-per-channel", "keys-per-token"])
+@pytest.mark.parametrize("kb,vb", [(4, 2), (8, 8), (2, 4)])
+def test_signed_zero_extremes(kvq_mod, oracle_mod, kb, vb, per_token, meta16):
+    """Groups whose minimum (or maximum) is zero and that hold +0 and -0 in both orders, only -0, or zeros only:
+    the zero-point and the scale are stored with a zero extreme as +0, so k_zero / v_zero / k_scale / v_scale agree
+    with the oracle bit for bit whatever order the kernel's reduction meets the zeros in."""
+    rng = np.random.default_rng(77)
+    B, H, T, D = 2, 2, 128, 128
+    K = (np.abs(rng.standard_normal((B, H, T, D))) + 0.25).astype(np.float16)
+    V = K.copy()
+    pz, nz = np.float16(0.0), np.float16(-0.0)
+    # key groups over tokens (per channel): block 0 (+0 before -0), block 1 (-0 before +0), block 2 (-0 only, rest
+    # negative: zero maximum), block 3 (all zeros of mixed sign) -- on some channels each, at several lane rows
+    for ch in (0, 1, 17, 64, 127):
+        K[:, :, 2, ch], K[:, :, 29, ch] = pz, nz
+        K[:, :, 32 + 1, ch], K[:, :, 32 + 30, ch] = nz, pz
+        K[:, :, 64:96, ch] = -K[:, :, 64:96, ch]
+        K[:, :, 64 + 7, ch] = nz
+        K[:, :, 96:128:2, ch], K[:, :, 97:128:2, ch] = nz, pz
+    # groups over channels (values, and keys when grouped per token): the same four cases on several tokens
+    for X in (V, K):
+        for t in (0, 5, 40, 77, 127):
+            X[:, :, t, 3], X[:, :, t, 30] = pz, nz
+            X[:, :, t, 32 + 4], X[:, :, t, 32 + 9] = nz, pz
+            X[:, :, t, 64:96] = -np.abs(X[:, :, t, 64:96])
+            X[:, :, t, 64 + 21] = nz
+            X[:, :, t, 96:128:2], X[:, :, t, 97:128:2] = pz, nz
+    g = kvq_mod.KVQ(1, B, 4 * H, H, D, 256, [kb], [vb], residual=0,
+                    key_mode=kvq_mod.KEYS_PER_TOKEN if per_token else kvq_mod.KEYS_PER_CHANNEL,
+                    meta_dtype=kvq_mod.META_FP16 if meta16 else kvq_mod.META_FP32)
+    o = oracle_mod.OracleCache(1, B, 4 * H, H, D, [kb], [vb], residual=0, key_per_token=per_token, scale_fp16=meta16)
+    # in two chunks, so that the second one is encoded out of the window ring
+    for a, b in ((0, 50), (50, T)):
+        g.quantize_append(0, torch.from_numpy(np.ascontiguousarray(K[:, :, a:b])).cuda(), torch.from_numpy(np.ascontiguousarray(V[:, :, a:b])).cuda())
+        o.quantize_append(0, np.ascontiguousarray(K[:, :, a:b]), np.ascontiguousarray(V[:, :, a:b]))
+    gd, od = g.debug_export(0), o.export(0)
+    assert_export_equal(gd, od, "signed zeros K%dV%d" % (kb, vb))
+    for key in ("k_zero", "v_zero", "k_scale", "v_scale"):
+        assert not np.any(od[key].view(np.uint32) == 0x80000000), key       # the cases are really there and canonical
+        assert np.any(od[key].view(np.uint32) == 0), key
+
+
+@pytest.mark.parametrize("kb,vb", [(4, 2), (2, 2), (8, 4), (4, 8)])
+def test_groups_spanning_the_fp16_range(kvq_mod, oracle_mod, kb, vb, variant):
+    """Keys and values whose groups span most of the fp16 range (about -6e4 .. 6e4) next to groups of ordinary and of
+    tiny magnitude in the same block: the scales of one block then differ by more than 2^30, which is the stress for
+    the lifting of the matrix-core operands by the block's largest scale exponent.  Codes, scales and zero-points bit
+    for bit; outputs within the bars (queries are small on the huge channels so that the logits stay finite)."""
+    w = W.Workload("span", 1, 2, 8, 2, 128, 32 * 5 + 9, [kb], [vb], seed=1700 + kb * 17 + vb, outlier_channels=3)
+    g, o = _pair(kvq_mod, oracle_mod, w, 512, variant=variant)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    q = W.query(w, 0)
+    big = torch.tensor([7, 40, 41, 100])
+    K[:, :, :, big] = (K[:, :, :, big].float() * 2.0e4).clamp(-6.0e4, 6.0e4).to(torch.float16)
+    K[:, :, :, 8] = (K[:, :, :, 8].float() * 2.0 ** -18).to(torch.float16)               # subnormal-range channel
+    q[:, :, big] = (q[:, :, big].float() * 2.0 ** -14).to(torch.float16)
+    V[:, :, 3::7, 32:64] = (V[:, :, 3::7, 32:64].float() * 2.0e4).clamp(-6.0e4, 6.0e4).to(torch.float16)
+    V[:, :, 5::11, 96:128] = (V[:, :, 5::11, 96:128].float() * 2.0 ** -16).to(torch.float16)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    assert_export_equal(g.debug_export(0), o.export(0), "span K%dV%d" % (kb, vb))
+    out = g.decode_attention(0, q.cuda())
+    o16, o64 = o.decode_attention(0, q.numpy())
+    # Outputs reach the magnitude of the large values, so the absolute bar grows with the output's own fp16 spacing.
+    # The matrix-core kernel gets one more term.  Its products p s c of a block's 32 tokens are summed by the matrix
+    # core, which aligns them to the largest one and drops what lies more than about 24 bits below that product's
+    # nominal exponent (the codes are fp16 subnormals: up to 6 leading zero bits); 32 products, truncated: the sum of a
+    # block is off by up to 2^-13, typically 2^-14, of the largest product p s c <= p * (group range), and the output,
+    # a weighted mean over blocks, by that fraction of the largest value-group range in the cache.  For N(0,1) values
+    # (range about 5) that is 3e-4, inside the 2e-3 bar that all other tests apply unchanged; here the range is 1.2e5.
+    gpu = out.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(gpu))
+    od = o.export(0)
+    largest_range = float(od["v_scale"].max()) * ((1 << vb) - 1)
+    bar = MAX_ABS + 2.0 ** -10 * np.abs(o64) + (2.0 ** -14 * largest_range if variant == 2 else 0.0)
+    excess = float((np.abs(gpu - o64) - bar).max())
+    assert excess <= 0.0, ("worst element exceeds its bar by", excess, "largest value-group range", largest_range)
+    rel = float(np.linalg.norm(gpu - o64) / np.linalg.norm(o64))
+    assert rel <= REL_L2, ("rel l2", rel)

@@ -281,3 +281,60 @@ def test_fp16_scale_variant_special_cases(oracle_mod):
     x[2] = 2.0 ** -24 * 100
     s, z, c = oracle_mod.quantize_group(x, 8, True)
     assert s == np.float32(2.0 ** -24) and c[1] == 255 and c[2] == 100
+
+
+def _bits32(x):
+    return int(np.float32(x).view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("scale_fp16", [False, True])
+def test_zero_extremes_are_stored_as_plus_zero(oracle_mod, bits, scale_fp16):
+    """Eq. 2 takes min(X) and max(X) as numbers; zero has two encodings.  The reading: a zero minimum (and a zero
+    maximum) is +0 whichever zeros the group holds and in whichever order, so z and s have one bit pattern each and
+    the result cannot depend on the order of the elements.  Expected bits are written out, not computed."""
+    pz, nz = np.float32(0.0), np.float32(-0.0)
+    assert _bits32(nz) == 0x80000000
+    qmax = (1 << bits) - 1
+    # minimum zero: both orders of (+0, -0), only -0, only +0; the rest positive (max = qmax -> s = 1 exactly)
+    for head in ([pz, nz], [nz, pz], [nz, nz], [pz, pz]):
+        x = np.array(head + [np.float32(qmax)] + [np.float32(1.0)] * 29, dtype=np.float32)
+        s, z, c = oracle_mod.quantize_group(x, bits, scale_fp16)
+        assert _bits32(z) == 0x00000000, head
+        assert _bits32(s) == 0x3F800000                       # 1.0
+        assert c.tolist() == [0, 0, qmax] + [1] * 29
+    # maximum zero: the rest negative (min = -qmax): s = (0 - (-qmax)) / qmax = 1, never -0-tainted
+    for head in ([pz, nz], [nz, pz], [nz, nz]):
+        x = np.array(head + [np.float32(-qmax)] + [np.float32(-1.0)] * 29, dtype=np.float32)
+        s, z, c = oracle_mod.quantize_group(x, bits, scale_fp16)
+        assert _bits32(z) == _bits32(np.float32(-qmax)) and _bits32(s) == 0x3F800000
+        assert c.tolist() == [qmax, qmax, 0] + [qmax - 1] * 29
+    # a group of zeros only: z = +0, s = +0 (not -0, which max - min would give for max = -0, min = +0), codes 0
+    for vals in ([nz] * 32, [pz, nz] * 16, [nz, pz] * 16):
+        s, z, c = oracle_mod.quantize_group(np.array(vals, dtype=np.float32), bits, scale_fp16)
+        assert _bits32(z) == 0 and _bits32(s) == 0 and not c.any()
+
+
+@pytest.mark.parametrize("key_per_token", [False, True])
+def test_zero_extremes_through_the_cache_export(oracle_mod, key_per_token):
+    """The same reading through quantize_append and the canonical export, keys and values, both key groupings:
+    k_zero / v_zero / k_scale / v_scale bits do not depend on the order in which +0 and -0 appear in a group."""
+    rng = np.random.default_rng(5)
+    B, H, T, D = 1, 1, 64, 128
+    base = np.abs(rng.standard_normal((B, H, T, D))).astype(np.float16) + np.float16(0.5)
+    dumps = []
+    for first, second in ((0.0, -0.0), (-0.0, 0.0)):
+        K, V = base.copy(), base.copy()
+        # keys per channel: tokens 3 and 17 of each key group hold the zeros; values (and per-token keys): channels 5, 9 of a group
+        K[:, :, 3::32, :] = np.float16(first); K[:, :, 17::32, :] = np.float16(second)
+        K[:, :, :, 5::32] = np.float16(first); K[:, :, :, 9::32] = np.float16(second)
+        V[:, :, :, 5::32] = np.float16(first); V[:, :, :, 9::32] = np.float16(second)
+        o = oracle_mod.OracleCache(1, B, 4, H, D, [4], [2], residual=0, key_per_token=key_per_token)
+        o.quantize_append(0, K, V)
+        dumps.append(o.export(0))
+        o.close()
+    a, b = dumps
+    for key in ("k_zero", "v_zero", "k_scale", "v_scale", "k_codes", "v_codes"):
+        assert np.array_equal(a[key].view(np.uint8), b[key].view(np.uint8)), key
+    for key in ("k_zero", "v_zero"):
+        assert not a[key].view(np.uint32).any()               # every group's minimum is zero: all-zero bits, never 0x80000000
