@@ -45,7 +45,9 @@ typedef enum kvq_status {
     KVQ_ECAPACITY = -2,   /* append would exceed max_tokens                                       */
     KVQ_ESTATE = -3,      /* decode on a layer that holds no token                                */
     KVQ_EWORKSPACE = -4,  /* workspace NULL, misaligned (needs 256 B) or smaller than required    */
-    KVQ_ELAUNCH = -5      /* the HIP runtime refused a launch (message via kvq_last_error)        */
+    KVQ_ELAUNCH = -5,     /* the HIP runtime refused a launch (message via kvq_last_error)        */
+    KVQ_ESCRATCH = -6     /* kvq_decode_attention_noalloc: the call needs more scratch than the   */
+                          /* built-in array holds (sizes via kvq_last_error)                      */
 } kvq_status;
 
 typedef struct kvq_ctx kvq_ctx;
@@ -135,6 +137,26 @@ int kvq_quantize_append(kvq_ctx *ctx, int32_t layer, const void *k_device, const
 int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void *out_device);
 
 /*
+ * kvq_decode_attention for callers that cannot allocate and cannot hand scratch memory along
+ * per call: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels, same result as kvq_decode_attention (bit for bit:
+ * the token-range splits are planned the same way).  The difference is where the splits'
+ * partial results live: not in the caller's workspace but in an array built into the library's
+ * device image, 16384 records of (128 outputs, maximum, sum) = 8.1 MiB, which every GPU the
+ * library runs on holds from its first use until the process ends.  The call allocates and frees
+ * nothing on host or device; on its first use on a GPU (with that GPU current) it looks up the
+ * array's address there.
+ *   Limit: batch * n_q_heads * splits <= 16384 records, else KVQ_ESCRATCH and nothing is
+ *   enqueued (kvq_last_error has the numbers).  With automatic splits (at most 2048 token
+ *   ranges over all (batch, kv head) caches) every shape with at most 8 query heads per kv head
+ *   fits; splits forced through kvq_set_decode_options may not.
+ *   All contexts and streams on one GPU share that GPU's array.  Nothing in it has to start at
+ *   zero (each call writes every record it later reads), but two such calls that overlap in time
+ *   on one GPU race on it: keep them on one stream or order them yourself.
+ */
+int kvq_decode_attention_noalloc(kvq_ctx *ctx, int32_t layer, const void *q_device, void *out_device);
+
+/*
  * One decode step of a layer in a single call: append exactly one new token per sequence
  * (k_device, v_device: fp16 [batch, n_kv_heads, 1, head_dim]) and then attend over all tokens,
  * the new one included (Eq. 1: K is the concatenation of the cached keys and the current one).
@@ -222,7 +244,7 @@ void kvq_destroy(kvq_ctx *ctx);
 /* Static description of a status code. */
 const char *kvq_strerror(int status);
 
-/* Detail of the last KVQ_ELAUNCH on this thread (empty string if none). */
+/* Detail of the last KVQ_ELAUNCH or KVQ_ESCRATCH on this thread (empty string if none). */
 const char *kvq_last_error(void);
 
 #ifdef __cplusplus

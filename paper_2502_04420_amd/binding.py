@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libkvq.so")
 _lib = None
 
 EXPORTED = [
-    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_append_decode_attention", "kvq_prefill_attention",
+    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_decode_attention_noalloc", "kvq_append_decode_attention", "kvq_prefill_attention",
     "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
     "kvq_last_error",
 ]
@@ -58,6 +58,8 @@ def load_library():
     lib.kvq_quantize_append.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32]
     lib.kvq_decode_attention.restype = c_int32
     lib.kvq_decode_attention.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
+    lib.kvq_decode_attention_noalloc.restype = c_int32
+    lib.kvq_decode_attention_noalloc.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
     lib.kvq_append_decode_attention.restype = c_int32
     lib.kvq_append_decode_attention.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.kvq_prefill_attention.restype = c_int32
@@ -87,7 +89,7 @@ def _check(status: int):
         lib = load_library()
         msg = lib.kvq_strerror(status).decode()
         detail = lib.kvq_last_error().decode()
-        raise KVQError(status, msg + (" (%s)" % detail if status == -5 and detail else ""))
+        raise KVQError(status, msg + (" (%s)" % detail if status in (-5, -6) and detail else ""))
 
 
 META_FP32, META_FP16 = 0, 1
@@ -181,6 +183,16 @@ class KVQ:
             out = torch.empty(shape, dtype=torch.float16, device=self.device)
         op = self._dev_ptr(out, shape, torch.float16, "out")
         _check(self._lib.kvq_decode_attention(self._h, layer, qp, op))
+        return out
+
+    def decode_attention_noalloc(self, layer: int, q, out):
+        """kvq_decode_attention_noalloc: the splits' partial results live in the library's built-in device array.  The
+        output tensor is the caller's (nothing is allocated on the way)."""
+        torch = self._torch
+        shape = (self.batch, self.n_q_heads, self.head_dim)
+        qp = self._dev_ptr(q, shape, torch.float16, "q")
+        op = self._dev_ptr(out, shape, torch.float16, "out")
+        _check(self._lib.kvq_decode_attention_noalloc(self._h, layer, qp, op))
         return out
 
     def append_decode_attention(self, layer: int, K, V, q, out=None):

@@ -5,9 +5,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -21,6 +23,22 @@ constexpr int kWindowWeight = 4;   // cost of the fp16 window in a split's share
 constexpr size_t kAlign = 256;
 
 thread_local char g_last_error[256] = "";
+
+// Built-in scratch of kvq_decode_attention_noalloc: the partial results of the token-range splits, which the other
+// decode calls keep in the caller's workspace.  One record per (query row, split): 128 un-normalised outputs, then
+// (further back) the pair (maximum, sum).  Every GPU the library runs on holds its own copy until the process ends.
+constexpr size_t kStaticRecords = 16384;                                   // 2048 groups x 8 grouped query heads
+constexpr size_t kStaticOutBytes = kStaticRecords * kvq::kD * sizeof(float);
+constexpr size_t kStaticBytes = kStaticOutBytes + kStaticRecords * 2 * sizeof(float);      // 8.1 MiB
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+// device address of `scratch` on each GPU (the array's name is only a host-side handle), looked up once per device
+std::atomic<unsigned char *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -124,6 +142,10 @@ kvq::LayerView view(const kvq_ctx *c, int l)
     return v;
 }
 
+float *ws_part_o(const kvq_ctx *c) { return reinterpret_cast<float *>(c->ws + c->plan.part_o); }
+float *ws_part_ml(const kvq_ctx *c) { return reinterpret_cast<float *>(c->ws + c->plan.part_ml); }
+size_t ws_part_records(const kvq_ctx *c) { return (size_t)c->cfg.batch * c->cfg.n_q_heads * kMaxSplits; }
+
 int launch_failed(const char *what, hipError_t e)
 {
     snprintf(g_last_error, sizeof g_last_error, "%s: %s", what, hipGetErrorString(e));
@@ -217,7 +239,9 @@ int append_tokens(kvq_ctx *c, int layer, const void *k_device, const void *v_dev
 
 // Decode attention over the layer's tokens.  k_new / v_new: rows of a token that append_tokens() left out of the
 // window ring (fused append), or NULL.
-int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, const void *k_new, const void *v_new)
+// part_o / part_ml: where the splits' partial results go, room for part_records (query row, split) records.
+int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, const void *k_new, const void *v_new,
+                 float *part_o, float *part_ml, size_t part_records)
 {
     const int T = c->tokens[layer];
     if (T < 1) return KVQ_ESTATE;
@@ -226,8 +250,8 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     a.lv = view(c, layer);
     a.q = static_cast<const uint16_t *>(q_device);
     a.out = static_cast<uint16_t *>(out_device);
-    a.part_o = reinterpret_cast<float *>(c->ws + c->plan.part_o);
-    a.part_ml = reinterpret_cast<float *>(c->ws + c->plan.part_ml);
+    a.part_o = part_o;
+    a.part_ml = part_ml;
     a.B = c->cfg.batch;
     a.Hq = c->cfg.n_q_heads;
     a.Hkv = c->cfg.n_kv_heads;
@@ -269,6 +293,12 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     if (splits > block_splits + (window ? 1 : 0)) splits = block_splits + (window ? 1 : 0);   // no empty split
     if (splits < 1) splits = 1;
     a.splits = splits;
+    if ((size_t)a.B * a.Hq * (size_t)splits > part_records) {
+        snprintf(g_last_error, sizeof g_last_error,
+                 "decode needs %zu partial records (%d query rows x %d splits), the scratch holds %zu",
+                 (size_t)a.B * a.Hq * (size_t)splits, a.B * a.Hq, splits, part_records);
+        return KVQ_ESCRATCH;
+    }
     const bool timed = c->ev_begin && c->ev_end;
     hipError_t e;
     if (variant == 2) {
@@ -296,7 +326,33 @@ int kvq_quantize_append(kvq_ctx *c, int32_t layer, const void *k_device, const v
 int kvq_decode_attention(kvq_ctx *c, int32_t layer, const void *q_device, void *out_device)
 {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
-    return decode_layer(c, layer, q_device, out_device, nullptr, nullptr);
+    return decode_layer(c, layer, q_device, out_device, nullptr, nullptr, ws_part_o(c), ws_part_ml(c), ws_part_records(c));
+}
+
+int kvq_decode_attention_noalloc(kvq_ctx *c, int32_t layer, const void *q_device, void *out_device)
+{
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_device || !out_device) return KVQ_EINVAL;
+    // the device address of the built-in scratch array, looked up once per GPU with that GPU current
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return launch_failed("hipGetDevice", e);
+    if (dev < 0 || dev >= kMaxDevices) {
+        snprintf(g_last_error, sizeof g_last_error, "device ordinal %d beyond the %d this build keeps scratch addresses for", dev, kMaxDevices);
+        return KVQ_ESCRATCH;
+    }
+    unsigned char *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        ptr = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!ptr) {
+            e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) return launch_failed("hipGetSymbolAddress(scratch)", e);
+            g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+        }
+    }
+    // every record the merge reads is written by this call's decode kernel first: nothing has to start at zero
+    return decode_layer(c, layer, q_device, out_device, nullptr, nullptr, reinterpret_cast<float *>(ptr),
+                        reinterpret_cast<float *>(ptr + kStaticOutBytes), kStaticRecords);
 }
 
 int kvq_append_decode_attention(kvq_ctx *c, int32_t layer, const void *k_device, const void *v_device, const void *q_device,
@@ -308,7 +364,8 @@ int kvq_append_decode_attention(kvq_ctx *c, int32_t layer, const void *k_device,
     const bool fused = decode_variant(c) == 2 && t_new <= c->cfg.max_tokens && t_new > packed_tokens(c, t_new);
     int rc = append_tokens(c, layer, k_device, v_device, 1, !fused);
     if (rc != KVQ_OK) return rc;
-    rc = decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr);
+    rc = decode_layer(c, layer, q_device, out_device, fused ? k_device : nullptr, fused ? v_device : nullptr,
+                      ws_part_o(c), ws_part_ml(c), ws_part_records(c));
     // A refused decode launch must not leave a token counted whose window rows the decode kernel was to store: the
     // layer goes back to its length before the call.  What was enqueued before the refusal (a flush of the oldest
     // window group, a window copy) only writes what a repeat of the call writes again, identically.
@@ -434,6 +491,7 @@ const char *kvq_strerror(int status)
     case KVQ_ESTATE: return "layer holds no token";
     case KVQ_EWORKSPACE: return "workspace missing, misaligned or too small";
     case KVQ_ELAUNCH: return "HIP launch failed";
+    case KVQ_ESCRATCH: return "the call needs more scratch than the library's built-in array holds";
     default: return "unknown status";
     }
 }

@@ -59,3 +59,25 @@ def test_quantize_kernel_keeps_the_fused_widen_and_subtract(tmp_path):
     kernels = [b for n, b in _kernels(asm, "quantize_blocks") if "ILi4ELi2ELb0E" in n]
     assert len(kernels) == 1
     assert len(re.findall(r"^\s*v_fma_mix_f32 ", kernels[0], re.M)) >= 128      # 2 tensors x 64 elements per lane
+
+
+def test_builtin_scratch_array_is_visible_to_the_loader():
+    """kvq_decode_attention_noalloc asks the runtime for the device address of the library's built-in scratch array.
+    That only works if the device code object exports the array as a global symbol (an attribute such as `used` keeps
+    a static device variable local, the lookup then yields an address that is not the array's, and the first kernel
+    that uses it faults).  Checked on the object the build produced."""
+    tools = "/opt/rocm/llvm/bin"
+    obj = os.path.join(ROOT, "paper_2502_04420_amd", "_build", "kvq_api.o")
+    if not (os.path.exists(obj) and all(os.path.exists(os.path.join(tools, t)) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf"))):
+        pytest.skip("needs the built object and the LLVM binary tools")
+    import tempfile
+
+    with tempfile.TemporaryDirectory() as tmp:
+        fat, co = os.path.join(tmp, "fat.bin"), os.path.join(tmp, "api.co")
+        subprocess.check_call([os.path.join(tools, "llvm-objcopy"), "-O", "binary", "--only-section=.hip_fatbin", obj, fat])
+        subprocess.check_call([os.path.join(tools, "clang-offload-bundler"), "--type=o", "--input=" + fat,
+                               "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", "--output=" + co, "--unbundle"])
+        syms = subprocess.check_output([os.path.join(tools, "llvm-readelf"), "-s", co], text=True)
+    rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch")]
+    assert rows, "no scratch symbol in the device code object"
+    assert all(r[4] == "GLOBAL" and r[3] == "OBJECT" and int(r[2]) == 16384 * 130 * 4 for r in rows), rows
