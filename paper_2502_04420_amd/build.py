@@ -85,8 +85,77 @@ def check_prefill_attention_code(asm: str) -> None:
         raise RuntimeError("kvq_prefill_attn.hip: register spills %s" % spills)
 
 
+def _vregs(text: str):
+    out = set()
+    for a, b in re.findall(r"\bv\[(\d+):(\d+)\]", text):
+        out.update(range(int(a), int(b) + 1))
+    out.update(int(a) for a in re.findall(r"\bv(\d+)\b", text))
+    return out
+
+
+def check_decode_code(asm: str) -> int:
+    """The matrix-core decode kernels issue the block loads of their streaming loop in inline assembly and wait for them
+    with hand-written counts; the compiler does not know that the destination registers are being written until the
+    wait.  The library is only linked if, in the generated code, no instruction of the compiler's own touches such a
+    register between the issue of a load and a wait that covers it.  Model: loads return in order, so after
+    `s_waitcnt vmcnt(N)` only the N youngest loads are pending.  The code is followed in layout order; a backward
+    conditional branch (a loop) is followed once more from its target with the state at the branch; the state is
+    dropped after an unconditional branch (what follows in the layout is reached from elsewhere).  Returns the number
+    of hand-issued loads seen."""
+    seen = 0
+    for name, body in kernel_bodies(asm, "decode_mfma"):
+        lines = body.split("\n")
+        labels = {}
+        for i, l in enumerate(lines):
+            m = re.match(r"^(\.LBB\d+_\d+):", l)
+            if m:
+                labels[m.group(1)] = i
+
+        def run(start, stop, pending, follow):
+            nonlocal seen
+            in_asm = False
+            i = start
+            while i < stop:
+                t = lines[i].strip()
+                i += 1
+                if t.startswith(";;#ASMSTART"):
+                    in_asm = True
+                    continue
+                if t.startswith(";;#ASMEND"):
+                    in_asm = False
+                    continue
+                if not t or t[0] in ";." or t.endswith(":"):
+                    continue
+                w = re.match(r"s_waitcnt\b.*vmcnt\((\d+)\)", t)
+                if w:
+                    n = int(w.group(1))
+                    pending = pending[len(pending) - n:] if n else []
+                    continue
+                if in_asm:
+                    if t.startswith("buffer_load"):
+                        pending = pending + [_vregs(t.split(",")[0])]
+                        if follow:
+                            seen += 1
+                    continue
+                used = _vregs(t)
+                for regs in pending:
+                    if used & regs:
+                        raise RuntimeError("%s: `%s` touches v%s while a hand-issued load may still be writing it"
+                                           % (name, t, sorted(used & regs)))
+                b = re.match(r"s_cbranch_\w+\s+(\.LBB\d+_\d+)", t)
+                if b and follow and labels.get(b.group(1), i) < i - 1:
+                    run(labels[b.group(1)], i - 1, list(pending), False)       # the loop once more, entered with this state
+                if t.startswith("s_branch") or t.startswith("s_endpgm"):
+                    pending = []
+
+        run(0, len(lines), [], True)
+    return seen
+
+
 def _check_generated_code() -> None:
     check_prefill_attention_code(device_assembly("kvq_prefill_attn.hip"))
+    if check_decode_code(device_assembly("kvq_decode_mfma.hip")) == 0:
+        raise RuntimeError("kvq_decode_mfma.hip: no hand-issued loads found in the generated code")
 
 
 def build(verbose: bool = True) -> str:

@@ -33,6 +33,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void wave_lds_sync()
 {
@@ -60,21 +61,31 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_b
 // log2 of the divisor of the code in the base position: operand element = code * 2^-CodeShift
 template <int BITS> struct CodeShift { static constexpr int value = BITS == 2 ? 20 : 24; };
 
+// one 32-token block of quantized keys / values as loaded by this lane
 template <int BITS>
-__device__ __forceinline__ half8 codes_operand(const uint32_t *dw, int m)
+struct CodeRegs {
+    u32x4 q[BITS < 16 ? BITS / 2 : 1];       // the lane's 64 codes, 16 bytes per load
+    u32x2 s2;                                // two fp32 scales.  keys: channels 2*lane, +1; values: group lane>>4, tokens 2*(lane&15), +1
+    uint32_t s1;                             // the same two scales as an fp16 pair (narrow metadata)
+    uint32_t z;                              // zero-points of the same two elements, fp16 pair
+    __device__ __forceinline__ uint32_t dw(int k) const { return q[k >> 2][k & 3]; }
+};
+
+template <int BITS>
+__device__ __forceinline__ half8 codes_operand(const CodeRegs<BITS> &r, int m)
 {
     if constexpr (BITS == 8) {
         // bytes (b0, b1), (b2, b3) -> halves 0x0000 | b : b * 2^-24
-        const uint32_t w0 = dw[2 * m], w1 = dw[2 * m + 1];
+        const uint32_t w0 = r.dw(2 * m), w1 = r.dw(2 * m + 1);
         return as_half8(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u), __builtin_amdgcn_perm(0u, w0, 0x0C030C02u),
                         __builtin_amdgcn_perm(0u, w1, 0x0C010C00u), __builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
     } else if constexpr (BITS == 4) {
         // nibbles (k, k + 4) of the dword form a pair; mantissa bits 3:0 read c * 2^-24, bits 7:4 read 16 c * 2^-24
-        const uint32_t x = dw[m], y = x >> 8;
+        const uint32_t x = r.dw(m), y = x >> 8;
         return as_half8(x & 0x000F000Fu, x & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
     } else {
         // 2-bit fields at mantissa bits 5:4 (c * 2^-20) or 7:6 (4 c * 2^-20), alternating
-        const uint32_t x = dw[m >> 1], lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
+        const uint32_t x = r.dw(m >> 1), lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
         return as_half8(lo & 0x00300030u, lo & 0x00C000C0u, hi & 0x00300030u, hi & 0x00C000C0u);
     }
 }
@@ -99,51 +110,145 @@ __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uin
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d0, d1));
 }
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// The packed blocks of one tensor of one (batch, kv head) cache, addressed through buffer resources: a load's address
+// is resource base + scalar byte offset of the block + a per-lane offset that never changes, so no vector register
+// holds an address.
+//
+// The block loads of the streaming loop are issued and awaited by hand (issue_block / await_block).  The loop keeps
+// one or two blocks in flight behind the one it works on, and what it must wait for is exactly "all but the loads of
+// the younger blocks".  Left to the compiler, the wait counts of a loop whose loads stay in flight across the back
+// edge came out far too low (all but one to three loads instead of all but eight to ten), the registers of the stage
+// about to be loaded were re-used for address arithmetic, which added waits in front of the issue, and a one-word
+// load per block was converted to a scalar where it was issued: every iteration cost one full memory round trip.
+// The compiler does not know that these loads exist: its own waits (for loads it knows of) can only come out longer
+// than needed, never shorter, and the registers a load writes are tied to the asm statements as read-write operands
+// from the issue to the wait, so nothing else is put into them in between.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// one 32-token block of quantized keys / values as loaded by this lane
-template <int BITS>
-struct CodeRegs {
-    uint32_t dw[BITS < 16 ? 2 * BITS : 1];   // the lane's 64 codes
-    uint2 sraw;                              // scales as loaded (two fp32, or one fp16 pair in .x). keys: channels 2*lane, +1;
-                                             // values: group lane>>4, tokens 2*(lane&15), +1
-    uint32_t z;                              // zero-points of the same two elements, fp16 pair
-    uint32_t bexp;                           // exponents of the block's largest key scale (low half) / value scale (high half)
+struct BlockStream {
+    i32x4 code, meta;                        // buffer resources: base, no stride, no bounds, 32-bit raw format
+    i32x4 bexp;                              // exponent words of this cache only (reads beyond it return zero)
+    uint32_t l16, l8, l4;                    // this lane's byte offsets into 16-, 8- and 4-byte-per-lane pieces
 };
 
-// NARROW: the block's scales are stored as fp16 (and were used that way by the encoder)
-template <int BITS, bool NARROW>
-__device__ __forceinline__ void load_codes(const uint8_t *code, const float *meta, const uint32_t *bexp, size_t blk_index,
-                                           int lane, CodeRegs<BITS> &r)
+// A resource of zero bytes: every load through it is out of range, touches no memory and returns zero.  The loop
+// issues its loads unconditionally (so that the number of loads behind a block is a constant); past the end of the
+// group's range they go through this resource.
+__device__ __forceinline__ i32x4 null_buffer() { return i32x4{0, 0, 0, 0x00020000}; }
+__device__ __forceinline__ i32x4 pick(bool real, const i32x4 &r)
 {
-    // Codes and metadata are read once per call and never again before the whole cache has streamed by: the loads
-    // carry the non-temporal hint, so the lines are not kept in the caches at the expense of anything else
-    // (measured: 2-7 % shorter calls, most for the 8-bit pair).
-    r.bexp = bexp[blk_index];
-    if constexpr (BITS < 16) {
-        const uint8_t *blk = code + blk_index * block_code_bytes(BITS);
-#pragma unroll
-        for (int c = 0; c < BITS / 2; c++) {
-            const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(blk + c * 1024 + lane * 16));
-            r.dw[4 * c] = x.x; r.dw[4 * c + 1] = x.y; r.dw[4 * c + 2] = x.z; r.dw[4 * c + 3] = x.w;
-        }
-        const float *m = meta + blk_index * meta_words(NARROW);
-        if constexpr (NARROW) {
-            r.sraw.x = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(meta_scales16(m) + 2 * lane));
-        } else {
-            const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(m + 2 * lane));
-            r.sraw = make_uint2(t.x, t.y);
-        }
-        r.z = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(meta_zeros(m, NARROW) + 2 * lane));
+    const i32x4 z = null_buffer();
+    return i32x4{real ? r[0] : z[0], real ? r[1] : z[1], real ? r[2] : z[2], real ? r[3] : z[3]};
+}
+
+__device__ __forceinline__ i32x4 buffer_words(const void *base, int bytes = 0x7fffffff)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(base);
+    return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)v), __builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32) & 0xffff),
+                 bytes, 0x00020000};
+}
+
+// streams of the keys (values = false) or values of the cache whose first block is number blk0 of the layer
+__device__ __forceinline__ BlockStream block_stream(const LayerView &lv, bool values, size_t blk0, int n_cache_blocks, int lane, bool narrow)
+{
+    BlockStream S;
+    const int bits = values ? lv.vbits : lv.kbits;
+    S.code = buffer_words((values ? lv.vcode : lv.kcode) + blk0 * block_code_bytes(bits));
+    S.meta = buffer_words((values ? lv.vmeta : lv.kmeta) + blk0 * meta_words(narrow));
+    S.bexp = buffer_words(lv.bexp + blk0, n_cache_blocks * 4);
+    S.l4 = (uint32_t)lane * 4u; S.l8 = (uint32_t)lane * 8u; S.l16 = (uint32_t)lane * 16u;
+    return S;
+}
+
+// The exponent words (largest key scale / largest value scale of a block, see the quantize kernel) of the blocks that
+// kChunk consecutive steps of the sweep visit, one per lane.  A block's word is read from the register with a lane
+// index, so the block pipeline holds no load whose result a scalar computation waits for.  Loaded once per chunk of
+// the sweep (issued by hand like the block loads; the first one ahead of the first blocks, later ones with a full
+// wait, once per kChunk blocks).  Lanes whose block lies beyond the cache read zero.
+constexpr int kChunk = 60;                   // steps per chunk: a multiple of both stage counts, at most 64
+
+// voff: byte offset of this lane's word in the cache's exponent array
+__device__ __forceinline__ void issue_exponents(uint32_t &words, const BlockStream &S, uint32_t voff)
+{
+    asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "+v"(words) : "v"(voff), "s"(S.bexp));
+}
+template <int N>
+__device__ __forceinline__ void await_exponents(uint32_t &words)
+{
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(words) : "n"(N));
+}
+
+// loads of one block per lane
+template <int BITS> constexpr int block_loads() { return BITS < 16 ? BITS / 2 + 2 : 0; }
+
+// Issue the loads of block `blk` of the cache (counted from the cache's first block) into r.  NARROW: the block's
+// scales are stored as fp16 (and were used that way by the encoder).  Codes and metadata are read once per call and
+// never again before the whole cache has streamed by: the loads carry the non-temporal hint, so the lines are not
+// kept in the caches at the expense of anything else (measured: 2-7 % shorter calls, most for the 8-bit pair).
+template <int BITS, bool NARROW>
+__device__ __forceinline__ void issue_block(const BlockStream &S0, bool real, int blk, CodeRegs<BITS> &r)
+{
+    static_assert(BITS < 16, "packed blocks only");
+    struct { i32x4 code, meta; uint32_t l16, l8, l4; } S = {pick(real, S0.code), pick(real, S0.meta), S0.l16, S0.l8, S0.l4};
+    const int coff = blk * block_code_bytes(BITS), moff = blk * 4 * meta_words(NARROW);
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen nt" : "+v"(r.q[0]) : "v"(S.l16), "s"(S.code), "s"(coff));
+    if constexpr (BITS >= 4) asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen offset:1024 nt" : "+v"(r.q[BITS >= 4 ? 1 : 0]) : "v"(S.l16), "s"(S.code), "s"(coff));
+    if constexpr (BITS == 8) {
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen offset:2048 nt" : "+v"(r.q[BITS == 8 ? 2 : 0]) : "v"(S.l16), "s"(S.code), "s"(coff));
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen offset:3072 nt" : "+v"(r.q[BITS == 8 ? 3 : 0]) : "v"(S.l16), "s"(S.code), "s"(coff));
     }
+    if constexpr (NARROW) {
+        asm volatile("buffer_load_dword %0, %1, %2, %3 offen nt" : "+v"(r.s1) : "v"(S.l4), "s"(S.meta), "s"(moff));
+        asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:256 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
+    } else {
+        asm volatile("buffer_load_dwordx2 %0, %1, %2, %3 offen nt" : "+v"(r.s2) : "v"(S.l8), "s"(S.meta), "s"(moff));
+        asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:512 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
+    }
+}
+
+// Wait until at most N vector memory operations of this wave are outstanding; r's registers are operands, so every
+// use of the block comes after the wait.
+template <int N, int BITS>
+__device__ __forceinline__ void await_loads(CodeRegs<BITS> &r)
+{
+    if constexpr (BITS == 8)
+        asm volatile("s_waitcnt vmcnt(%7)" : "+v"(r.q[0]), "+v"(r.q[BITS == 8 ? 1 : 0]), "+v"(r.q[BITS == 8 ? 2 : 0]), "+v"(r.q[BITS == 8 ? 3 : 0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z) : "n"(N));
+    else if constexpr (BITS == 4)
+        asm volatile("s_waitcnt vmcnt(%5)" : "+v"(r.q[0]), "+v"(r.q[BITS == 4 ? 1 : 0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z) : "n"(N));
+    else
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(r.q[0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z) : "n"(N));
+}
+
+// Block r is needed; the loads of DEPTH - 1 blocks were issued after its own (real ones or empty ones).
+template <int BITS, int DEPTH>
+__device__ __forceinline__ void await_block(CodeRegs<BITS> &r)
+{
+    await_loads<(DEPTH - 1) * block_loads<BITS>(), BITS>(r);
+}
+
+// a block outside the streaming loop: issue and wait for everything
+template <int BITS, bool NARROW>
+__device__ __forceinline__ void load_block_now(const BlockStream &S, int blk, CodeRegs<BITS> &r)
+{
+    issue_block<BITS, NARROW>(S, true, blk, r);
+    await_loads<0, BITS>(r);
+}
+
+template <int BITS>
+__device__ __forceinline__ void clear_regs(CodeRegs<BITS> &r)
+{
+#pragma unroll
+    for (int c = 0; c < (BITS < 16 ? BITS / 2 : 1); c++) r.q[c] = u32x4{0u, 0u, 0u, 0u};
+    r.s2 = u32x2{0u, 0u}; r.s1 = 0u; r.z = 0u;
 }
 
 // the two scales of a loaded block as floats
 template <bool NARROW, int BITS>
 __device__ __forceinline__ float2 scales_of(const CodeRegs<BITS> &r)
 {
-    if constexpr (NARROW) return make_float2(half_lo(r.sraw.x), half_hi(r.sraw.x));
-    return make_float2(__builtin_bit_cast(float, r.sraw.x), __builtin_bit_cast(float, r.sraw.y));
+    if constexpr (NARROW) return make_float2(half_lo(r.s1), half_hi(r.s1));
+    const uint32_t x = r.s2[0], y = r.s2[1];       // (a bit cast applied to a vector element directly reads element 0)
+    return make_float2(__builtin_bit_cast(float, x), __builtin_bit_cast(float, y));
 }
 
 // max over the 16 lanes of a DPP row (lanes that share lane >> 4), result in every lane
@@ -211,12 +316,12 @@ struct ValueState {
 
 // scores of a quantized block: s[th][hh] for head 2*rq + hh, tokens 16*th + n
 template <int KB, int GQ, bool NARROW>
-__device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
+__device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, uint32_t bexp, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
                                               float (&s)[2][2])
 {
     const int n = lane & 15, rq = lane >> 4;
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
-    const int ek = (int)(blk.bexp & 0xffffu) - 32768;
+    const int ek = (int)(bexp & 0xffffu) - 32768;
     const float2 sc = scales_of<NARROW>(blk);
     const float ks0 = ldexpf(sc.x, 14 - ek), ks1 = ldexpf(sc.y, 14 - ek);
     const float ah = ldexpf(Q.alpha_h, ek - 14);
@@ -234,8 +339,8 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, const Que
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
         const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
-        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb), S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb), S1, 0, 0, 0);
+        S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, cb), S0, 0, 0, 0);
+        S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, 4 + cb), S1, 0, 0, 0);
         Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
     }
     // this lane holds rows 4*rq + i: (high, low) of head 2*rq and (high, low) of head 2*rq + 1
@@ -266,8 +371,8 @@ __device__ __forceinline__ void scores_packed_per_token(const CodeRegs<KB> &blk,
 #pragma unroll
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
-        const float4v D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, cb), zero, 0, 0, 0);
-        const float4v D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk.dw, 4 + cb), zero, 0, 0, 0);
+        const float4v D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, cb), zero, 0, 0, 0);
+        const float4v D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, 4 + cb), zero, 0, 0, 0);
         const float s0 = L.Mk[0][32 * cb + n], s1 = L.Mk[0][32 * cb + 16 + n];
         const float z0 = L.Mk[1][32 * cb + n], z1 = L.Mk[1][32 * cb + 16 + n];
 #pragma unroll
@@ -355,12 +460,12 @@ __device__ __forceinline__ void apply_rescale(ValueState<GQ> &W, const PairLds<G
 
 // output contribution of a quantized block
 template <int VB, int GQ, bool NARROW>
-__device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const QueryRegs<GQ> &Q, ValueState<GQ> &W,
+__device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, uint32_t bexp, const QueryRegs<GQ> &Q, ValueState<GQ> &W,
                                               PairLds<GQ> &L, int buf, int lane)
 {
     const int n = lane & 15, rq = lane >> 4;
     // keep p*s at the top of the fp16 range; when a block brings a larger scale, re-base the accumulators (exact)
-    const int ev = (int)(blk.bexp >> 16) - 32768;
+    const int ev = (int)(bexp >> 16) - 32768;
     if (ev > W.ev) {
 #pragma unroll
         for (int cblk = 0; cblk < 8; cblk++)
@@ -386,7 +491,7 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, const Que
 #pragma unroll
         for (int c2 = 0; c2 < 2; c2++) {
             const int cblk = 2 * gd + c2;
-            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk.dw, cblk), W.O[cblk], 0, 0, 0);
+            W.O[cblk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<VB>(blk, cblk), W.O[cblk], 0, 0, 0);
         }
     }
 }
@@ -428,9 +533,11 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 {
     static_assert(GQ == 4 || GQ == 8, "rows 2j and 2j + 1 of a 16-row tile");
     constexpr bool kFast = KB < 16 && VB < 16;
-    // register stages of the phase-1 pipelines (units in flight per wave = stages - 1)
-    constexpr int DK = KB <= 4 ? 3 : 2;
-    constexpr int DV = VB <= 4 ? 3 : 2;
+    // register stages of the phase-1 pipelines (blocks in flight per wave = stages - 1)
+    // One block in flight behind the one being worked on (measured with exact wait counts, batch 16..32, 8K..32K
+    // tokens: two or three blocks behind are 3-5 % slower for 4- and 2-bit codes and no faster for 8-bit ones: the
+    // memory system is the queue here, more requests in it only wait longer).
+    constexpr int DK = 2, DV = 2;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform on purpose: block indices stay scalar
     const int n = lane & 15, rq = lane >> 4;
@@ -455,15 +562,21 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     const int f1 = kFast ? (u1 < a.n_blocks ? u1 : a.n_blocks) : u0;     // phase 1 = [u0, f1), phase 2 = [f1, u1)
     const int f1c = f1 > u0 ? f1 : u0;
     const int n1 = f1c - u0, n2 = u1 - f1c;
-    const size_t blk0 = (size_t)bh * a.NB;
-    // block index of the i-th phase-1 unit, clamped so that prefetches never leave the range
+    const size_t blk0 = (size_t)bh * a.NB;       // first block of this cache in the layer's arrays
+    // cache block number of the i-th phase-1 unit (0 <= i < n1).
     // Every group starts its sweep at a different place of its range and wraps around: groups advance at the
     // same pace, and with equal phases their addresses would keep falling on the same memory channels.
     const int rot = n1 > 0 ? (int)(((uint32_t)bh * 40503u + (uint32_t)split * 9973u) % (uint32_t)n1) : 0;
     auto blk1 = [&](int i) {
-        const int last = n1 > 0 ? n1 - 1 : 0;
-        const int r = (i < last ? i : last) + rot;
-        return blk0 + (size_t)(u0 + (r < n1 ? r : r - n1));
+        const int r = i + rot;
+        return u0 + (r < n1 ? r : r - n1);
+    };
+    auto blk1c = [&](int i) { return i < n1 ? blk1(i) : 0; };     // past the range: any number, the load is an empty one
+    // byte offset, in the cache's exponent array, of the word this lane holds for the chunk that starts at step c0
+    auto exp_offset = [&](int c0) {
+        const int i = c0 + lane;
+        const int r = i + rot - (i + rot >= n1 ? n1 : 0);
+        return (uint32_t)((i < n1 ? u0 + r : a.n_blocks) * 4);     // beyond the range: beyond the array, reads zero
     };
 
     QueryRegs<GQ> Q;
@@ -479,12 +592,15 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             qw[j] = 0;
             if (j < nvalid) qw[j] = *reinterpret_cast<const uint32_t *>(a.q + (qrow0 + j) * kD + 2 * lane);
         }
+        const BlockStream KS = block_stream(a.lv, false, blk0, a.n_blocks, lane, NARROW);
+        uint32_t kexp = 0;                               // exponent words of the chunk's blocks, one per lane
         CodeRegs<KB> kr[DK];
         if constexpr (kFast) {
-            if (n1 > 0) {
 #pragma unroll
-                for (int d = 0; d < DK - 1; d++) load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(d), lane, kr[d]);
-            }
+            for (int d = 0; d < DK; d++) clear_regs(kr[d]);
+            issue_exponents(kexp, KS, exp_offset(0));
+#pragma unroll
+            for (int d = 0; d < DK - 1; d++) issue_block<KB, NARROW>(KS, d < n1, blk1c(d), kr[d]);
         }
         {
             // queries divided by a power of two that brings the largest to [0.5, 1).  Per-channel keys: with the softmax
@@ -549,22 +665,36 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         for (int i = 0; i < 2; i++) { W.m[i] = -INFINITY; W.l[i] = 0.0f; }
         float s[2][2];
         if constexpr (kFast) {
-            // DK register stages in rotation: stage d is consumed while the loads of the next DK - 1 units are in
-            // flight.  Every stage is loaded unconditionally (the index is clamped), so the wait counts stay exact.
-            bool more = n1 > 0;
-            for (int i = 0; more;) {
+            // DK register stages in rotation: stage d is consumed while the loads of the next DK - 1 units (as far as
+            // there are any) are in flight.
+            // The sweep goes in chunks of kChunk steps (one register of exponent words each); a chunk starts at stage 0.
+            await_exponents<(DK - 1) * block_loads<KB>()>(kexp);           // the first chunk's: issued ahead of the first blocks
+            for (int c0 = 0; c0 < n1; c0 += kChunk) {
+                if (c0 > 0) {
+                    issue_exponents(kexp, KS, exp_offset(c0));
+                    await_exponents<0>(kexp);
+                }
+                const int cend = c0 + kChunk < n1 ? c0 + kChunk : n1;
+                bool more = true;
+                for (int i = c0; more;) {
 #pragma unroll
-                for (int d = 0; d < DK; d++) {
-                    if (more) {
-                        load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk1(i + DK - 1), lane, kr[(d + DK - 1) % DK]);
-                        if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
-                        else scores_packed<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
-                        softmax_publish<GQ>(s, W, L, i & 1, lane);
-                        wg_barrier();
-                        more = ++i < n1;
+                    for (int d = 0; d < DK; d++) {
+                        if (more) {
+                            issue_block<KB, NARROW>(KS, i + DK - 1 < n1, blk1c(i + DK - 1), kr[(d + DK - 1) % DK]);
+                            await_block<KB, DK>(kr[d]);
+                            const uint32_t ew = (uint32_t)__builtin_amdgcn_readlane((int)kexp, i - c0);
+                            if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
+                            else scores_packed<KB, GQ, NARROW>(kr[d], ew, Q, L, lane, s);
+                            softmax_publish<GQ>(s, W, L, i & 1, lane);
+                            wg_barrier();
+                            more = ++i < cend;
+                        }
                     }
                 }
             }
+#pragma unroll
+            for (int d = 0; d < DK; d++) await_loads<0, KB>(kr[d]);      // the empty loads past the end of the range, before
+            await_exponents<0>(kexp);                                    // their registers go back to the compiler
         }
         for (int i = 0; i < n2; i++) {
             const int u = f1c + i;
@@ -575,9 +705,10 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             if constexpr (KB < 16) if (packed) {
                 k_rows = false;
                 CodeRegs<KB> r;
-                load_codes<KB, NARROW>(a.lv.kcode, a.lv.kmeta, a.lv.bexp, blk0 + u, lane, r);
+                clear_regs(r);
+                load_block_now<KB, NARROW>(KS, u, r);
                 if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(r, Q, L, lane, s);
-                else scores_packed<KB, GQ, NARROW>(r, Q, L, lane, s);
+                else scores_packed<KB, GQ, NARROW>(r, a.lv.bexp[blk0 + u], Q, L, lane, s);
             }
             if (k_rows) {
                 const uint16_t *kbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.kcode) + (size_t)bh * a.NB * kG * kD
@@ -619,12 +750,15 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             qx[pass] = make_uint4(0, 0, 0, 0);
             if (jr < nvalid) qx[pass] = *reinterpret_cast<const uint4 *>(a.q + (qrow0 + jr) * kD + 8 * n);
         }
+        const BlockStream VS = block_stream(a.lv, true, blk0, a.n_blocks, lane, NARROW);
+        uint32_t vexp = 0;
         CodeRegs<VB> vr[DV];
         if constexpr (kFast) {
-            if (n1 > 0) {
 #pragma unroll
-                for (int d = 0; d < DV - 1; d++) load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(d), lane, vr[d]);
-            }
+            for (int d = 0; d < DV; d++) clear_regs(vr[d]);
+            issue_exponents(vexp, VS, exp_offset(0));
+#pragma unroll
+            for (int d = 0; d < DV - 1; d++) issue_block<VB, NARROW>(VS, d < n1, blk1c(d), vr[d]);
         }
 #pragma unroll
         for (int pass = 0; pass < 4; pass++) *reinterpret_cast<uint4 *>(&aq_lds[4 * pass + rq][8 * n]) = qx[pass];
@@ -644,23 +778,36 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         W.ev = -100;
         wg_barrier();                                   // the key wave has produced the first unit
         if constexpr (kFast) {
-            bool more = n1 > 0;
-            for (int i = 0; more;) {
+            await_exponents<(DV - 1) * block_loads<VB>()>(vexp);
+            for (int c0 = 0; c0 < n1; c0 += kChunk) {
+                if (c0 > 0) {
+                    issue_exponents(vexp, VS, exp_offset(c0));
+                    await_exponents<0>(vexp);
+                }
+                const int cend = c0 + kChunk < n1 ? c0 + kChunk : n1;
+                bool more = true;
+                for (int i = c0; more;) {
 #pragma unroll
-                for (int d = 0; d < DV; d++) {
-                    if (more) {
-                        load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk1(i + DV - 1), lane, vr[(d + DV - 1) % DV]);
-                        // (always true here; as a run-time test it keeps the rarely taken re-base and rescale
-                        // paths out of line, without it the register count of the loop grows by half)
-                        if (i < n1) {
-                            apply_rescale<GQ>(W, L, i & 1, lane);
-                            output_packed<VB, GQ, NARROW>(vr[d], Q, W, L, i & 1, lane);
+                    for (int d = 0; d < DV; d++) {
+                        if (more) {
+                            issue_block<VB, NARROW>(VS, i + DV - 1 < n1, blk1c(i + DV - 1), vr[(d + DV - 1) % DV]);
+                            await_block<VB, DV>(vr[d]);
+                            const uint32_t ew = (uint32_t)__builtin_amdgcn_readlane((int)vexp, i - c0);
+                            // (always true here; as a run-time test it keeps the rarely taken re-base and rescale
+                            // paths out of line, without it the register count of the loop grows by half)
+                            if (i < n1) {
+                                apply_rescale<GQ>(W, L, i & 1, lane);
+                                output_packed<VB, GQ, NARROW>(vr[d], ew, Q, W, L, i & 1, lane);
+                            }
+                            wg_barrier();
+                            more = ++i < cend;
                         }
-                        wg_barrier();
-                        more = ++i < n1;
                     }
                 }
             }
+#pragma unroll
+            for (int d = 0; d < DV; d++) await_loads<0, VB>(vr[d]);
+            await_exponents<0>(vexp);
         }
         for (int i = 0; i < n2; i++) {
             const int u = f1c + i, buf = (n1 + i) & 1;
@@ -672,8 +819,9 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             if constexpr (VB < 16) if (packed) {
                 v_rows = false;
                 CodeRegs<VB> r;
-                load_codes<VB, NARROW>(a.lv.vcode, a.lv.vmeta, a.lv.bexp, blk0 + u, lane, r);
-                output_packed<VB, GQ, NARROW>(r, Q, W, L, buf, lane);
+                clear_regs(r);
+                load_block_now<VB, NARROW>(VS, u, r);
+                output_packed<VB, GQ, NARROW>(r, a.lv.bexp[blk0 + u], Q, W, L, buf, lane);
             }
             if (v_rows) {
                 const uint16_t *vbase = packed ? reinterpret_cast<const uint16_t *>(a.lv.vcode) + (size_t)bh * a.NB * kG * kD

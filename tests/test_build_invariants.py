@@ -81,3 +81,22 @@ def test_builtin_scratch_array_is_visible_to_the_loader():
     rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch")]
     assert rows, "no scratch symbol in the device code object"
     assert all(r[4] == "GLOBAL" and r[3] == "OBJECT" and int(r[2]) == 16384 * 130 * 4 for r in rows), rows
+
+
+def test_decode_kernels_leave_hand_issued_loads_alone():
+    """The matrix-core decode kernels issue their block loads in inline assembly and wait for them with hand-written
+    counts.  The build refuses a library in whose generated code an instruction of the compiler's own touches a
+    register such a load may still be writing: the same check, run here on one instantiation, and shown not to be
+    vacuous by planting a copy of an in-flight register."""
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    from paper_2502_04420_amd import build as B
+
+    asm = B.device_assembly("kvq_decode_mfma.hip")
+    assert B.check_decode_code(asm) > 1000                               # every instantiation streams through these loads
+    name, body = [kb for kb in B.kernel_bodies(asm, "decode_mfma") if "ILi4ELi2ELi4ELb0ELb0E" in kb[0]][0]
+    m = re.search(r"buffer_load_dwordx4 (v\[(\d+):\d+\]), [^\n]*\n\s*;;#ASMEND\n", body)
+    assert m
+    planted = body[:m.end()] + "\tv_mov_b32_e32 v200, v%s\n" % m.group(2) + body[m.end():]
+    with pytest.raises(RuntimeError):
+        B.check_decode_code(asm.replace(body, planted, 1))
