@@ -59,7 +59,7 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_b
 // below it, the same as for a normal operand 1 + code * 2^-10, without a "1 +" to remove.)
 
 // log2 of the divisor of the code in the base position: operand element = code * 2^-CodeShift
-template <int BITS> struct CodeShift { static constexpr int value = BITS == 2 ? 20 : 24; };
+template <int BITS> struct CodeShift { static constexpr int value = 24; };
 
 // one 32-token block of quantized keys / values as loaded by this lane
 template <int BITS>
@@ -84,9 +84,10 @@ __device__ __forceinline__ half8 codes_operand(const CodeRegs<BITS> &r, int m)
         const uint32_t x = r.dw(m), y = x >> 8;
         return as_half8(x & 0x000F000Fu, x & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
     } else {
-        // 2-bit fields at mantissa bits 5:4 (c * 2^-20) or 7:6 (4 c * 2^-20), alternating
-        const uint32_t x = r.dw(m >> 1), lo = (m & 1) ? x >> 4 : x << 4, hi = (m & 1) ? x >> 8 : x;
-        return as_half8(lo & 0x00300030u, lo & 0x00C000C0u, hi & 0x00300030u, hi & 0x00C000C0u);
+        // the four 2-bit fields of a byte pair are masked where they sit: mantissa bits 1:0, 3:2, 5:4, 7:6 read
+        // c, 4 c, 16 c, 64 c (* 2^-24); the upper byte pair of the dword comes down with one shift
+        const uint32_t x = (m & 1) ? r.dw(m >> 1) >> 8 : r.dw(m >> 1);
+        return as_half8(x & 0x00030003u, x & 0x000C000Cu, x & 0x00300030u, x & 0x00C000C0u);
     }
 }
 
@@ -96,7 +97,7 @@ template <int BITS>
 __device__ __forceinline__ float code_weight_inv(int e)
 {
     if (BITS == 4) return ((e >> 1) & 1) ? 0.0625f : 1.0f;
-    if (BITS == 2) return ((e >> 1) & 1) ? 0.25f : 1.0f;
+    if (BITS == 2) return 1.0f / (float)(1 << (2 * ((e >> 1) & 3)));
     return 1.0f;
 }
 
@@ -106,6 +107,19 @@ __device__ __forceinline__ void split_pair(float r0, float r1, uint32_t &hi, uin
 {
     const half2v h = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(r0, r1));
     const float d0 = r0 - (float)h[0], d1 = r1 - (float)h[1];
+    hi = __builtin_bit_cast(uint32_t, h);
+    lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d0, d1));
+}
+
+// The same for two products a0 b0, a1 b1 whose factors are also at hand rounded to fp16 (a16, b16: pairs).  The
+// high parts are the packed fp16 product of the rounded factors (one instruction for both; off the true product by
+// less than 2^-9 of it), the low parts what is missing from the true products, each one mixed-precision
+// multiply-add.  hi + lo = a b to about 2^-20: four instructions instead of six.
+__device__ __forceinline__ void split_products(float a0, float b0, float a1, float b1, uint32_t a16, uint32_t b16,
+                                               uint32_t &hi, uint32_t &lo)
+{
+    const half2v h = __builtin_bit_cast(half2v, a16) * __builtin_bit_cast(half2v, b16);
+    const float d0 = __builtin_fmaf(a0, b0, -(float)h[0]), d1 = __builtin_fmaf(a1, b1, -(float)h[1]);
     hi = __builtin_bit_cast(uint32_t, h);
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d0, d1));
 }
@@ -292,6 +306,8 @@ struct __attribute__((aligned(16))) PairLds {
 template <int GQ>
 struct QueryRegs {
     float q2[GQ][2];               // scaled queries for channels 2*lane, 2*lane+1 (for q * s)
+    uint32_t q16[GQ];              // the same pair rounded to fp16
+    int nvalid;                    // heads of this tile that exist (the A-tile rows of the others stay zero)
     const _Float16 *Aq;            // LDS: exact fp16 queries as an A tile [16][kD + 8] (rows 2j and 2j + 1 = head j)
     float c, alpha_h;              // log2(e)/sqrt(D); weight of the partial scores
     float vw0, vw1;                // bit-position weights of tokens 2n, 2n+1 in the value codes
@@ -325,10 +341,12 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, uint32_t 
     const float2 sc = scales_of<NARROW>(blk);
     const float ks0 = ldexpf(sc.x, 14 - ek), ks1 = ldexpf(sc.y, 14 - ek);
     const float ah = ldexpf(Q.alpha_h, ek - 14);
+    const uint32_t ks16 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ks0, ks1));
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
+        if (j >= 4 && j >= Q.nvalid) continue;           // (a tile of 8 holds at least 5 heads)
         uint32_t hi, lo;
-        split_pair(Q.q2[j][0] * ks0, Q.q2[j][1] * ks1, hi, lo);
+        split_products(Q.q2[j][0], ks0, Q.q2[j][1], ks1, Q.q16[j], ks16, hi, lo);
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j][2 * lane]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j + 1][2 * lane]) = lo;
     }
@@ -475,11 +493,13 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, uint32_t 
     }
     const float2 sc = scales_of<NARROW>(blk);
     const float sv0 = ldexpf(sc.x * Q.vw0, 14 - W.ev), sv1 = ldexpf(sc.y * Q.vw1, 14 - W.ev);
+    const uint32_t sv16 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(sv0, sv1));
 #pragma unroll
     for (int j = 0; j < GQ; j++) {
+        if (j >= 4 && j >= Q.nvalid) continue;
         const float2 pp = *reinterpret_cast<const float2 *>(&L.P[buf][j][2 * n]);
         uint32_t hi, lo;
-        split_pair(pp.x * sv0, pp.y * sv1, hi, lo);
+        split_products(pp.x, sv0, pp.y, sv1, __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pp.x, pp.y)), sv16, hi, lo);
         *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j][2 * n]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j + 1][2 * n]) = lo;
         W.accz[j] = fmaf(pp.x, half_lo(blk.z), fmaf(pp.y, half_hi(blk.z), W.accz[j]));
@@ -580,6 +600,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
     };
 
     QueryRegs<GQ> Q;
+    Q.nvalid = nvalid;
     Q.c = a.scale_log2e;
     Q.Aq = &aq_lds[0][0];
 
@@ -651,12 +672,14 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
                 for (int j = 0; j < GQ; j++) {
                     Q.q2[j][0] = ldexpf(qraw[j][0], -qexp) * w0;
                     Q.q2[j][1] = ldexpf(qraw[j][1], -qexp) * w1;
+                    Q.q16[j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(Q.q2[j][0], Q.q2[j][1]));
                 }
             }
-            if constexpr (GQ < 8) {
+            {
                 // A-tile rows of heads that do not exist are never written: they must read as zero
-                for (int i = lane; i < (16 - 2 * GQ) * (kD + 8) / 8; i += 64)
-                    reinterpret_cast<uint4 *>(&L.Ak[2 * GQ][0])[i] = make_uint4(0, 0, 0, 0);
+                const int row0 = 2 * (GQ == 8 ? nvalid : GQ);
+                for (int i = lane; i < (16 - row0) * (kD + 8) / 8; i += 64)
+                    reinterpret_cast<uint4 *>(&L.Ak[row0][0])[i] = make_uint4(0, 0, 0, 0);
             }
         }
         wg_barrier();                                   // the value wave has written the exact-fp16 query tile
@@ -762,10 +785,11 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         }
 #pragma unroll
         for (int pass = 0; pass < 4; pass++) *reinterpret_cast<uint4 *>(&aq_lds[4 * pass + rq][8 * n]) = qx[pass];
-        if constexpr (GQ < 8) {
-            constexpr int per = (16 - 2 * GQ) * (32 + 8) / 8;        // 16-byte pieces of the unused rows per channel group
+        {
+            const int row0 = 2 * (GQ == 8 ? nvalid : GQ);
+            const int per = (16 - row0) * (32 + 8) / 8;              // 16-byte pieces of the unused rows per channel group
             for (int i = lane; i < 4 * per; i += 64)
-                reinterpret_cast<uint4 *>(&L.Av[i / per][2 * GQ][0])[i % per] = make_uint4(0, 0, 0, 0);
+                reinterpret_cast<uint4 *>(&L.Av[i / per][row0][0])[i % per] = make_uint4(0, 0, 0, 0);
         }
         Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
         Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
