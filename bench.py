@@ -313,14 +313,81 @@ def cpu_baseline(W, w, budget_s=20.0):
     }
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "decode_traffic.json")
+KERNEL_SOURCES = ("kvq_decode_mfma.hip", "kvq_layout.h", "kvq_internal.h")
+
+
+def kernel_source_hash():
+    """Hash of the decode kernel's sources: a counter record taken with other sources is not this kernel's."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2502_04420_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def summary(res, w):
+    """The figures of one timed workload that the extra objects of the line carry."""
+    counts = {}
+    for l in range(w.n_layers):
+        k = "K%dV%d" % (w.kbits[l], w.vbits[l])
+        counts[k] = counts.get(k, 0) + 1
+    pairs = {}
+    for k, v in res["per_pair"].items():
+        pairs[k] = {"layers": counts[k], "kernel_us": v["kernel_ms"] * 1e3, "bytes_per_launch": v["bytes"],
+                    "kernel_gbps": v["kernel_gbps"], "frac_of_hbm_peak": v["kernel_gbps"] / HBM_PEAK_GBPS}
+    return {"workload": w.name, "tokens_per_s": res["tokens_per_s"], "ms_per_step": res["ms_per_step"],
+            "hbm_gbps": res["algorithmic_gbps"], "hbm_frac_of_peak": res["algorithmic_gbps"] / HBM_PEAK_GBPS, "per_pair": pairs}
+
+
+def extra_configs(torch, pkg, W, args):
+    """The benchmark's other single-GPU configurations, each a decode loop like the main one (fewer steps):
+    the Qwen2.5-7B shape (28 layers, 28 q / 4 kv heads, biased keys) at batch 8 and 32768 tokens with the 4.0-bit
+    schedule (even layers K8V2, odd K4V2) against uniform K8V8, and uniform K8V8 on the Llama shape at batch 16 and
+    4096 tokens."""
+    out = {}
+    wq, wq8 = W.named("qwen7b", "mix4.0", 8, 32768), W.named("qwen7b", "K8V8", 8, 32768)
+    rq = time_workload(torch, pkg, W, wq, 16, 2, args.variant, args.splits)
+    rq8 = time_workload(torch, pkg, W, wq8, 16, 2, args.variant, args.splits)
+    out["qwen7b-B8-T32768"] = dict(summary(rq, wq), steps=16, warmup=2, kv8=summary(rq8, wq8),
+                                   speedup_vs_kv8=rq["tokens_per_s"] / rq8["tokens_per_s"])
+    w2 = W.config2(16, 4096)
+    r2 = time_workload(torch, pkg, W, w2, 32, 4, args.variant, args.splits)
+    out["llama8b-B16-T4096-K8V8"] = dict(summary(r2, w2), steps=32, warmup=4)
+    return out
+
+
 def read_traffic(name):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if one exists."""
-    path = os.path.join(ROOT, "profiles", "decode_traffic.json")
+    """HBM bytes per launch of a decode kernel from the committed rocprofv3 counter record (FETCH_SIZE / WRITE_SIZE
+    runs, see profiles/), or None when there is none for this configuration or when it was taken with other kernel
+    sources than the ones in the tree (the record carries their hash)."""
     try:
-        with open(path) as f:
-            return json.load(f).get(name)
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(name)
     except (OSError, ValueError):
         return None
+    if rec is None or rec.get("kernel_sources") != kernel_source_hash():
+        return None
+    return rec
+
+
+def record_traffic(args):
+    """--record-traffic NAME FETCH_KIB WRITE_KIB FETCH_SCALE WRITE_SCALE SOURCE: store the counter means of one decode
+    kernel (per dispatch, from two rocprofv3 --pmc runs) together with the hash of the kernel sources they belong to."""
+    name, fetch_kib, write_kib, fscale, wscale, source = args
+    try:
+        with open(TRAFFIC_FILE) as f:
+            data = json.load(f)
+    except (OSError, ValueError):
+        data = {}
+    fb, wb = float(fetch_kib) * 1024.0 * float(fscale), float(write_kib) * 1024.0 * float(wscale)
+    data[name] = {"fetch_bytes": fb, "write_bytes": wb, "total_bytes": fb + wb, "source": source,
+                  "kernel_sources": kernel_source_hash(), "recorded": time.strftime("%Y-%m-%d")}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(data, f, indent=1)
+    print("recorded", name, data[name])
 
 
 def main():
@@ -350,10 +417,18 @@ def main():
     ap.add_argument("--no-prefill-attn", action="store_true",
                     help="skip the extra measurement of the prefill-stage attention kernel (one layer of the dominant pair)")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="skip the two further benchmark configurations timed after the main one: the Qwen2.5-7B shape "
+                         "(28 q / 4 kv heads, batch 8, 32768 tokens, 4.0-bit mix vs K8V8) and uniform K8V8 at 4096 tokens")
+    ap.add_argument("--record-traffic", nargs=6, metavar=("NAME", "FETCH_KIB", "WRITE_KIB", "FETCH_SCALE", "WRITE_SCALE", "SOURCE"),
+                    help="no benchmark: store rocprofv3 FETCH_SIZE / WRITE_SIZE means of a decode kernel in profiles/decode_traffic.json")
     ap.add_argument("--copy-calib", action="store_true",
                     help="first run 5 plain streaming kernels that read 1 GiB and write 1 GiB (torch.neg on fp32; "
                          "a known-size reference for hardware counters)")
     args = ap.parse_args()
+    if args.record_traffic:
+        record_traffic(args.record_traffic)
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
               file=sys.stderr)
@@ -411,8 +486,8 @@ def main():
     # HBM bytes per launch measured with the counters (fetch + write), or null when this configuration was not profiled
     detail = read_traffic(w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") + (":keys-per-token" if KEYS_PER_TOKEN else ""))
     roofline["traffic"] = detail["total_bytes"] if detail else None
-    if detail:
-        roofline["traffic_detail"] = detail
+    roofline["traffic_detail"] = detail if detail else (
+        "no counter record for this configuration taken with the kernel sources in the tree (profiles/decode_traffic.json)")
     from paper_2502_04420_amd import equivalent_precision
 
     eq_bits = equivalent_precision(w_main.kbits, w_main.vbits)
@@ -422,7 +497,8 @@ def main():
     out = {
         "metric": metric_name, "value": main_res["tokens_per_s"],
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp16 MFMA operands (codes exact, q*s and p*s as hi + lo fp16 pairs), fp32 accumulate", "data": "synthetic",
         "config": {"workload": w_main.name, "layers": w_main.n_layers, "batch": w_main.batch, "q_heads": w_main.n_q_heads,
                    "kv_heads": w_main.n_kv_heads, "head_dim": w_main.head_dim, "context": w_main.context,
                    "equivalent_bits": equivalent_precision(w_main.kbits, w_main.vbits), "group": 32, "residual": 32,
@@ -452,6 +528,8 @@ def main():
             "kv8": {"workload": w8.name, "tokens_per_s": r_kv8["tokens_per_s"], "ms_per_step": r_kv8["ms_per_step"],
                     "hbm_frac_of_peak": r_kv8["algorithmic_gbps"] / HBM_PEAK_GBPS, "per_pair": r_kv8["per_pair"]},
             "speedup_vs_kv8": r_mix["tokens_per_s"] / r_kv8["tokens_per_s"]}
+    if not args.no_extra_configs and not args.only and fam == "llama8b" and not args.schedule:
+        out["extra_configs"] = extra_configs(torch, pkg, W, args)
     if not args.no_prefill_attn and not args.only:
         dom_layers = [l for l in range(w_main.n_layers) if "K%dV%d" % (w_main.kbits[l], w_main.vbits[l]) == dom]
         out["prefill_attention"] = time_prefill_attention(

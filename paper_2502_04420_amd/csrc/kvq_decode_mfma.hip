@@ -295,10 +295,15 @@ __device__ __forceinline__ void wg_barrier()
 template <int GQ>
 struct __attribute__((aligned(16))) PairLds {
     _Float16 Ak[16][kD + 8];       // key wave: score A tiles [row][channel]
-    _Float16 Av[4][16][32 + 8];    // value wave: output A tiles [channel group][row][token]
+    // value wave: output A tiles [channel group][row][token].  A tile is 16 rows of 80 bytes plus 64 bytes: the four
+    // lane rows of a wave write the same (row, token pair) of the four tiles at once, and with this distance between
+    // the tiles (336 dwords = 16 banks more than a multiple of 64) they fall on four different quarters of the banks
+    struct AvTile { _Float16 at[16][32 + 8]; _Float16 pad[32]; } Av[4];
     _Float16 Zk[kD];               // key wave: key zero-points (fp16 as stored); per-token keys: 32 floats of query sums
     float Mk[2][kD];               // key wave, per-token keys: the block's scales and zero-points as [group][token] floats
-    float P[2][8][32];             // hand-off: softmax numerators of a block per head, double-buffered
+    // hand-off: softmax numerators of a block per head, double-buffered.  Rows of 40 floats: the four lane rows of
+    // the key wave write rows 2 rq + hh at once, 80 dwords apart = four different quarters of the banks
+    float P[2][8][32 + 8];
     float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
     int rescale[2][2];             // hand-off: non-zero when alpha is not all ones (padded to 16 bytes)
 };
@@ -500,14 +505,14 @@ __device__ __forceinline__ void output_packed(const CodeRegs<VB> &blk, uint32_t 
         const float2 pp = *reinterpret_cast<const float2 *>(&L.P[buf][j][2 * n]);
         uint32_t hi, lo;
         split_products(pp.x, sv0, pp.y, sv1, __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pp.x, pp.y)), sv16, hi, lo);
-        *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j][2 * n]) = hi;
-        *reinterpret_cast<uint32_t *>(&L.Av[rq][2 * j + 1][2 * n]) = lo;
+        *reinterpret_cast<uint32_t *>(&L.Av[rq].at[2 * j][2 * n]) = hi;
+        *reinterpret_cast<uint32_t *>(&L.Av[rq].at[2 * j + 1][2 * n]) = lo;
         W.accz[j] = fmaf(pp.x, half_lo(blk.z), fmaf(pp.y, half_hi(blk.z), W.accz[j]));
     }
     wave_lds_sync();
 #pragma unroll
     for (int gd = 0; gd < 4; gd++) {
-        const half8 Aop = *reinterpret_cast<const half8 *>(&L.Av[gd][n][8 * rq]);
+        const half8 Aop = *reinterpret_cast<const half8 *>(&L.Av[gd].at[n][8 * rq]);
 #pragma unroll
         for (int c2 = 0; c2 < 2; c2++) {
             const int cblk = 2 * gd + c2;
@@ -789,7 +794,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             const int row0 = 2 * (GQ == 8 ? nvalid : GQ);
             const int per = (16 - row0) * (32 + 8) / 8;              // 16-byte pieces of the unused rows per channel group
             for (int i = lane; i < 4 * per; i += 64)
-                reinterpret_cast<uint4 *>(&L.Av[i / per][row0][0])[i % per] = make_uint4(0, 0, 0, 0);
+                reinterpret_cast<uint4 *>(&L.Av[i / per].at[row0][0])[i % per] = make_uint4(0, 0, 0, 0);
         }
         Q.vw0 = code_weight_inv<VB < 16 ? VB : 8>((2 * n) & 7);
         Q.vw1 = code_weight_inv<VB < 16 ? VB : 8>((2 * n + 1) & 7);
@@ -863,7 +868,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         // channel 16 cblk + n, rows of heads 2 rq, 2 rq + 1) is turned into (lane = channels 2 lane, 2 lane + 1,
         // all heads) through the A-tile memory, which is no longer needed.
         static_assert(sizeof(L.Av) >= GQ * kD * sizeof(float), "output staging fits the A tiles");
-        float *o_lds = reinterpret_cast<float *>(&L.Av[0][0][0]);
+        float *o_lds = reinterpret_cast<float *>(&L.Av[0].at[0][0]);
         constexpr int vshift = CodeShift<VB < 16 ? VB : 8>::value;
         const float wO = ldexpf(1.0f, vshift + W.ev - 14);       // high and low parts carry the same weight
         wave_lds_sync();
