@@ -336,8 +336,10 @@ def summary(res, w):
         counts[k] = counts.get(k, 0) + 1
     pairs = {}
     for k, v in res["per_pair"].items():
+        rec = read_traffic(w.name + ":" + k)
         pairs[k] = {"layers": counts[k], "kernel_us": v["kernel_ms"] * 1e3, "bytes_per_launch": v["bytes"],
-                    "kernel_gbps": v["kernel_gbps"], "frac_of_hbm_peak": v["kernel_gbps"] / HBM_PEAK_GBPS}
+                    "kernel_gbps": v["kernel_gbps"], "frac_of_hbm_peak": v["kernel_gbps"] / HBM_PEAK_GBPS,
+                    "traffic": rec["total_bytes"] if rec else None}
     return {"workload": w.name, "tokens_per_s": res["tokens_per_s"], "ms_per_step": res["ms_per_step"],
             "hbm_gbps": res["algorithmic_gbps"], "hbm_frac_of_peak": res["algorithmic_gbps"] / HBM_PEAK_GBPS, "per_pair": pairs}
 
