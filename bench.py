@@ -315,15 +315,18 @@ def cpu_baseline(W, w, budget_s=20.0):
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "decode_traffic.json")
 KERNEL_SOURCES = ("kvq_decode_mfma.hip", "kvq_layout.h", "kvq_internal.h")
+PREFILL_SOURCES = ("kvq_prefill_attn.hip", "kvq_layout.h", "kvq_internal.h")
 
 
-def kernel_source_hash():
-    """Hash of the decode kernel's sources: a counter record taken with other sources is not this kernel's."""
+def kernel_source_hash(name=""):
+    """Hash of the sources of the kernel a traffic record belongs to (records named prefill_attention:... belong to the
+    prefill-stage attention kernels, all others to the decode kernel): a counter record taken with other sources is
+    not this kernel's."""
     import hashlib
 
     h = hashlib.sha256()
-    for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2502_04420_amd", "csrc", name), "rb") as f:
+    for src in (PREFILL_SOURCES if name.startswith("prefill_attention:") else KERNEL_SOURCES):
+        with open(os.path.join(ROOT, "paper_2502_04420_amd", "csrc", src), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
 
@@ -370,7 +373,7 @@ def read_traffic(name):
             rec = json.load(f).get(name)
     except (OSError, ValueError):
         return None
-    if rec is None or rec.get("kernel_sources") != kernel_source_hash():
+    if rec is None or rec.get("kernel_sources") != kernel_source_hash(name):
         return None
     return rec
 
@@ -386,7 +389,7 @@ def record_traffic(args):
         data = {}
     fb, wb = float(fetch_kib) * 1024.0 * float(fscale), float(write_kib) * 1024.0 * float(wscale)
     data[name] = {"fetch_bytes": fb, "write_bytes": wb, "total_bytes": fb + wb, "source": source,
-                  "kernel_sources": kernel_source_hash(), "recorded": time.strftime("%Y-%m-%d")}
+                  "kernel_sources": kernel_source_hash(name), "recorded": time.strftime("%Y-%m-%d")}
     with open(TRAFFIC_FILE, "w") as f:
         json.dump(data, f, indent=1)
     print("recorded", name, data[name])
@@ -537,6 +540,12 @@ def main():
         out["prefill_attention"] = time_prefill_attention(
             torch, pkg, W, w_main, dom_layers[len(dom_layers) // 2],
             meta=pkg.META_FP16 if args.meta == "fp16" else None, keys=pkg.KEYS_PER_TOKEN if KEYS_PER_TOKEN else None)
+        # HBM bytes of one call (all its launches: dequantization passes and attention passes), from the counter record
+        rec = read_traffic("prefill_attention:" + w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") +
+                           (":keys-per-token" if KEYS_PER_TOKEN else ""))
+        out["prefill_attention"]["roofline"]["traffic"] = rec["total_bytes"] if rec else None
+        if rec:
+            out["prefill_attention"]["roofline"]["traffic_detail"] = rec
     out["paper_context"] = "paper reports +16.79%..+21.25% end-to-end tokens/s for its 3.25-bit schedule over KIVI-KV8 (GPU not named)"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W, w_main)
