@@ -100,8 +100,10 @@ def check_decode_code(asm: str) -> int:
     register between the issue of a load and a wait that covers it.  Model: loads return in order, so after
     `s_waitcnt vmcnt(N)` only the N youngest loads are pending.  The code is followed in layout order; a backward
     conditional branch (a loop) is followed once more from its target with the state at the branch; the state is
-    dropped after an unconditional branch (what follows in the layout is reached from elsewhere).  Returns the number
-    of hand-issued loads seen."""
+    dropped after an unconditional branch (what follows in the layout is reached from elsewhere).  A statement that
+    holds two waits (await_loads_either: the count depends on whether the zero-points of the next blocks were asked
+    for in this step) is taken with the larger count if at least that many loads were issued since the last wait,
+    else with the smaller.  Returns the number of hand-issued loads seen."""
     seen = 0
     for name, body in kernel_bodies(asm, "decode_mfma"):
         lines = body.split("\n")
@@ -114,26 +116,41 @@ def check_decode_code(asm: str) -> int:
         def run(start, stop, pending, follow):
             nonlocal seen
             in_asm = False
+            asm_waits = []
+            issued = 0                      # hand-issued loads since the last wait on the load counter
             i = start
             while i < stop:
                 t = lines[i].strip()
                 i += 1
                 if t.startswith(";;#ASMSTART"):
                     in_asm = True
+                    asm_waits = []
                     continue
                 if t.startswith(";;#ASMEND"):
                     in_asm = False
+                    if asm_waits:
+                        # A statement that holds two waits takes one of them at run time: the larger count when further
+                        # loads (the zero-points of the next blocks) went out behind the awaited block's in this step,
+                        # which shows in the number of loads issued since the last wait; otherwise the smaller one.
+                        n = max(asm_waits) if issued >= max(asm_waits) else min(asm_waits)
+                        pending = pending[len(pending) - n:] if n else []
+                        issued = 0
                     continue
                 if not t or t[0] in ";." or t.endswith(":"):
                     continue
                 w = re.match(r"s_waitcnt\b.*vmcnt\((\d+)\)", t)
                 if w:
                     n = int(w.group(1))
-                    pending = pending[len(pending) - n:] if n else []
+                    if in_asm and re.match(r"s_waitcnt\s+vmcnt\(\d+\)$", t):
+                        asm_waits.append(n)
+                    else:
+                        pending = pending[len(pending) - n:] if n else []
+                        issued = 0
                     continue
                 if in_asm:
                     if t.startswith("buffer_load"):
                         pending = pending + [_vregs(t.split(",")[0])]
+                        issued += 1
                         if follow:
                             seen += 1
                     continue

@@ -179,7 +179,8 @@ __device__ __forceinline__ BlockStream block_stream(const LayerView &lv, bool va
 // index, so the block pipeline holds no load whose result a scalar computation waits for.  Loaded once per chunk of
 // the sweep (issued by hand like the block loads; the first one ahead of the first blocks, later ones with a full
 // wait, once per kChunk blocks).  Lanes whose block lies beyond the cache read zero.
-constexpr int kChunk = 60;                   // steps per chunk: a multiple of both stage counts, at most 64
+constexpr int kChunk = 48;                   // steps per chunk: a multiple of both stage counts and of kZChunk, at most 64
+constexpr int kZChunk = 16;                  // steps whose zero-point terms of the scores are formed at once (the columns of one tile)
 
 // voff: byte offset of this lane's word in the cache's exponent array
 __device__ __forceinline__ void issue_exponents(uint32_t &words, const BlockStream &S, uint32_t voff)
@@ -193,13 +194,14 @@ __device__ __forceinline__ void await_exponents(uint32_t &words)
 }
 
 // loads of one block per lane
-template <int BITS> constexpr int block_loads() { return BITS < 16 ? BITS / 2 + 2 : 0; }
+template <int BITS, bool LOADZ = true> constexpr int block_loads() { return BITS < 16 ? BITS / 2 + (LOADZ ? 2 : 1) : 0; }
 
 // Issue the loads of block `blk` of the cache (counted from the cache's first block) into r.  NARROW: the block's
 // scales are stored as fp16 (and were used that way by the encoder).  Codes and metadata are read once per call and
 // never again before the whole cache has streamed by: the loads carry the non-temporal hint, so the lines are not
 // kept in the caches at the expense of anything else (measured: 2-7 % shorter calls, most for the 8-bit pair).
-template <int BITS, bool NARROW>
+// LOADZ = false: without the zero-points (the key wave fetches those of sixteen blocks at a time, issue_zero_points).
+template <int BITS, bool NARROW, bool LOADZ = true>
 __device__ __forceinline__ void issue_block(const BlockStream &S0, bool real, int blk, CodeRegs<BITS> &r)
 {
     static_assert(BITS < 16, "packed blocks only");
@@ -213,11 +215,28 @@ __device__ __forceinline__ void issue_block(const BlockStream &S0, bool real, in
     }
     if constexpr (NARROW) {
         asm volatile("buffer_load_dword %0, %1, %2, %3 offen nt" : "+v"(r.s1) : "v"(S.l4), "s"(S.meta), "s"(moff));
-        asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:256 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
+        if constexpr (LOADZ) asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:256 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
     } else {
         asm volatile("buffer_load_dwordx2 %0, %1, %2, %3 offen nt" : "+v"(r.s2) : "v"(S.l8), "s"(S.meta), "s"(moff));
-        asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:512 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
+        if constexpr (LOADZ) asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:512 nt" : "+v"(r.z) : "v"(S.l4), "s"(S.meta), "s"(moff));
     }
+}
+
+// The zero-points of the keys of kZChunk blocks, fetched as the B operand of one matrix product: lane (n, rq) gets
+// channels 32 cb + 8 rq .. + 7 of the n-th of those blocks (16 bytes per load, cb = 0..3).  voff: byte offset, in the
+// cache's metadata, of that block's zero-points plus 16 rq.  Issued by hand like the block loads.
+__device__ __forceinline__ void issue_zero_points(u32x4 (&zb)[4], const BlockStream &S, bool real, uint32_t voff)
+{
+    const i32x4 meta = pick(real, S.meta);
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen nt" : "+v"(zb[0]) : "v"(voff), "s"(meta));
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:64 nt" : "+v"(zb[1]) : "v"(voff), "s"(meta));
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:128 nt" : "+v"(zb[2]) : "v"(voff), "s"(meta));
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:192 nt" : "+v"(zb[3]) : "v"(voff), "s"(meta));
+}
+template <int N>
+__device__ __forceinline__ void await_zero_points(u32x4 (&zb)[4])
+{
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(zb[0]), "+v"(zb[1]), "+v"(zb[2]), "+v"(zb[3]) : "n"(N));
 }
 
 // Wait until at most N vector memory operations of this wave are outstanding; r's registers are operands, so every
@@ -238,6 +257,26 @@ template <int BITS, int DEPTH>
 __device__ __forceinline__ void await_block(CodeRegs<BITS> &r)
 {
     await_loads<(DEPTH - 1) * block_loads<BITS>(), BITS>(r);
+}
+
+// The same wait with one of two counts, N + EXTRA when `more_behind` (EXTRA further loads were issued behind the
+// block's own) and N otherwise.  One statement with the branch inside: two statements on two code paths would make
+// the compiler merge two versions of registers that loads are still writing.
+template <int N, int EXTRA, int BITS>
+__device__ __forceinline__ void await_loads_either(CodeRegs<BITS> &r, int more_behind)
+{
+    static_assert(BITS == 2 || BITS == 4 || BITS == 8, "packed blocks only");
+#define KVQ_EITHER "s_cmp_eq_u32 %[mb], 0\n\ts_cbranch_scc1 1f\n\ts_waitcnt vmcnt(%[hi])\n\ts_branch 2f\n1:\n\ts_waitcnt vmcnt(%[lo])\n2:"
+    if constexpr (BITS == 8)
+        asm volatile(KVQ_EITHER : "+v"(r.q[0]), "+v"(r.q[BITS == 8 ? 1 : 0]), "+v"(r.q[BITS == 8 ? 2 : 0]), "+v"(r.q[BITS == 8 ? 3 : 0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z)
+                     : [mb] "s"(more_behind), [hi] "n"(N + EXTRA), [lo] "n"(N) : "scc");
+    else if constexpr (BITS == 4)
+        asm volatile(KVQ_EITHER : "+v"(r.q[0]), "+v"(r.q[BITS == 4 ? 1 : 0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z)
+                     : [mb] "s"(more_behind), [hi] "n"(N + EXTRA), [lo] "n"(N) : "scc");
+    else
+        asm volatile(KVQ_EITHER : "+v"(r.q[0]), "+v"(r.s2), "+v"(r.s1), "+v"(r.z)
+                     : [mb] "s"(more_behind), [hi] "n"(N + EXTRA), [lo] "n"(N) : "scc");
+#undef KVQ_EITHER
 }
 
 // a block outside the streaming loop: issue and wait for everything
@@ -304,6 +343,7 @@ struct __attribute__((aligned(16))) PairLds {
     // hand-off: softmax numerators of a block per head, double-buffered.  Rows of 40 floats: the four lane rows of
     // the key wave write rows 2 rq + hh at once, 80 dwords apart = four different quarters of the banks
     float P[2][8][32 + 8];
+    float Zt[kZChunk][4][2];       // key wave: zero-point terms of the scores of kZChunk blocks, [block][lane row] = heads 2 rq, 2 rq + 1
     float alpha[2][8];             // hand-off: factor by which everything accumulated before the block shrinks
     int rescale[2][2];             // hand-off: non-zero when alpha is not all ones (padded to 16 bytes)
 };
@@ -336,9 +376,11 @@ struct ValueState {
 // ------------------------------------------------------------------ key wave
 
 // scores of a quantized block: s[th][hh] for head 2*rq + hh, tokens 16*th + n
-template <int KB, int GQ, bool NARROW>
+// ZB: the zero-point terms c * sum_d q_d z_d of heads 2 rq and 2 rq + 1 come ready-made in zc (zero_point_terms) instead
+// of from the block's own zero-points.
+template <int KB, int GQ, bool NARROW, bool ZB = false>
 __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, uint32_t bexp, const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane,
-                                              float (&s)[2][2])
+                                              float (&s)[2][2], float2 zc = make_float2(0.0f, 0.0f))
 {
     const int n = lane & 15, rq = lane >> 4;
     // lift the operand to the top of the fp16 range: the largest q*s of the block lands in [2^12, 2^14)
@@ -355,24 +397,42 @@ __device__ __forceinline__ void scores_packed(const CodeRegs<KB> &blk, uint32_t 
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j][2 * lane]) = hi;
         *reinterpret_cast<uint32_t *>(&L.Ak[2 * j + 1][2 * lane]) = lo;
     }
-    *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = blk.z;
+    if constexpr (!ZB) *reinterpret_cast<uint32_t *>(&L.Zk[2 * lane]) = blk.z;
     wave_lds_sync();
     float4v S0 = {0.0f, 0.0f, 0.0f, 0.0f}, S1 = S0, Z = S0;
 #pragma unroll
     for (int cb = 0; cb < 4; cb++) {
         const half8 Aop = *reinterpret_cast<const half8 *>(&L.Ak[n][32 * cb + 8 * rq]);
-        const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
         S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, cb), S0, 0, 0, 0);
         S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(Aop, codes_operand<KB>(blk, 4 + cb), S1, 0, 0, 0);
-        Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
+        if constexpr (!ZB) {
+            const half8 Bz = *reinterpret_cast<const half8 *>(&L.Zk[32 * cb + 8 * rq]);
+            Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq), Bz, Z, 0, 0, 0);
+        }
     }
     // this lane holds rows 4*rq + i: (high, low) of head 2*rq and (high, low) of head 2*rq + 1
 #pragma unroll
     for (int hh = 0; hh < 2; hh++) {
-        const float zc = Q.c * Z[2 * hh];
-        s[0][hh] = fmaf(ah, S0[2 * hh] + S0[2 * hh + 1], zc);
-        s[1][hh] = fmaf(ah, S1[2 * hh] + S1[2 * hh + 1], zc);
+        const float zt = ZB ? (hh ? zc.y : zc.x) : Q.c * Z[2 * hh];
+        s[0][hh] = fmaf(ah, S0[2 * hh] + S0[2 * hh + 1], zt);
+        s[1][hh] = fmaf(ah, S1[2 * hh] + S1[2 * hh + 1], zt);
     }
+}
+
+// The zero-point terms c * sum_d q_d z_d of kZChunk blocks at once: the blocks are the columns of one product whose
+// A operand is the exact fp16 query tile (rows 2j = 2j + 1 = head j) and whose B operand came straight from memory
+// (issue_zero_points).  Lane (n, rq) ends up with the terms of block n for heads 2 rq and 2 rq + 1 and leaves them in
+// L.Zt[n][rq], where the lanes of row rq pick them up block by block.
+template <int GQ>
+__device__ __forceinline__ void zero_point_terms(const u32x4 (&zb)[4], const QueryRegs<GQ> &Q, PairLds<GQ> &L, int lane)
+{
+    const int n = lane & 15, rq = lane >> 4;
+    float4v Z = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int cb = 0; cb < 4; cb++)
+        Z = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const half8 *>(Q.Aq + n * (kD + 8) + 32 * cb + 8 * rq),
+                                                   as_half8(zb[cb][0], zb[cb][1], zb[cb][2], zb[cb][3]), Z, 0, 0, 0);
+    *reinterpret_cast<float2 *>(&L.Zt[n][rq][0]) = make_float2(Q.c * Z[0], Q.c * Z[2]);
 }
 
 // Scores of a quantized block whose keys are grouped per token (one (s, z) per token and 32-channel group):
@@ -621,12 +681,29 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
         const BlockStream KS = block_stream(a.lv, false, blk0, a.n_blocks, lane, NARROW);
         uint32_t kexp = 0;                               // exponent words of the chunk's blocks, one per lane
         CodeRegs<KB> kr[DK];
+        // per-channel keys: the zero-points do not come with the blocks but for kZChunk blocks at a time, as the operand
+        // of one matrix product (zero_point_terms), which saves 4 of the 12 matrix instructions of a block's scores
+        // (not next to 8-bit values in a tile of 8 heads: that instantiation has no registers to spare and would spill)
+        constexpr bool kZB = kFast && !KPT && !(GQ == 8 && VB == 8);
+        constexpr int NLK = block_loads<KB, !kZB>();
+        u32x4 zb[4];
+        // byte offset, in the cache's metadata, of the 16 bytes of zero-points this lane fetches for the chunk of steps
+        // that starts at z0 (beyond the range: those of some block of the range, not used)
+        auto zero_point_offset = [&](int z0) {
+            const int i = z0 + n;
+            return (uint32_t)(blk1c(i) * (4 * meta_words(NARROW)) + (NARROW ? 256 : 512) + 16 * rq);
+        };
         if constexpr (kFast) {
 #pragma unroll
             for (int d = 0; d < DK; d++) clear_regs(kr[d]);
             issue_exponents(kexp, KS, exp_offset(0));
+            if constexpr (kZB) {
 #pragma unroll
-            for (int d = 0; d < DK - 1; d++) issue_block<KB, NARROW>(KS, d < n1, blk1c(d), kr[d]);
+                for (int cb = 0; cb < 4; cb++) zb[cb] = u32x4{0u, 0u, 0u, 0u};
+                issue_zero_points(zb, KS, n1 > 0, zero_point_offset(0));
+            }
+#pragma unroll
+            for (int d = 0; d < DK - 1; d++) issue_block<KB, NARROW, !kZB>(KS, d < n1, blk1c(d), kr[d]);
         }
         {
             // queries divided by a power of two that brings the largest to [0.5, 1).  Per-channel keys: with the softmax
@@ -696,26 +773,42 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
             // DK register stages in rotation: stage d is consumed while the loads of the next DK - 1 units (as far as
             // there are any) are in flight.
             // The sweep goes in chunks of kChunk steps (one register of exponent words each); a chunk starts at stage 0.
-            await_exponents<(DK - 1) * block_loads<KB>()>(kexp);           // the first chunk's: issued ahead of the first blocks
+            await_exponents<(DK - 1) * NLK>(kexp);                         // the first chunk's: issued ahead of the first blocks
             for (int c0 = 0; c0 < n1; c0 += kChunk) {
                 if (c0 > 0) {
                     issue_exponents(kexp, KS, exp_offset(c0));
                     await_exponents<0>(kexp);
                 }
                 const int cend = c0 + kChunk < n1 ? c0 + kChunk : n1;
-                bool more = true;
-                for (int i = c0; more;) {
+                for (int z0 = c0; z0 < cend; z0 += kZChunk) {
+                    const int zend = z0 + kZChunk < cend ? z0 + kZChunk : cend;
+                    if constexpr (kZB) {
+                        // The chunk's zero-points were asked for a chunk ago (the first chunk's ahead of the first
+                        // blocks): they are older than every load still allowed to be pending here.  Form the chunk's
+                        // terms, then ask for the next chunk's; those four loads go out in front of the first step's
+                        // block loads, so that step alone waits with four more loads allowed behind its block.
+                        await_zero_points<(DK - 1) * NLK>(zb);
+                        zero_point_terms<GQ>(zb, Q, L, lane);
+                        wave_lds_sync();
+                        issue_zero_points(zb, KS, z0 + kZChunk < n1, zero_point_offset(z0 + kZChunk));
+                    }
+                    bool more = true;
+                    for (int i = z0; more;) {
 #pragma unroll
-                    for (int d = 0; d < DK; d++) {
-                        if (more) {
-                            issue_block<KB, NARROW>(KS, i + DK - 1 < n1, blk1c(i + DK - 1), kr[(d + DK - 1) % DK]);
-                            await_block<KB, DK>(kr[d]);
-                            const uint32_t ew = (uint32_t)__builtin_amdgcn_readlane((int)kexp, i - c0);
-                            if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
-                            else scores_packed<KB, GQ, NARROW>(kr[d], ew, Q, L, lane, s);
-                            softmax_publish<GQ>(s, W, L, i & 1, lane);
-                            wg_barrier();
-                            more = ++i < cend;
+                        for (int d = 0; d < DK; d++) {
+                            if (more) {
+                                issue_block<KB, NARROW, !kZB>(KS, i + DK - 1 < n1, blk1c(i + DK - 1), kr[(d + DK - 1) % DK]);
+                                if constexpr (kZB) await_loads_either<(DK - 1) * NLK, 4, KB>(kr[d], __builtin_amdgcn_readfirstlane(i == z0 ? 1 : 0));
+                                else await_block<KB, DK>(kr[d]);
+                                const uint32_t ew = (uint32_t)__builtin_amdgcn_readlane((int)kexp, i - c0);
+                                if constexpr (KPT) scores_packed_per_token<KB, GQ, NARROW>(kr[d], Q, L, lane, s);
+                                else if constexpr (kZB)
+                                    scores_packed<KB, GQ, NARROW, true>(kr[d], ew, Q, L, lane, s, *reinterpret_cast<const float2 *>(&L.Zt[i - z0][rq][0]));
+                                else scores_packed<KB, GQ, NARROW>(kr[d], ew, Q, L, lane, s);
+                                softmax_publish<GQ>(s, W, L, i & 1, lane);
+                                wg_barrier();
+                                more = ++i < zend;
+                            }
                         }
                     }
                 }
@@ -723,6 +816,7 @@ __global__ __launch_bounds__(128, 4) void decode_mfma(DecodeArgs a)
 #pragma unroll
             for (int d = 0; d < DK; d++) await_loads<0, KB>(kr[d]);      // the empty loads past the end of the range, before
             await_exponents<0>(kexp);                                    // their registers go back to the compiler
+            if constexpr (kZB) await_zero_points<0>(zb);
         }
         for (int i = 0; i < n2; i++) {
             const int u = f1c + i;

@@ -257,6 +257,23 @@ def test_result_does_not_depend_on_splits(kvq_mod, oracle_mod, variant, splits):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("kb,vb,gq,splits", [(4, 2, 4, 1), (2, 2, 7, 1), (8, 4, 4, 2), (4, 8, 8, 1), (8, 8, 3, 3)])
+def test_one_group_sweeps_many_chunks(kvq_mod, oracle_mod, kb, vb, gq, splits):
+    """The matrix-core kernel fetches per-block exponents for 48 steps of a group's sweep at a time and the keys'
+    zero-points for 16: a group that owns 50..101 blocks crosses several chunk boundaries of both kinds, with a ragged
+    last chunk (the bench shapes give a group 16 blocks)."""
+    w = W.Workload("chunks", 1, 2, gq * 2, 2, 128, 32 * 101 + 45, [kb], [vb], seed=640 + kb + vb, outlier_channels=3, key_bias_std=4.0)
+    g, o = _pair(kvq_mod, oracle_mod, w, 4096)
+    K, V = W.kv_tokens(w, 0, 0, w.context)
+    g.quantize_append(0, K.cuda(), V.cuda())
+    o.quantize_append(0, K.numpy(), V.numpy())
+    g.set_decode_options(2, splits)
+    for step in range(2):
+        q = W.query(w, 0, step)
+        o16, o64 = o.decode_attention(0, q.numpy())
+        assert_outputs_close(g.decode_attention(0, q.cuda()), o16, o64, "K%dV%d gq %d splits %d" % (kb, vb, gq, splits))
+
+
 def test_biased_keys_gq7_mixed_layers(kvq_mod, oracle_mod, variant):
     """Shape of the Qwen configuration in small: g_q = 7, keys with a large per-channel offset, K8V2 / K4V2 layers."""
     w = W.config4(batch=2, context=32 * 20 + 32)
