@@ -145,7 +145,8 @@ int kvq_decode_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, void
  * device image, 16384 records of (128 outputs, maximum, sum) = 8.1 MiB, which every GPU the
  * library runs on holds from its first use until the process ends.  The call allocates and frees
  * nothing on host or device; on its first use on a GPU (with that GPU current) it looks up the
- * array's address there.
+ * array's address there (make that first call outside a stream capture; every later call only
+ * launches kernels and can be recorded into a graph and replayed).
  *   Limit: batch * n_q_heads * splits <= 16384 records, else KVQ_ESCRATCH and nothing is
  *   enqueued (kvq_last_error has the numbers).  With automatic splits (at most 2048 token
  *   ranges over all (batch, kv head) caches) every shape with at most 8 query heads per kv head

@@ -100,3 +100,35 @@ def test_noalloc_rejects_what_the_array_cannot_hold(kvq_mod):
     ref, got = _both(g, q)
     _assert_same(ref, got, "after a rejected call")
     g.close()
+
+
+def test_noalloc_recorded_into_a_graph_and_replayed(kvq_mod):
+    """The callers the entry point is for: a decode call recorded into a HIP graph (stream capture forbids
+    allocation) and replayed with new queries.  The address of the built-in array is looked up by an eager call
+    before the capture.  Every replay is checked against an eager kvq_decode_attention on the same inputs, with eager
+    work and synchronisations between the replays."""
+    side = torch.cuda.Stream()
+    w = W.Workload("na-graph", 1, 4, 16, 4, 128, 32 * 40 + 50, [4], [2], seed=2300, outlier_channels=3)
+    with torch.cuda.stream(side):
+        g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, 2048, w.kbits, w.vbits, stream=side)
+        K, V = W.kv_tokens(w, 0, 0, w.context, device="cuda:0")
+        g.quantize_append(0, K, V)
+        lib, h = g._lib, g._h
+        q = W.query(w, 0, 0, device="cuda:0").clone()
+        out = torch.empty_like(q)
+        ref = torch.empty_like(q)
+        assert lib.kvq_decode_attention_noalloc(h, 0, c_void_p(q.data_ptr()), c_void_p(out.data_ptr())) == 0     # address lookup, eager
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        rc = lib.kvq_decode_attention_noalloc(h, 0, c_void_p(q.data_ptr()), c_void_p(out.data_ptr()))
+    assert rc == 0, lib.kvq_last_error()
+    for step in range(1, 4):
+        with torch.cuda.stream(side):
+            q.copy_(W.query(w, 0, step, device="cuda:0"))
+            out.fill_(float("nan"))
+            graph.replay()
+            assert lib.kvq_decode_attention(h, 0, c_void_p(q.data_ptr()), c_void_p(ref.data_ptr())) == 0
+        side.synchronize()
+        assert torch.equal(out, ref), "replay %d differs from the eager call" % step
+    g.close()
