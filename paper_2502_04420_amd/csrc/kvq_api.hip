@@ -19,7 +19,7 @@ namespace {
 
 constexpr int kMaxSplits = 128;
 constexpr int kPrefillChunk = 16;   // caches dequantized per prefill-attention pass (two per XCD)
-constexpr int kWindowWeight = 4;   // cost of the fp16 window in a split's share, in packed blocks (measured: 2..8 alike, 0 slower)
+constexpr int kWindowWeight = 6;   // cost of a chunk (<= 32 tokens) of the fp16 window in a split's share, in packed blocks
 constexpr size_t kAlign = 256;
 
 thread_local char g_last_error[256] = "";
@@ -282,16 +282,31 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     }
     if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
-    // The fp16 window rides on the last split.  Its rows go through the vector units one token at a time, which costs
-    // about as much as kWindowWeight packed blocks, so the last split is handed that many blocks fewer (none at all
-    // when its fair share is smaller than that).
-    const int window = a.n_res > 0 ? kWindowWeight : 0;
+    // The fp16 window rides on the last split.  Its rows are fetched and used after the split's blocks, chunk by chunk
+    // and the values after the keys: memory round trips in a row, which cost about as much as kWindowWeight packed
+    // blocks per chunk.  The window counts as that many units behind the blocks, and the units are dealt out evenly
+    // (the last split gets that many blocks fewer, none at all when its share is smaller than that).  Measured at
+    // batch 16, 8192..8223 tokens: weights 6..10 for one chunk and 10..16 for two are alike; with 4 a two-chunk window
+    // makes its split the straggler (36.5 us against 30.4).
+    int window = kWindowWeight * ((a.n_res + 31) / 32);
     if (a.n_blocks == 0) splits = 1;
-    a.units_per_split = (a.n_blocks + window + splits - 1) / splits;
-    if (a.units_per_split < 1) a.units_per_split = 1;
-    const int block_splits = (a.n_blocks + a.units_per_split - 1) / a.units_per_split;   // splits that own packed blocks
-    if (splits > block_splits + (window ? 1 : 0)) splits = block_splits + (window ? 1 : 0);   // no empty split
+    const int most = a.n_blocks + (window ? 1 : 0);              // no more splits than blocks (+ one for the window)
+    if (splits > most) splits = most;
     if (splits < 1) splits = 1;
+    // (never more than a split's share of blocks: with many small splits the window's split simply takes no blocks)
+    if (window > (a.n_blocks + splits - 1) / splits) window = (a.n_blocks + splits - 1) / splits;
+    if (a.n_res > 0 && window < 1) window = 1;
+    for (;;) {
+        const int total = a.n_blocks + window;
+        a.units_per_split = total / splits;
+        a.split_rem = total % splits;
+        if (splits <= 1) break;
+        // every split but the last must start inside the blocks (no empty split): look at the one before the last
+        const int s2 = splits - 2;
+        const int u0 = s2 * a.units_per_split + (s2 < a.split_rem ? s2 : a.split_rem);
+        if (u0 < a.n_blocks && (window || (splits - 1) * a.units_per_split + (splits - 1 < a.split_rem ? splits - 1 : a.split_rem) < a.n_blocks)) break;
+        splits--;
+    }
     a.splits = splits;
     if ((size_t)a.B * a.Hq * (size_t)splits > part_records) {
         snprintf(g_last_error, sizeof g_last_error,
