@@ -220,6 +220,18 @@ int kvq_debug_export(kvq_ctx *ctx, int32_t layer, void *k_codes, void *k_scale, 
                      void *v_codes, void *v_scale, void *v_zero, void *k_res, void *v_res);
 
 /*
+ * The split plan a decode call would use (host only, no GPU work): with n_tokens tokens in
+ * `layer` of a cache configured as *cfg, kernel `variant` and `forced_splits` as in
+ * kvq_set_decode_options, each (batch, kv head) cache is divided among *splits groups.  Work
+ * units are the packed blocks (N_p / 32, in order) followed by a few virtual units that stand
+ * for the fp16 window; group s takes *units_per_split consecutive units, one more if
+ * s < *split_rem, cut off at the last block; the last group also owns the window.  No group is
+ * empty.  For tests and tuning; KVQ_EINVAL on invalid arguments.
+ */
+int kvq_debug_split_plan(const kvq_config *cfg, int32_t layer, int32_t n_tokens, int32_t variant, int32_t forced_splits,
+                         int32_t *splits, int32_t *units_per_split, int32_t *split_rem);
+
+/*
  * Tuning knobs (optional).  variant: 0 = choose automatically, 1 = vector-ALU kernel,
  * 2 = matrix-core kernel.  splits: 0 = automatic, else the number of token-range splits
  * per (batch, kv head) used to fill the GPU (at most 128).  Returns KVQ_EINVAL for unknown

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libkvq.so")
 _lib = None
 
 EXPORTED = [
-    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_decode_attention_noalloc", "kvq_append_decode_attention", "kvq_prefill_attention",
+    "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_decode_attention_noalloc", "kvq_debug_split_plan", "kvq_append_decode_attention", "kvq_prefill_attention",
     "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
     "kvq_last_error",
 ]

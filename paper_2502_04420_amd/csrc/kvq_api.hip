@@ -237,6 +237,59 @@ int append_tokens(kvq_ctx *c, int layer, const void *k_device, const void *v_dev
     return KVQ_OK;
 }
 
+// How a decode launch divides the tokens of a (batch, kv head) cache among its groups.
+struct SplitPlan { int splits, units_per_split, split_rem; };
+
+// BH caches, code width = key bits + value bits, n_blocks packed blocks and n_res fp16 window tokens per cache;
+// forced: the caller's split count (0 = choose); variant: 1 vector-ALU kernel, 2 matrix-core kernel.
+SplitPlan plan_splits(int BH, int width, int n_blocks, int n_res, int forced, int variant)
+{
+    int splits = forced;
+    if (splits <= 0) {
+        // 16 waves per compute unit (4 on every SIMD) over 256 compute units: 2048 two-wave groups of the
+        // matrix-core kernel or 1024 four-wave groups of the vector kernel.  More splits only add per-group
+        // set-up and merge work, so split no further and keep at least 4 (8) blocks per group.
+        // The wider a layer's codes, the more bytes every group keeps in flight and the fewer groups serve it
+        // best (measured at batch 8..64, 8K and 32K tokens: K8V8 4-7 % faster with 1024 groups than with 2048,
+        // K8V4 and K4V8 5 %, K8V2 3-4 % with 1536; K4V4 and narrower are fastest with 2048).
+        const int groups = variant != 2 ? 1024 : width <= 8 ? 2048 : width <= 10 ? 1536 : 1024;
+        const int min_units = variant == 2 ? 4 : 8;
+        splits = (groups + BH - 1) / BH;
+        const int cap = (n_blocks + min_units - 1) / min_units + (n_res > 0 ? 1 : 0);
+        if (splits > cap) splits = cap;
+    }
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits < 1) splits = 1;
+    // The fp16 window rides on the last split.  Its rows are fetched and used after the split's blocks, chunk by chunk
+    // and the values after the keys: memory round trips in a row, which cost about as much as kWindowWeight packed
+    // blocks per chunk.  The window counts as that many units behind the blocks, and the units are dealt out evenly
+    // (the last split gets that many blocks fewer, none at all when its share is smaller than that).  Measured at
+    // batch 16, 8192..8223 tokens: weights 6..10 for one chunk and 10..16 for two are alike; with 4 a two-chunk window
+    // makes its split the straggler (36.5 us against 30.4).
+    int window = kWindowWeight * ((n_res + 31) / 32);
+    if (n_blocks == 0) splits = 1;
+    const int most = n_blocks + (window ? 1 : 0);                // no more splits than blocks (+ one for the window)
+    if (splits > most) splits = most;
+    if (splits < 1) splits = 1;
+    // (never more than a split's share of blocks: with many small splits the window's split simply takes no blocks)
+    if (window > (n_blocks + splits - 1) / splits) window = (n_blocks + splits - 1) / splits;
+    if (n_res > 0 && window < 1) window = 1;
+    SplitPlan p;
+    for (;;) {
+        const int total = n_blocks + window;
+        p.units_per_split = total / splits;
+        p.split_rem = total % splits;
+        if (splits <= 1) break;
+        // No empty split: every split but the last must start inside the blocks (look at the one before the last), and
+        // without a window so must the last.
+        auto first_unit = [&](int sidx) { return sidx * p.units_per_split + (sidx < p.split_rem ? sidx : p.split_rem); };
+        if (first_unit(splits - 2) < n_blocks && (window || first_unit(splits - 1) < n_blocks)) break;
+        splits--;
+    }
+    p.splits = splits;
+    return p;
+}
+
 // Decode attention over the layer's tokens.  k_new / v_new: rows of a token that append_tokens() left out of the
 // window ring (fused append), or NULL.
 // part_o / part_ml: where the splits' partial results go, room for part_records (query row, split) records.
@@ -264,49 +317,10 @@ int decode_layer(kvq_ctx *c, int layer, const void *q_device, void *out_device, 
     a.v_new = static_cast<const uint16_t *>(v_new);
     a.new_pos = T - 1;
     const int variant = decode_variant(c);
-    int splits = c->splits;
-    if (splits <= 0) {
-        // 16 waves per compute unit (4 on every SIMD) over 256 compute units: 2048 two-wave groups of the
-        // matrix-core kernel or 1024 four-wave groups of the vector kernel.  More splits only add per-group
-        // set-up and merge work, so split no further and keep at least 4 (8) blocks per group.
-        // The wider a layer's codes, the more bytes every group keeps in flight and the fewer groups serve it
-        // best (measured at batch 8..64, 8K and 32K tokens: K8V8 4-7 % faster with 1024 groups than with 2048,
-        // K8V4 and K4V8 5 %, K8V2 3-4 % with 1536; K4V4 and narrower are fastest with 2048).
-        const int BH = a.B * a.Hkv;
-        const int width = a.lv.kbits + a.lv.vbits;
-        const int groups = variant != 2 ? 1024 : width <= 8 ? 2048 : width <= 10 ? 1536 : 1024;
-        const int min_units = variant == 2 ? 4 : 8;
-        splits = (groups + BH - 1) / BH;
-        const int cap = (a.n_blocks + min_units - 1) / min_units + (a.n_res > 0 ? 1 : 0);
-        if (splits > cap) splits = cap;
-    }
-    if (splits > kMaxSplits) splits = kMaxSplits;
-    if (splits < 1) splits = 1;
-    // The fp16 window rides on the last split.  Its rows are fetched and used after the split's blocks, chunk by chunk
-    // and the values after the keys: memory round trips in a row, which cost about as much as kWindowWeight packed
-    // blocks per chunk.  The window counts as that many units behind the blocks, and the units are dealt out evenly
-    // (the last split gets that many blocks fewer, none at all when its share is smaller than that).  Measured at
-    // batch 16, 8192..8223 tokens: weights 6..10 for one chunk and 10..16 for two are alike; with 4 a two-chunk window
-    // makes its split the straggler (36.5 us against 30.4).
-    int window = kWindowWeight * ((a.n_res + 31) / 32);
-    if (a.n_blocks == 0) splits = 1;
-    const int most = a.n_blocks + (window ? 1 : 0);              // no more splits than blocks (+ one for the window)
-    if (splits > most) splits = most;
-    if (splits < 1) splits = 1;
-    // (never more than a split's share of blocks: with many small splits the window's split simply takes no blocks)
-    if (window > (a.n_blocks + splits - 1) / splits) window = (a.n_blocks + splits - 1) / splits;
-    if (a.n_res > 0 && window < 1) window = 1;
-    for (;;) {
-        const int total = a.n_blocks + window;
-        a.units_per_split = total / splits;
-        a.split_rem = total % splits;
-        if (splits <= 1) break;
-        // every split but the last must start inside the blocks (no empty split): look at the one before the last
-        const int s2 = splits - 2;
-        const int u0 = s2 * a.units_per_split + (s2 < a.split_rem ? s2 : a.split_rem);
-        if (u0 < a.n_blocks && (window || (splits - 1) * a.units_per_split + (splits - 1 < a.split_rem ? splits - 1 : a.split_rem) < a.n_blocks)) break;
-        splits--;
-    }
+    const SplitPlan sp = plan_splits(a.B * a.Hkv, a.lv.kbits + a.lv.vbits, a.n_blocks, a.n_res, c->splits, variant);
+    const int splits = sp.splits;
+    a.units_per_split = sp.units_per_split;
+    a.split_rem = sp.split_rem;
     a.splits = splits;
     if ((size_t)a.B * a.Hq * (size_t)splits > part_records) {
         snprintf(g_last_error, sizeof g_last_error,
@@ -476,6 +490,22 @@ int kvq_debug_export(kvq_ctx *c, int32_t layer, void *k_codes, void *k_scale, vo
     if (T == 0) return KVQ_OK;
     hipError_t e = kvq::launch_export(a, c->stream);
     if (e != hipSuccess) return launch_failed("export kernel", e);
+    return KVQ_OK;
+}
+
+int kvq_debug_split_plan(const kvq_config *cfg, int32_t layer, int32_t n_tokens, int32_t variant, int32_t forced_splits,
+                         int32_t *splits, int32_t *units_per_split, int32_t *split_rem)
+{
+    if (!config_ok(cfg) || layer < 0 || layer >= cfg->n_layers || n_tokens < 1 || n_tokens > cfg->max_tokens || variant < 0 ||
+        variant > 2 || forced_splits < 0 || forced_splits > kMaxSplits || !splits || !units_per_split || !split_rem)
+        return KVQ_EINVAL;
+    const int over = n_tokens - cfg->residual;
+    const int np = over > 0 ? kvq::kG * (over / kvq::kG) : 0;
+    const SplitPlan p = plan_splits(cfg->batch * cfg->n_kv_heads, cfg->kbits[layer] + cfg->vbits[layer], np / kvq::kG, n_tokens - np,
+                                    forced_splits, variant == 0 ? 2 : variant);
+    *splits = p.splits;
+    *units_per_split = p.units_per_split;
+    *split_rem = p.split_rem;
     return KVQ_OK;
 }
 

@@ -142,3 +142,56 @@ def test_equivalent_precision_matches_the_papers_printed_values():
     assert parse_pairs("K8V4, KV4,K4V2") == ([8, 4, 4], [4, 4, 2])
     with pytest.raises(ValueError):
         parse_pairs("K3V4")
+
+
+def _split_ranges(n_blocks, n_res, splits, units, rem):
+    """The units [u0, u1) of every split as the kernels read the plan: blocks first, the window's chunks on the last."""
+    out = []
+    for s in range(splits):
+        u0 = min(s * units + min(s, rem), n_blocks)
+        u1 = min(u0 + units + (1 if s < rem else 0), n_blocks)
+        if s == splits - 1:
+            u1 = n_blocks + (n_res + 31) // 32
+        out.append((u0, u1))
+    return out
+
+
+def test_split_plan_covers_every_unit_once_and_leaves_no_split_empty(lib):
+    """kvq_debug_split_plan over many shapes, lengths, widths, kernel variants and forced split counts: the splits'
+    ranges tile the blocks in order, the window sits on the last split, no split is empty (an empty split would hand
+    the merge a record without a maximum), blocks per split differ by at most one in front of the window's units, and
+    a forced split count is never exceeded."""
+    i32 = ctypes.c_int32
+    seen_uneven = False
+    for batch, hq, hkv in ((1, 1, 1), (2, 8, 2), (16, 32, 8), (8, 28, 4), (64, 32, 8)):
+        for kb, vb in ((2, 2), (4, 2), (8, 8), (16, 4), (16, 16)):
+            max_tokens = 40000
+            cfg, keep = _cfg(n_layers=1, batch=batch, n_q_heads=hq, n_kv_heads=hkv, max_tokens=max_tokens, kbits=[kb], vbits=[vb])
+            for T in (1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 160, 200, 1000, 4005, 8192, 8200, 8223, 32768, 32800, 39999):
+                over = T - 32
+                n_p = 32 * (over // 32) if over > 0 else 0
+                n_blocks, n_res = n_p // 32, T - n_p
+                for variant in (1, 2):
+                    for forced in (0, 1, 2, 3, 7, 16, 100, 128):
+                        s, u, r = i32(), i32(), i32()
+                        assert lib.kvq_debug_split_plan(ctypes.byref(cfg), 0, T, variant, forced, ctypes.byref(s), ctypes.byref(u), ctypes.byref(r)) == 0
+                        splits, units, rem = s.value, u.value, r.value
+                        where = (batch, hkv, kb, vb, T, variant, forced, splits, units, rem)
+                        assert 1 <= splits <= 128 and (forced == 0 or splits <= forced), where
+                        assert units >= 0 and 0 <= rem < splits, where
+                        ranges = _split_ranges(n_blocks, n_res, splits, units, rem)
+                        assert ranges[0][0] == 0 and ranges[-1][1] == n_blocks + (n_res + 31) // 32, where
+                        for (a0, a1), (b0, b1) in zip(ranges, ranges[1:]):
+                            assert a1 == b0, where                       # in order, no gap, no overlap
+                        assert all(u1 > u0 for u0, u1 in ranges), where  # nobody is empty
+                        # the splits that lie in front of the window's virtual units
+                        blocks = [u1 - u0 for k, (u0, u1) in enumerate(ranges[:-1]) if k * units + min(k, rem) + units + (k < rem) <= n_blocks]
+                        if blocks:
+                            assert max(blocks) - min(blocks) <= 1, where
+                            seen_uneven |= max(blocks) != min(blocks)
+    assert seen_uneven
+    s, u, r = i32(), i32(), i32()
+    cfg, keep = _cfg()
+    for bad in ((5, 10, 2, 0), (0, 0, 2, 0), (0, 257, 2, 0), (0, 10, 3, 0), (0, 10, 2, 129), (-1, 10, 2, 0)):
+        assert lib.kvq_debug_split_plan(ctypes.byref(cfg), bad[0], bad[1], bad[2], bad[3], ctypes.byref(s), ctypes.byref(u), ctypes.byref(r)) == -1, bad
+    assert lib.kvq_debug_split_plan(ctypes.byref(cfg), 0, 10, 2, 0, None, ctypes.byref(u), ctypes.byref(r)) == -1
