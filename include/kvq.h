@@ -225,7 +225,7 @@ int kvq_debug_export(kvq_ctx *ctx, int32_t layer, void *k_codes, void *k_scale, 
  * kvq_set_decode_options, each (batch, kv head) cache is divided among *splits groups.  Work
  * units are the packed blocks (N_p / 32, in order) followed by a few virtual units that stand
  * for the fp16 window; group s takes *units_per_split consecutive units, one more if
- * s < *split_rem, cut off at the last block; the last group also owns the window.  No group is
+ * s >= *splits - *split_rem, cut off at the last block; the last group also owns the window.  No group is
  * empty.  For tests and tuning; KVQ_EINVAL on invalid arguments.
  */
 int kvq_debug_split_plan(const kvq_config *cfg, int32_t layer, int32_t n_tokens, int32_t variant, int32_t forced_splits,

@@ -282,7 +282,7 @@ SplitPlan plan_splits(int BH, int width, int n_blocks, int n_res, int forced, in
         if (splits <= 1) break;
         // No empty split: every split but the last must start inside the blocks (look at the one before the last), and
         // without a window so must the last.
-        auto first_unit = [&](int sidx) { return sidx * p.units_per_split + (sidx < p.split_rem ? sidx : p.split_rem); };
+        auto first_unit = [&](int sidx) { return sidx * p.units_per_split + (sidx > splits - p.split_rem ? sidx - (splits - p.split_rem) : 0); };
         if (first_unit(splits - 2) < n_blocks && (window || first_unit(splits - 1) < n_blocks)) break;
         splits--;
     }

@@ -61,7 +61,7 @@ struct DecodeArgs {
     int n_res;             // fp16 tokens at positions [32*n_blocks, 32*n_blocks + n_res)
     int NB, RC;
     int splits;            // gridDim.x
-    int units_per_split;   // work units per split: the first split_rem splits take one more.  Units are the quantized blocks, then
+    int units_per_split;   // work units per split: the last split_rem splits take one more.  Units are the quantized blocks, then
     int split_rem;         // (owned by the last split, counted as a few units) the fp16 window
     float scale_log2e;     // log2(e) / sqrt(D)
     // fused append of one token per sequence (matrix-core kernel only): its fp16 rows [B*Hkv][128], not yet in the
@@ -88,12 +88,14 @@ struct PrefillArgs {
 
 // Work units [u0, u1) of a split: units are the quantized blocks, then the chunks of <= 32 fp16 window tokens.  The
 // blocks and the window's weight (a few virtual units behind the blocks) are dealt out evenly: units_per_split each,
-// one more for the first split_rem splits; the last split owns the window and whatever blocks its share leaves room
+// one more for the last split_rem splits (the window's split among them: its share holds the window's units
+// first); the last split owns the window and whatever blocks its share leaves room
 // for (possibly none).
 __device__ __forceinline__ void split_range(const DecodeArgs &a, int split, int &u0, int &u1)
 {
-    u0 = split * a.units_per_split + (split < a.split_rem ? split : a.split_rem);
-    u1 = u0 + a.units_per_split + (split < a.split_rem ? 1 : 0);
+    const int first_big = a.splits - a.split_rem;            // the last split_rem splits take one unit more
+    u0 = split * a.units_per_split + (split > first_big ? split - first_big : 0);
+    u1 = u0 + a.units_per_split + (split >= first_big ? 1 : 0);
     if (u0 > a.n_blocks) u0 = a.n_blocks;
     if (u1 > a.n_blocks) u1 = a.n_blocks;
     if (split == a.splits - 1) u1 = a.n_blocks + (a.n_res + 31) / 32;

@@ -148,8 +148,9 @@ def _split_ranges(n_blocks, n_res, splits, units, rem):
     """The units [u0, u1) of every split as the kernels read the plan: blocks first, the window's chunks on the last."""
     out = []
     for s in range(splits):
-        u0 = min(s * units + min(s, rem), n_blocks)
-        u1 = min(u0 + units + (1 if s < rem else 0), n_blocks)
+        big = splits - rem                                   # the last `rem` splits take one unit more
+        u0 = min(s * units + max(0, s - big), n_blocks)
+        u1 = min(u0 + units + (1 if s >= big else 0), n_blocks)
         if s == splits - 1:
             u1 = n_blocks + (n_res + 31) // 32
         out.append((u0, u1))
@@ -185,7 +186,7 @@ def test_split_plan_covers_every_unit_once_and_leaves_no_split_empty(lib):
                             assert a1 == b0, where                       # in order, no gap, no overlap
                         assert all(u1 > u0 for u0, u1 in ranges), where  # nobody is empty
                         # the splits that lie in front of the window's virtual units
-                        blocks = [u1 - u0 for k, (u0, u1) in enumerate(ranges[:-1]) if k * units + min(k, rem) + units + (k < rem) <= n_blocks]
+                        blocks = [u1 - u0 for k, (u0, u1) in enumerate(ranges[:-1]) if k * units + max(0, k - (splits - rem)) + units + (k >= splits - rem) <= n_blocks]
                         if blocks:
                             assert max(blocks) - min(blocks) <= 1, where
                             seen_uneven |= max(blocks) != min(blocks)
