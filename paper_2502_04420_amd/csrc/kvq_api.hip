@@ -251,8 +251,9 @@ SplitPlan plan_splits(int BH, int width, int n_blocks, int n_res, int forced, in
         // set-up and merge work, so split no further and keep at least 4 (8) blocks per group.
         // The wider a layer's codes, the more bytes every group keeps in flight and the fewer groups serve it
         // best (measured at batch 8..64, 8K and 32K tokens: K8V8 4-7 % faster with 1024 groups than with 2048,
-        // K8V4 and K4V8 5 %, K8V2 3-4 % with 1536; K4V4 and narrower are fastest with 2048).
-        const int groups = variant != 2 ? 1024 : width <= 8 ? 2048 : width <= 10 ? 1536 : 1024;
+        // K8V4 and K4V8 5 %; K4V4 and narrower are fastest with 2048).  K8V2 and K2V8 are as fast with 1024 as with
+        // 2048 and 2-6 % slower with 1536 (3 waves per SIMD: the key and value roles cannot be even on every SIMD).
+        const int groups = variant != 2 ? 1024 : width <= 8 ? 2048 : 1024;
         const int min_units = variant == 2 ? 4 : 8;
         splits = (groups + BH - 1) / BH;
         const int cap = (n_blocks + min_units - 1) / min_units + (n_res > 0 ? 1 : 0);

@@ -628,9 +628,9 @@ __device__ __forceinline__ void output_rows(const uint16_t *base, int pos0, int 
 // ------------------------------------------------------------------ kernel
 
 // Waves per SIMD the register allocation must leave room for: the host plans 2048 groups (4 waves per SIMD) for code
-// widths up to 8 bits per key + value element, 1536 (3) up to 10 and 1024 (2) beyond; the wider instantiations may
+// widths up to 8 bits per key + value element and 1024 (2) beyond; the wider instantiations may
 // use the registers that fewer resident waves leave free instead of spilling.
-template <int KB, int VB> constexpr int resident_waves() { return (KB < 16 && VB < 16) ? (KB + VB <= 8 ? 4 : KB + VB <= 10 ? 3 : 2) : 4; }
+template <int KB, int VB> constexpr int resident_waves() { return (KB < 16 && VB < 16) ? (KB + VB <= 8 ? 4 : 2) : 4; }
 
 template <int KB, int VB, int GQ, bool NARROW, bool KPT>
 __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(DecodeArgs a)
