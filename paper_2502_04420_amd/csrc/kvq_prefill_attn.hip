@@ -330,33 +330,56 @@ __device__ __forceinline__ float xor_lanes(float x, int mask) { return __shfl_xo
 
 // S^T = K^ Q^T: rows = tokens 16 tt + 4 rq + r, column = query n of tile qt.  KLO: quantized keys, whose fp16 rounding
 // remainders are multiplied as well.
+// the A operand of the output product for channel tile ct: V^T rows 16 ct + n, tokens {4 rq .. + 3, 16 + 4 rq .. + 3}
+__device__ __forceinline__ half8 value_operand(const Tiles &X, int ct, int n, int rq)
+{
+    const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
+    const half4 v1 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][16 + 4 * rq]);
+    return half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+}
+
 template <bool KLO>
-__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq)
+__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq,
+                                           const Tiles *Xv = nullptr, half8 *Av = nullptr)
 {
 #pragma unroll
     for (int tt = 0; tt < 2; tt++)
 #pragma unroll
         for (int qt = 0; qt < kQT; qt++) S[tt][qt] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+    // Operands come from LDS one batch (two rows x 8 channels per lane = 8 registers) at a time, two batches ahead of the
+    // products that use them; a compiler barrier per batch keeps the order (left alone, the compiler either fetches all
+    // 64 registers of a unit up front or waits for every batch right after asking for it).  With Xv: the value
+    // operands of the output product that follows (unit Xv) are asked for during the last batches, so that they are
+    // there when the softmax is done.
+    constexpr int kBatches = KLO ? 8 : 4;
+    auto fetch = [&](int bt, half8 &A0, half8 &A1) {
+        const int step = bt & 3;
+        if (KLO && bt >= 4) {
+            A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
+            A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
+        } else {
+            A0 = *reinterpret_cast<const half8 *>(&X.K[n][32 * step + 8 * rq]);
+            A1 = *reinterpret_cast<const half8 *>(&X.K[16 + n][32 * step + 8 * rq]);
+        }
+    };
+    half8 A0[kBatches], A1[kBatches];
+    constexpr int kAhead = 2;                                   // batches in flight (2..4 measured alike)
 #pragma unroll
-    for (int step = 0; step < 4; step++) {
-        const half8 A0 = *reinterpret_cast<const half8 *>(&X.K[n][32 * step + 8 * rq]);
-        const half8 A1 = *reinterpret_cast<const half8 *>(&X.K[16 + n][32 * step + 8 * rq]);
+    for (int bt = 0; bt < kAhead && bt < kBatches; bt++) fetch(bt, A0[bt], A1[bt]);
+    constexpr int kVFirst = kBatches - 2;                       // the value operands ride with the last two batches
+#pragma unroll
+    for (int bt = 0; bt < kBatches; bt++) {
+        if (bt + kAhead < kBatches) fetch(bt + kAhead, A0[bt + kAhead], A1[bt + kAhead]);
+        if (Xv && bt >= kVFirst && bt < kVFirst + 2) {
+#pragma unroll
+            for (int k = 0; k < 4; k++) Av[4 * (bt - kVFirst) + k] = value_operand(*Xv, 4 * (bt - kVFirst) + k, n, rq);
+        }
+        asm volatile("" ::: "memory");
+        const int step = bt & 3;
 #pragma unroll
         for (int qt = 0; qt < kQT; qt++) {
-            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
-            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
-        }
-    }
-    if constexpr (KLO) {
-#pragma unroll
-        for (int step = 0; step < 4; step++) {
-            const half8 A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
-            const half8 A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
-#pragma unroll
-            for (int qt = 0; qt < kQT; qt++) {
-                S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0, Qf[qt][step], S[0][qt], 0, 0, 0);
-                S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1, Qf[qt][step], S[1][qt], 0, 0, 0);
-            }
+            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], Qf[qt][step], S[0][qt], 0, 0, 0);
+            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], Qf[qt][step], S[1][qt], 0, 0, 0);
         }
     }
 }
@@ -444,16 +467,12 @@ __device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c
 
 // O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
 // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.
-__device__ __forceinline__ void output_add(const Tiles &X, const half8 (&P)[kQT], float4v (&O)[8][kQT], int n, int rq)
+__device__ __forceinline__ void output_add(const half8 (&Av)[8], const half8 (&P)[kQT], float4v (&O)[8][kQT])
 {
 #pragma unroll
-    for (int ct = 0; ct < 8; ct++) {
-        const half4 v0 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][4 * rq]);
-        const half4 v1 = *reinterpret_cast<const half4 *>(&X.Vt[16 * ct + n][16 + 4 * rq]);
-        const half8 A = half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    for (int ct = 0; ct < 8; ct++)
 #pragma unroll
-        for (int qt = 0; qt < kQT; qt++) O[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P[qt], O[ct][qt], 0, 0, 0);
-    }
+        for (int qt = 0; qt < kQT; qt++) O[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Av[ct], P[qt], O[ct][qt], 0, 0, 0);
 }
 
 // O^T *= alpha per query, before the unit's product is added (on the exact path only, which is the rare one).
@@ -617,21 +636,30 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             if (u <= wlast) {
                 const bool ahead = u + 1 < nb && u + 1 <= wlast;
                 half8 P[kQT];
+                float alpha[kQT];
+                const bool was_calm = calm;
+                half8 Av[8];
                 if (calm) {
                     // the common case, one stretch of straight-line code: score products of the next unit next to the
                     // weights of this one against the unchanged reference (calm implies that there is a next unit)
-                    score_unit<KLO>(X1, Qf, Sout, n, rq);
+                    score_unit<KLO>(X1, Qf, Sout, n, rq, &X0, Av);
                     softmax_calm(Sin, c, m, lsum, P);
                 } else {
-                    float alpha[kQT];
-                    if (ahead) score_unit<KLO>(X1, Qf, Sout, n, rq);
+                    if (ahead) score_unit<KLO>(X1, Qf, Sout, n, rq, &X0, Av);
+                    else {
+#pragma unroll
+                        for (int ct = 0; ct < 8; ct++) Av[ct] = value_operand(X0, ct, n, rq);
+                    }
                     if (u < open_units) softmax_unit<false>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
                     else softmax_unit<true>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
-                    output_rescale(alpha, O);
                 }
+                // The accumulators are touched under a condition of their own, not inside the two-sided one above: there
+                // the compiler's merge block sits in front of the calm side, and the calm side then copied all 64
+                // accumulator registers, every unit, to meet the rescaled ones.
+                if (!was_calm) output_rescale(alpha, O);
                 // one place adds to the accumulators on every path: they stay in the same registers (with a product
                 // on each path the compiler copied all 64 of them after every unit)
-                output_add(X0, P, O, n, rq);
+                output_add(Av, P, O);
                 // the next unit is calm if it needs no mask, has a unit after it to look ahead to, and none of its
                 // scores exceeds its query's reference (as it stands now) by more than kCalm
                 calm = ahead && u + 2 < nb && u + 2 <= wlast && u + 1 < open_units && !unit_exceeds(Sout, calm_over_c, m);
@@ -661,7 +689,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             score_unit<false>(L[0], Qf, S, n, rq);
             softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
             output_rescale(alpha, O);
-            output_add(L[0], P, O, n, rq);
+            half8 Av[8];
+#pragma unroll
+            for (int ct = 0; ct < 8; ct++) Av[ct] = value_operand(L[0], ct, n, rq);
+            output_add(Av, P, O);
         }
         __syncthreads();
     }
