@@ -7,9 +7,11 @@
 // chunk of (batch, kv head) caches at a time:
 //   1. prefill_dequantize: every packed unit (32 tokens) of the chunk is dequantized once, X^ = fma(code, s, z) in
 //      fp32, into a scratch area as fp16, in the layout the attention kernel keeps a unit in LDS: K^ as
-//      [token][channel], V^ transposed as [channel][token].  Dequantized keys are kept as two fp16 numbers (the rounded
-//      value and the remainder) and multiplied twice: keys have a few channels of large magnitude, and one fp16
-//      rounding of those, times a large query entry, moves a logit by several 1e-3.  Dequantizing inside the attention
+//      [token][channel], V^ transposed as [channel][token].  Dequantized keys are multiplied by the softmax constant
+//      log2(e) / sqrt(D) in fp32 (the score products then come out in the exponent's units) and kept as two fp16
+//      numbers (the rounded value and the remainder), which are multiplied twice: keys have a few channels of large
+//      magnitude, and one fp16 rounding of those, times a large query entry, moves a logit by several 1e-3.
+//      Dequantizing inside the attention
 //      kernel instead repeats this work for every query head of the group and every query tile (256 times per unit at
 //      8192 queries) and made that kernel bound by its vector instructions.
 //   2. prefill_attention: a work-group of 8 waves owns 256 consecutive queries of one query head, 32 per wave (two
@@ -20,8 +22,9 @@
 //      {4 rq .. 4 rq + 3} and {16 + 4 rq ..}, which is exactly a B operand of O^T += V^T P^T when the A operand (V^T
 //      from LDS) lists its tokens in the same order.  The softmax weights therefore go from the accumulator of one
 //      product into the operand of the next without leaving the registers.  Online softmax in base 2 per query (the
-//      reference maximum is shared by the four lanes that hold a query and only moves when a score exceeds it by more
-//      than 2^8), fp32 accumulation, one division at the end.
+//      reference is shared by the four lanes that hold a query and only moves when a score exceeds it by more than 8
+//      in the exponent; the score products of quantized keys start from minus the reference, so that in the common
+//      case their results are the exponents themselves), fp32 accumulation, one division at the end.
 #include <hip/hip_ext.h>
 
 #include <type_traits>
@@ -208,8 +211,10 @@ __device__ __forceinline__ void slab_meta8(const uint32_t *scales, const uint16_
     for (int e = 0; e < 8; e++) z[e] = half_bits((e & 1) ? c[e >> 1] >> 16 : c[e >> 1] & 0xffffu);
 }
 
+// kscale: the softmax constant log2(e) / sqrt(D), multiplied into the dequantized keys in fp32 before they are split
+// into two fp16 numbers: the attention kernel's score products then come out in the exponent's units.
 template <int BITS, bool KPT>
-__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c)
+__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c, float kscale)
 {
     const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
     const bool narrow = lv.narrow != 0;
@@ -228,7 +233,7 @@ __device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, c
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; e++)      // m = 4 th + cb: m & 1 == cb & 1
-            x[e] = fmaf(code_of<BITS>(th == 0 ? c[0] : c[2], th == 0 ? c[1] : c[3], cb, e), s[e], z[e]);
+            x[e] = fmaf(code_of<BITS>(th == 0 ? c[0] : c[2], th == 0 ? c[1] : c[3], cb, e), s[e], z[e]) * kscale;
         *reinterpret_cast<u32x4 *>(&L.K[t][32 * cb + 8 * kq]) = pack8(x);
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
@@ -292,13 +297,13 @@ __device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, cons
     }
     if constexpr (KQ) {
         if (a.lv.kpt) {
-            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0);
-            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0);
-            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0);
+            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
         } else {
-            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0);
-            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0);
-            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0);
+            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
         }
     } else {
         store_key_rows(L, tid, st.k0, st.k1);
@@ -340,12 +345,12 @@ __device__ __forceinline__ half8 value_operand(const Tiles &X, int ct, int n, in
 
 template <bool KLO>
 __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq,
-                                           const Tiles *Xv = nullptr, half8 *Av = nullptr)
+                                           const float4v (&init)[kQT], const Tiles *Xv = nullptr, half8 *Av = nullptr)
 {
-#pragma unroll
-    for (int tt = 0; tt < 2; tt++)
-#pragma unroll
-        for (int qt = 0; qt < kQT; qt++) S[tt][qt] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+    // KLO: the keys carry the softmax constant (see prefill_dequantize) and the accumulators start from init[qt] = minus
+    // the query's reference maximum, four times: the products come out in the exponent's units, relative to the
+    // reference, and the common case of the softmax has neither a multiplication nor a subtraction left to do.
+    // Otherwise (fp16 rows: window chunks, 16-bit keys) they start from zero and the scores are raw.
     // Operands come from LDS one batch (two rows x 8 channels per lane = 8 registers) at a time, two batches ahead of the
     // products that use them; a compiler barrier per batch keeps the order (left alone, the compiler either fetches all
     // 64 registers of a unit up front or waits for every batch right after asking for it).  With Xv: the value
@@ -378,8 +383,9 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
         const int step = bt & 3;
 #pragma unroll
         for (int qt = 0; qt < kQT; qt++) {
-            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], Qf[qt][step], S[0][qt], 0, 0, 0);
-            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], Qf[qt][step], S[1][qt], 0, 0, 0);
+            const float4v start = KLO ? init[qt] : float4v{0.0f, 0.0f, 0.0f, 0.0f};
+            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], Qf[qt][step], bt == 0 ? start : S[0][qt], 0, 0, 0);
+            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], Qf[qt][step], bt == 0 ? start : S[1][qt], 0, 0, 0);
         }
     }
 }
@@ -395,18 +401,26 @@ __device__ __forceinline__ float add_weights(float acc, half8 P)
     return acc;
 }
 
-// Online softmax in base 2 of the unit's scores: weights P (fp16, already in the operand order of the output product),
-// running maximum m (raw scores), partial sums lsum, and the factors alpha by which the accumulators shrink.
+// The reference m of a query (in the exponent's units: score * log2(e) / sqrt(D)) only has to keep the weights in range,
+// it need not be the exact maximum: as long as no score exceeds it by more than kCalm, it stays (no rescaling, weights
+// <= 2^kCalm: fp16 holds them, the accumulators are fp32).
+constexpr float kCalm = 8.0f;
+
+// Online softmax in base 2 of the unit's scores, exact form: weights P (fp16, already in the operand order of the output
+// product), reference m, partial sums lsum, and the factors alpha by which the accumulators shrink.  Returns whether
+// some reference moved (in any lane).
+// PRE: the scores are in the exponent's units and relative to base[qt] (score_unit with KLO); otherwise raw, times c.
 // MASK: the unit reaches beyond some query's position.
-template <bool MASK>
-__device__ __forceinline__ void softmax_unit(const float4v (&S)[2][kQT], float c, int u, const int (&qpos)[kQT], float (&m)[kQT],
-                                             float (&lsum)[kQT], half8 (&P)[kQT], float (&alpha)[kQT], int rq)
+template <bool MASK, bool PRE>
+__device__ __forceinline__ bool softmax_unit(const float4v (&S)[2][kQT], float c, int u, const int (&qpos)[kQT], const float (&base)[kQT],
+                                             float (&m)[kQT], float (&lsum)[kQT], half8 (&P)[kQT], float (&alpha)[kQT], int rq)
 {
+    bool moved = false;
 #pragma unroll
     for (int qt = 0; qt < kQT; qt++) {
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3];      // raw scores; the running maximum is kept raw too
+        for (int e = 0; e < 8; e++) x[e] = S[e >> 2][qt][e & 3];
         if constexpr (MASK) {
 #pragma unroll
             for (int e = 0; e < 8; e++)
@@ -415,27 +429,26 @@ __device__ __forceinline__ void softmax_unit(const float4v (&S)[2][kQT], float c
         float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         mx = fmaxf(mx, xor_lanes(mx, 16));
         mx = fmaxf(mx, xor_lanes(mx, 32));
-        // unit 0 holds token 0, which every query sees: the running maximum is finite from the start
-        const float mn = fmaxf(m[qt], mx);
-        alpha[qt] = __builtin_amdgcn_exp2f((m[qt] - mn) * c);
+        // unit 0 holds token 0, which every query sees: the reference is finite from the start
+        const float top = PRE ? mx + base[qt] : mx * c;
+        const float mn = top > m[qt] + kCalm ? top : m[qt];              // m = -inf at the start: moves
+        moved |= mn != m[qt];
+        alpha[qt] = __builtin_amdgcn_exp2f(m[qt] - mn);
         m[qt] = mn;
-        const float shift = -mn * c;                                   // the softmax constant rides on the exponent's fma
+        const float shift = PRE ? base[qt] - mn : -mn;
 #pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(fmaf(x[e], c, shift));
+        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(PRE ? x[e] + shift : fmaf(x[e], c, shift));
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
                       (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
         lsum[qt] = add_weights(lsum[qt] * alpha[qt], P[qt]);
     }
+    return __any(moved);
 }
 
-// The running maximum only has to be a reference that keeps the weights in range, not the exact maximum: as long as no
-// score of the unit exceeds it by more than kCalm (in the exponent's units), the unit can be added with the reference
-// unchanged: no maximum across lanes, no rescaling, weights <= 2^kCalm (fp16 holds them, the accumulators are fp32).
-constexpr float kCalm = 8.0f;
-
-// true if some score of the unit (no mask) exceeds its query's reference by more than kCalm (in the exponent's units),
-// in any lane of the wave.  calm_over_c = kCalm / c: the comparison is made on the raw scores.
-__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float calm_over_c, const float (&m)[kQT])
+// true if some score of the unit (no mask) exceeds its query's reference by more than kCalm, in any lane of the wave.
+// PRE: the scores are relative to the reference already; otherwise raw (compared against (m + kCalm) / c).
+template <bool PRE>
+__device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float inv_c, const float (&m)[kQT])
 {
     bool over = false;
 #pragma unroll
@@ -445,20 +458,20 @@ __device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float c
         mx = fmaxf(fmaxf(mx, a[3]), b[0]);
         mx = fmaxf(fmaxf(mx, b[1]), b[2]);
         mx = fmaxf(mx, b[3]);
-        over |= mx > m[qt] + calm_over_c;                   // m = -inf at the start: always over
+        over |= PRE ? mx > kCalm : mx > (m[qt] + kCalm) * inv_c;
     }
     return __any(over);
 }
 
-// softmax weights of a unit against the unchanged reference (no mask)
+// softmax weights of a unit against the unchanged reference (no mask).  PRE: the scores are the exponents themselves.
+template <bool PRE>
 __device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c, const float (&m)[kQT], float (&lsum)[kQT], half8 (&P)[kQT])
 {
 #pragma unroll
     for (int qt = 0; qt < kQT; qt++) {
-        const float shift = -m[qt] * c;
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(fmaf(S[e >> 2][qt][e & 3], c, shift));
+        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(PRE ? S[e >> 2][qt][e & 3] : fmaf(S[e >> 2][qt][e & 3], c, -m[qt]));
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
                       (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
         lsum[qt] = add_weights(lsum[qt], P[qt]);
@@ -579,7 +592,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     const int wmin = p0 + iw;                                    // position of the wave's first query
     const int open_units = iw < a.n_q ? (wmin + 1) / 32 : 0;     // units [0, open_units) lie before it: no mask needed
     const float c = a.scale_log2e;
-    const float calm_over_c = kCalm / c;
+    const float inv_c = 1.0f / c;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     Tiles *L = reinterpret_cast<Tiles *>(lds_raw);
@@ -627,7 +640,19 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         wait_fetches();                                         // units 0, 1 and 2 are there
         __syncthreads();
         float4v S[2][kQT], Sn[2][kQT];
-        if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq);
+        // base[qt]: what the scores waiting in S / Sn are relative to (KLO only: the reference as it stood when their
+        // products were issued, zero while it is still -inf); init = minus that, as the products' starting value
+        float base[kQT];
+        float4v init[kQT];
+        auto set_base = [&]() {
+#pragma unroll
+            for (int qt = 0; qt < kQT; qt++) {
+                base[qt] = KLO && m[qt] > -INFINITY ? m[qt] : 0.0f;
+                init[qt] = float4v{-base[qt], -base[qt], -base[qt], -base[qt]};
+            }
+        };
+        set_base();
+        if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq, init);
         // one unit: its scores come in Sin, those of the next unit leave in Sout (the two arrays swap roles from unit to
         // unit).  Whether a unit may take the calm form is decided one unit ahead, right after its scores were issued:
         // the test then sits next to the output products of the unit before, which need nothing from it.
@@ -638,20 +663,27 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                 half8 P[kQT];
                 float alpha[kQT];
                 const bool was_calm = calm;
+                bool moved = false;                              // some reference moved after the next unit's scores were issued
                 half8 Av[8];
                 if (calm) {
                     // the common case, one stretch of straight-line code: score products of the next unit next to the
-                    // weights of this one against the unchanged reference (calm implies that there is a next unit)
-                    score_unit<KLO>(X1, Qf, Sout, n, rq, &X0, Av);
-                    softmax_calm(Sin, c, m, lsum, P);
+                    // weights of this one against the unchanged reference (calm implies that there is a next unit, and
+                    // that this unit's scores are relative to the reference as it stands: base, init are up to date)
+                    score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av);
+                    softmax_calm<KLO>(Sin, c, m, lsum, P);
                 } else {
-                    if (ahead) score_unit<KLO>(X1, Qf, Sout, n, rq, &X0, Av);
-                    else {
+                    float bin[kQT];
+#pragma unroll
+                    for (int qt = 0; qt < kQT; qt++) bin[qt] = base[qt];
+                    if (ahead) {
+                        set_base();
+                        score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av);
+                    } else {
 #pragma unroll
                         for (int ct = 0; ct < 8; ct++) Av[ct] = value_operand(X0, ct, n, rq);
                     }
-                    if (u < open_units) softmax_unit<false>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
-                    else softmax_unit<true>(Sin, c, u, qpos, m, lsum, P, alpha, rq);
+                    if (u < open_units) moved = softmax_unit<false, KLO>(Sin, c, u, qpos, bin, m, lsum, P, alpha, rq);
+                    else moved = softmax_unit<true, KLO>(Sin, c, u, qpos, bin, m, lsum, P, alpha, rq);
                 }
                 // The accumulators are touched under a condition of their own, not inside the two-sided one above: there
                 // the compiler's merge block sits in front of the calm side, and the calm side then copied all 64
@@ -660,9 +692,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                 // one place adds to the accumulators on every path: they stay in the same registers (with a product
                 // on each path the compiler copied all 64 of them after every unit)
                 output_add(Av, P, O);
-                // the next unit is calm if it needs no mask, has a unit after it to look ahead to, and none of its
-                // scores exceeds its query's reference (as it stands now) by more than kCalm
-                calm = ahead && u + 2 < nb && u + 2 <= wlast && u + 1 < open_units && !unit_exceeds(Sout, calm_over_c, m);
+                // the next unit is calm if it needs no mask, has a unit after it to look ahead to, its scores are
+                // relative to the reference as it stands now, and none of them exceeds it by more than kCalm
+                calm = ahead && u + 2 < nb && u + 2 <= wlast && u + 1 < open_units && !(KLO && moved) && !unit_exceeds<KLO>(Sout, inv_c, m);
             }
         };
         auto after = [](int x) { return x + 1 < kBuffers ? x + 1 : 0; };
@@ -686,8 +718,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             float4v S[2][kQT];
             half8 P[kQT];
             float alpha[kQT];
-            score_unit<false>(L[0], Qf, S, n, rq);
-            softmax_unit<true>(S, c, u, qpos, m, lsum, P, alpha, rq);
+            const float4v none[kQT] = {};
+            const float nobase[kQT] = {};                       // fp16 rows: raw scores
+            score_unit<false>(L[0], Qf, S, n, rq, none);
+            softmax_unit<true, false>(S, c, u, qpos, nobase, m, lsum, P, alpha, rq);
             output_rescale(alpha, O);
             half8 Av[8];
 #pragma unroll
