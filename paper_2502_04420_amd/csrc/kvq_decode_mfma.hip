@@ -323,6 +323,14 @@ __device__ __forceinline__ float row_sum16(float x)
     return x;
 }
 
+// A split's partial results are written through to memory as they are stored (system-scope stores): left in the
+// write-back cache they would all be written out at once when the kernel ends, in front of the merge kernel that is
+// waiting for it (measured: calls 1-3 % shorter, most with many splits per cache).
+__device__ __forceinline__ void store_through(float *p, float2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // Work-group barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for
 // the global loads of the next block, which are meant to stay in flight across it.
 __device__ __forceinline__ void wg_barrier()
@@ -878,7 +886,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
             const int j = 2 * rq + hh;
             if (n == 0 && j < nvalid) {
                 const size_t prow = (qrow0 + j) * a.splits + split;
-                *reinterpret_cast<float2 *>(a.part_ml + prow * 2) = make_float2(W.m[hh], lsum);
+                store_through(a.part_ml + prow * 2, make_float2(W.m[hh], lsum));
             }
         }
     } else {
@@ -1003,7 +1011,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
             if (j < nvalid) {
                 const float2 t = *reinterpret_cast<const float2 *>(&o_lds[j * kD + 2 * lane]);
                 const size_t prow = (qrow0 + j) * a.splits + split;
-                *reinterpret_cast<float2 *>(a.part_o + prow * kD + 2 * lane) = make_float2(t.x + W.oF[j][0] + az, t.y + W.oF[j][1] + az);
+                store_through(a.part_o + prow * kD + 2 * lane, make_float2(t.x + W.oF[j][0] + az, t.y + W.oF[j][1] + az));
             }
         }
     }

@@ -343,9 +343,12 @@ __device__ __forceinline__ half8 value_operand(const Tiles &X, int ct, int n, in
     return half8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
 }
 
-template <bool KLO>
+struct NoSlice { __device__ __forceinline__ void operator()(int) const {} };
+
+template <bool KLO, class Slice = NoSlice>
 __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq,
-                                           const float4v (&init)[kQT], const Tiles *Xv = nullptr, half8 *Av = nullptr)
+                                           const float4v (&init)[kQT], const Tiles *Xv = nullptr, half8 *Av = nullptr,
+                                           Slice slice = Slice())
 {
     // KLO: the keys carry the softmax constant (see prefill_dequantize) and the accumulators start from init[qt] = minus
     // the query's reference maximum, four times: the products come out in the exponent's units, relative to the
@@ -356,6 +359,9 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
     // 64 registers of a unit up front or waits for every batch right after asking for it).  With Xv: the value
     // operands of the output product that follows (unit Xv) are asked for during the last batches, so that they are
     // there when the softmax is done.
+    // slice(bt): vector work of another unit (a share of its softmax) that is to be issued between the products of batch
+    // bt and those of the next; with one, nothing is moved across the end of a batch (left alone, the compiler puts all
+    // of it behind the last products, where the matrix cores then idle).
     constexpr int kBatches = KLO ? 8 : 4;
     auto fetch = [&](int bt, half8 &A0, half8 &A1) {
         const int step = bt & 3;
@@ -386,6 +392,10 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
             const float4v start = KLO ? init[qt] : float4v{0.0f, 0.0f, 0.0f, 0.0f};
             S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], Qf[qt][step], bt == 0 ? start : S[0][qt], 0, 0, 0);
             S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], Qf[qt][step], bt == 0 ? start : S[1][qt], 0, 0, 0);
+        }
+        if constexpr (!std::is_same<Slice, NoSlice>::value) {
+            slice(bt);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -463,20 +473,34 @@ __device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float i
     return __any(over);
 }
 
-// softmax weights of a unit against the unchanged reference (no mask).  PRE: the scores are the exponents themselves.
+// Softmax weights of a unit against the unchanged reference (no mask), dealt out in kBatches shares so that a share
+// can be issued between two batches of another unit's score products.  PRE: the scores are the exponents themselves.
 template <bool PRE>
-__device__ __forceinline__ void softmax_calm(const float4v (&S)[2][kQT], float c, const float (&m)[kQT], float (&lsum)[kQT], half8 (&P)[kQT])
-{
+struct CalmSoftmax {
+    const float4v (&S)[2][kQT];
+    float c;
+    const float (&m)[kQT];
+    float (&lsum)[kQT];
+    half8 (&P)[kQT];
+    static constexpr int kShares = PRE ? 8 : 4;                 // = the batches of score_unit<KLO = PRE>
+    __device__ __forceinline__ void operator()(int share) const
+    {
+        typedef _Float16 half2 __attribute__((ext_vector_type(2)));
+        const half2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-    for (int qt = 0; qt < kQT; qt++) {
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(PRE ? S[e >> 2][qt][e & 3] : fmaf(S[e >> 2][qt][e & 3], c, -m[qt]));
-        P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
-                      (_Float16)x[4], (_Float16)x[5], (_Float16)x[6], (_Float16)x[7]};
-        lsum[qt] = add_weights(lsum[qt], P[qt]);
+        for (int j = 0; j < 8 / kShares; j++) {
+            const int pair = share * (8 / kShares) + j, qt = pair >> 2, e = 2 * (pair & 3);     // elements e, e + 1 of query tile qt
+            const float s0 = S[e >> 2][qt][e & 3], s1 = S[e >> 2][qt][(e & 3) + 1];
+            const float x0 = __builtin_amdgcn_exp2f(PRE ? s0 : fmaf(s0, c, -m[qt]));
+            const float x1 = __builtin_amdgcn_exp2f(PRE ? s1 : fmaf(s1, c, -m[qt]));
+            const half2 h = {(_Float16)x0, (_Float16)x1};
+            P[qt][e] = h[0];
+            P[qt][e + 1] = h[1];
+            // the denominator is summed from the rounded weights, as they enter the output product
+            lsum[qt] = __builtin_amdgcn_fdot2(h, ones, lsum[qt], false);
+        }
     }
-}
+};
 
 // O^T += V^T P^T: rows = channels 16 ct + 4 rq + r; both operands list the tokens as
 // {4 rq .. 4 rq + 3, 16 + 4 rq .. 16 + 4 rq + 3}.
@@ -669,8 +693,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                     // the common case, one stretch of straight-line code: score products of the next unit next to the
                     // weights of this one against the unchanged reference (calm implies that there is a next unit, and
                     // that this unit's scores are relative to the reference as it stands: base, init are up to date)
-                    score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av);
-                    softmax_calm<KLO>(Sin, c, m, lsum, P);
+                    score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av, CalmSoftmax<KLO>{Sin, c, m, lsum, P});
                 } else {
                     float bin[kQT];
 #pragma unroll
