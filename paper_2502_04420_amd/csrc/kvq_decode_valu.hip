@@ -303,8 +303,10 @@ __global__ __launch_bounds__(256) void decode_valu(DecodeArgs a)
 
 // Merge the splits of one (batch, query head) by log-sum-exp and store fp16 (round to nearest even).
 // 512 threads: thread = (quarter g, channel d).  Quarter g merges the splits g, g + 4, g + 8, .., fetching
-// eight partial records at a time with independent loads (a plain loop would pay one memory latency per
-// split); the four quarter results are merged through LDS.  The order of all sums is fixed.
+// W partial records at a time with independent loads (a plain loop would pay one memory latency per
+// split; W = 16 for more than 32 splits, so that up to 64 splits are one round trip); the four quarter results are
+// merged through LDS.  The order of all sums is fixed.
+template <int W>
 __global__ __launch_bounds__(512) void combine_splits(DecodeArgs a)
 {
     const size_t row = blockIdx.x;
@@ -313,10 +315,10 @@ __global__ __launch_bounds__(512) void combine_splits(DecodeArgs a)
     const float *po = a.part_o + row * a.splits * kD + d;
     __shared__ float Mq[4], Lq[4], Oq[4][kD];
     float M = -INFINITY, L = 0.0f, O = 0.0f;
-    for (int s0 = g; s0 < a.splits; s0 += 32) {
-        float m8[8], l8[8], o8[8];
+    for (int s0 = g; s0 < a.splits; s0 += 4 * W) {
+        float m8[W], l8[W], o8[W];
 #pragma unroll
-        for (int k = 0; k < 8; k++) {
+        for (int k = 0; k < W; k++) {
             const int sp = s0 + 4 * k;
             const bool ok = sp < a.splits;
             m8[k] = ok ? ml[sp * 2] : -INFINITY;
@@ -325,11 +327,11 @@ __global__ __launch_bounds__(512) void combine_splits(DecodeArgs a)
         }
         float Mn = M;
 #pragma unroll
-        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, m8[k]);
+        for (int k = 0; k < W; k++) Mn = fmaxf(Mn, m8[k]);
         const float fo = exp2f(M - Mn);          // M = -inf on the first pass: factor 0 on empty sums
         L *= fo; O *= fo;
 #pragma unroll
-        for (int k = 0; k < 8; k++) {
+        for (int k = 0; k < W; k++) {
             const float f = exp2f(m8[k] - Mn);   // an absent split has m = -inf: factor 0
             L = fmaf(l8[k], f, L);
             O = fmaf(o8[k], f, O);
@@ -404,7 +406,8 @@ hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s)
 
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(combine_splits, dim3(a.B * a.Hq), dim3(512), 0, s, a);
+    if (a.splits > 32) hipLaunchKernelGGL(combine_splits<16>, dim3(a.B * a.Hq), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL(combine_splits<8>, dim3(a.B * a.Hq), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
