@@ -16,7 +16,7 @@ _lib = None
 
 EXPORTED = [
     "kvq_workspace_bytes", "kvq_configure", "kvq_quantize_append", "kvq_decode_attention", "kvq_decode_attention_noalloc", "kvq_debug_split_plan", "kvq_append_decode_attention", "kvq_prefill_attention",
-    "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
+    "kvq_layer_tokens", "kvq_reset", "kvq_debug_export", "kvq_set_decode_options", "kvq_set_prefill_options", "kvq_set_kernel_events", "kvq_destroy", "kvq_strerror",
     "kvq_last_error",
 ]
 
@@ -72,6 +72,8 @@ def load_library():
     lib.kvq_debug_export.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
     lib.kvq_set_decode_options.restype = c_int32
     lib.kvq_set_decode_options.argtypes = [c_void_p, c_int32, c_int32]
+    lib.kvq_set_prefill_options.restype = c_int32
+    lib.kvq_set_prefill_options.argtypes = [c_void_p, c_int32]
     lib.kvq_set_kernel_events.restype = c_int32
     lib.kvq_set_kernel_events.argtypes = [c_void_p, c_void_p, c_void_p]
     lib.kvq_destroy.restype = None
@@ -234,6 +236,9 @@ class KVQ:
 
     def set_decode_options(self, variant: int = 0, splits: int = 0):
         _check(self._lib.kvq_set_decode_options(self._h, variant, splits))
+
+    def set_prefill_options(self, low_parts: int = 0):
+        _check(self._lib.kvq_set_prefill_options(self._h, low_parts))
 
     def set_kernel_events(self, begin_event=None, end_event=None):
         """Raw hipEvent_t handles (integers or c_void_p) recorded around the main decode kernel; None switches off."""

@@ -66,7 +66,7 @@ struct LayerPlan {
 
 struct Plan {
     std::vector<LayerPlan> layer;
-    size_t part_o, part_ml, prefill_scratch, total;
+    size_t part_o, part_ml, prefill_scratch, prefill_select, total;
     int NB, RC;
     int prefill_chunk;      // (batch, kv head) caches whose dequantized units the prefill scratch holds at a time
 };
@@ -96,6 +96,7 @@ Plan make_plan(const kvq_config *c)
     p.part_ml = off; off = align_up(off + rows * kMaxSplits * 2 * sizeof(float));
     p.prefill_chunk = BH < (size_t)kPrefillChunk ? (int)BH : kPrefillChunk;
     p.prefill_scratch = off; off = align_up(off + (size_t)p.prefill_chunk * p.NB * kvq::prefill_unit_bytes());
+    p.prefill_select = off; off = align_up(off + BH * kvq::prefill_select_bytes());       // (a pass may take all caches)
     p.total = off;
     return p;
 }
@@ -111,6 +112,7 @@ struct kvq_ctx {
     hipStream_t stream;
     int variant;                    // 0 auto, 1 vector ALU, 2 matrix core
     int splits;                     // 0 auto
+    int prefill_low_parts;          // 0: chosen per cache, 1: every key channel keeps its low part
     hipEvent_t ev_begin, ev_end;    // recorded around the main decode kernel when both are set
 };
 
@@ -184,6 +186,7 @@ int kvq_configure(kvq_ctx **out, const kvq_config *cfg, void *workspace_device, 
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->variant = 0;
     c->splits = 0;
+    c->prefill_low_parts = 0;
     c->ev_begin = c->ev_end = nullptr;
     *out = c;
     return KVQ_OK;
@@ -427,6 +430,7 @@ int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32
     a.n_q = n_q;
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)kvq::kD));
     a.scratch = c->ws + c->plan.prefill_scratch;
+    a.select = nullptr;
     const bool timed = c->ev_begin && c->ev_end;
     const int BH = a.B * a.Hkv;
     // The caches are taken a chunk at a time: dequantize the chunk's packed units into the scratch area, attend.
@@ -440,10 +444,24 @@ int kvq_prefill_attention(kvq_ctx *c, int32_t layer, const void *q_device, int32
     } else if (a.n_blocks == 0) {
         chunk = BH;                                             // window only: nothing goes through the scratch area
     }
+    // Keys quantized per channel: one kernel in front decides for every cache which channels keep the low parts of
+    // their keys (one record per cache), unless the caller wants them kept for all.
+    uint8_t *select = nullptr;
+    bool begun = false;                                         // the first kernel of the call has taken ev_begin
+    if (c->prefill_low_parts == 0 && a.lv.kbits < 16 && !a.lv.kpt && a.n_blocks > 0) {
+        select = c->ws + c->plan.prefill_select;
+        a.bh0 = 0;
+        a.n_bh = BH;
+        a.select = select;
+        const hipError_t e = kvq::launch_prefill_select(a, c->stream, timed ? c->ev_begin : nullptr);
+        if (e != hipSuccess) return launch_failed("prefill channel selection kernel", e);
+        begun = true;
+    }
     for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
         a.bh0 = bh0;
         a.n_bh = BH - bh0 < chunk ? BH - bh0 : chunk;
-        const bool first = bh0 == 0, last = bh0 + chunk >= BH;
+        a.select = select ? select + (size_t)bh0 * kvq::prefill_select_bytes() : nullptr;
+        const bool first = bh0 == 0 && !begun, last = bh0 + chunk >= BH;
         const hipError_t e = kvq::launch_prefill_attention(a, c->stream, timed && first ? c->ev_begin : nullptr,
                                                            timed && last ? c->ev_end : nullptr);
         if (e != hipSuccess) return launch_failed("prefill attention kernels", e);
@@ -515,6 +533,13 @@ int kvq_set_decode_options(kvq_ctx *c, int32_t variant, int32_t splits)
     if (!c || variant < 0 || variant > 2 || splits < 0 || splits > kMaxSplits) return KVQ_EINVAL;
     c->variant = variant;
     c->splits = splits;
+    return KVQ_OK;
+}
+
+int kvq_set_prefill_options(kvq_ctx *c, int32_t low_parts)
+{
+    if (!c || low_parts < 0 || low_parts > 1) return KVQ_EINVAL;
+    c->prefill_low_parts = low_parts;
     return KVQ_OK;
 }
 

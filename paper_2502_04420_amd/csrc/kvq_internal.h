@@ -84,6 +84,9 @@ struct PrefillArgs {
     // scratch[n_bh][n_blocks][prefill_unit_bytes()] first
     uint8_t *scratch;
     int bh0, n_bh;
+    // one record of prefill_select_bytes() per cache of the launch (written and read by the launch's kernels): which 32
+    // key channels keep the remainders of their fp16 rounding, or that all do
+    uint8_t *select;
 };
 
 // Work units [u0, u1) of a split: units are the quantized blocks, then the chunks of <= 32 fp16 window tokens.  The
@@ -108,7 +111,12 @@ hipError_t launch_decode_valu(const DecodeArgs &a, hipStream_t s);
 // ev_begin / ev_end (both or neither): receive the start and stop time stamps of the kernel's own dispatch
 hipError_t launch_decode_mfma(const DecodeArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 size_t prefill_unit_bytes();     // scratch bytes per packed unit (32 tokens) of one (batch, kv head) cache
-// dequantizes the packed units of the caches [bh0, bh0 + n_bh) into the scratch area, then attends; ev_begin / ev_end
+size_t prefill_select_bytes();   // bytes of the channel-selection record of one (batch, kv head) cache
+// decides for the caches [bh0, bh0 + n_bh) which key channels keep their low parts (a.select: their records; layers with
+// packed, per-channel quantized keys only); ev_begin (may be null) receives the kernel's start
+hipError_t launch_prefill_select(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr);
+// dequantizes the packed units of the caches [bh0, bh0 + n_bh) into the scratch area (a.select: their selection
+// records, or null: every channel keeps its low part), then attends; ev_begin / ev_end
 // (either may be null) receive the start of the first and the end of the last kernel
 hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_combine(const DecodeArgs &a, hipStream_t s);

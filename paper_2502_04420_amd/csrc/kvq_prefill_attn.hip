@@ -4,7 +4,13 @@
 // design of Section 5.3): quantized tokens enter as X^ = Q(X) s + z (Eq. 2), window tokens as their fp16 values.
 //
 // This is a dense contraction (4 * D flops per query-token pair), so it runs on the matrix cores, in two passes over a
-// chunk of (batch, kv head) caches at a time:
+// chunk of (batch, kv head) caches at a time, behind one small kernel per call:
+//   0. prefill_select (keys quantized per channel): the low parts of the keys (below) cost a third of the matrix
+//      instructions, and they matter in the channels where keys and queries are large.  Per cache, from the stored
+//      scales and zero-points and a sample of the queries, the kernel picks the 32 channels where one fp16 rounding
+//      moves the logits most and checks that in all the others together it moves them by less than the fp16 softmax
+//      weights are rounded by anyway; then only those 32 keep their low parts (one batch of score products instead of
+//      four), otherwise all 128 do.
 //   1. prefill_dequantize: every packed unit (32 tokens) of the chunk is dequantized once, X^ = fma(code, s, z) in
 //      fp32, into a scratch area as fp16, in the layout the attention kernel keeps a unit in LDS: K^ as
 //      [token][channel], V^ transposed as [channel][token].  Dequantized keys are multiplied by the softmax constant
@@ -55,6 +61,23 @@ struct Tiles {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Which key channels of a (batch, kv head) cache keep the remainders of their fp16 rounding (prefill_select).  In the
+// compact form only the 32 selected channels do, and their remainders are stored as a tile [token][slot] of
+// kLoStride halves per row at the place of Tiles::Klo (the first 2.5 KiB of it): one batch of the score products
+// instead of four.
+struct Select {
+    uint8_t pos[kD];          // slot (0..31) of a channel's remainders in the compact tile, 255 = none kept
+    uint8_t chan[32];         // the channel of a slot
+    uint32_t compact;         // 0: every channel keeps its remainder (Tiles::Klo as declared)
+    uint8_t pad[92];
+};
+static_assert(sizeof(Select) == 256, "one record per cache");
+constexpr int kLoStride = 32 + 8;       // halves per row of the compact tile: 80 bytes = 20 banks, the 16-byte reads of a wave
+                                        // (16 rows x 4 pieces) fall on every bank exactly four times
+constexpr int kLoPieces = 3;            // KiB of the compact tile that are fetched (32 rows x 80 bytes = 2.5 KiB)
+// how the keys' low parts enter the attention kernel
+constexpr int kLoNone = 0, kLoAll = 1, kLoCompact = 2;
 
 // Metadata of the unit being dequantized (in LDS), one slab per wave (wave w dequantizes channel group w of the keys and of the
 // values, so it needs 32 scales and 32 zero-points of each tensor and nobody else's): written and read by the same
@@ -213,8 +236,10 @@ __device__ __forceinline__ void slab_meta8(const uint32_t *scales, const uint16_
 
 // kscale: the softmax constant log2(e) / sqrt(D), multiplied into the dequantized keys in fp32 before they are split
 // into two fp16 numbers: the attention kernel's score products then come out in the exponent's units.
+// sel: the cache's selection record when its low parts go into the compact tile, else null
 template <int BITS, bool KPT>
-__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c, float kscale)
+__device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c, float kscale,
+                                                const Select *sel = nullptr)
 {
     const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
     const bool narrow = lv.narrow != 0;
@@ -237,7 +262,17 @@ __device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, c
         *reinterpret_cast<u32x4 *>(&L.K[t][32 * cb + 8 * kq]) = pack8(x);
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
-        *reinterpret_cast<u32x4 *>(&L.Klo[t][32 * cb + 8 * kq]) = pack8(x);
+        if (sel) {
+            const u32x2 pw = *reinterpret_cast<const u32x2 *>(&sel->pos[32 * cb + 8 * kq]);
+            _Float16 *row = &L.Klo[0][0] + t * kLoStride;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const uint32_t slot = ((e < 4 ? pw[0] : pw[1]) >> (8 * (e & 3))) & 255u;
+                if (slot < 32u) row[slot] = (_Float16)x[e];
+            }
+        } else {
+            *reinterpret_cast<u32x4 *>(&L.Klo[t][32 * cb + 8 * kq]) = pack8(x);
+        }
     }
 }
 
@@ -288,7 +323,7 @@ __device__ __forceinline__ void load_packed(const PrefillArgs &a, int bh, int u,
 }
 
 template <bool KQ, bool VQ>
-__device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, const Stage &st, Tiles &L, MetaSlab &M)
+__device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, const Stage &st, Tiles &L, MetaSlab &M, const Select *sel)
 {
     if constexpr (KQ || VQ) {
         wave_lds_sync();                                   // the slab's readers of the unit before are done
@@ -297,13 +332,13 @@ __device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, cons
     }
     if constexpr (KQ) {
         if (a.lv.kpt) {
-            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
-            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
-            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
         } else {
-            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
-            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
-            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0, a.scale_log2e);
+            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
         }
     } else {
         store_key_rows(L, tid, st.k0, st.k1);
@@ -345,11 +380,17 @@ __device__ __forceinline__ half8 value_operand(const Tiles &X, int ct, int n, in
 
 struct NoSlice { __device__ __forceinline__ void operator()(int) const {} };
 
-template <bool KLO, class Slice = NoSlice>
-__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], float4v (&S)[2][kQT], int n, int rq,
-                                           const float4v (&init)[kQT], const Tiles *Xv = nullptr, half8 *Av = nullptr,
+// batches of score products per unit: four for the keys' 128 channels, then those of the low parts
+template <int LO> constexpr int score_batches() { return LO == kLoAll ? 8 : LO == kLoCompact ? 5 : 4; }
+
+// LO: how the low parts of quantized keys come (none: fp16 rows; all channels: Tiles::Klo; compact: the tile of the 32
+// selected channels, against Qlo = the queries' values at those channels).
+template <int LO, class Slice = NoSlice>
+__device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT][4], const half8 (&Qlo)[kQT], float4v (&S)[2][kQT],
+                                           int n, int rq, const float4v (&init)[kQT], const Tiles *Xv = nullptr, half8 *Av = nullptr,
                                            Slice slice = Slice())
 {
+    constexpr bool KLO = LO != kLoNone;
     // KLO: the keys carry the softmax constant (see prefill_dequantize) and the accumulators start from init[qt] = minus
     // the query's reference maximum, four times: the products come out in the exponent's units, relative to the
     // reference, and the common case of the softmax has neither a multiplication nor a subtraction left to do.
@@ -362,10 +403,14 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
     // slice(bt): vector work of another unit (a share of its softmax) that is to be issued between the products of batch
     // bt and those of the next; with one, nothing is moved across the end of a batch (left alone, the compiler puts all
     // of it behind the last products, where the matrix cores then idle).
-    constexpr int kBatches = KLO ? 8 : 4;
+    constexpr int kBatches = score_batches<LO>();
     auto fetch = [&](int bt, half8 &A0, half8 &A1) {
         const int step = bt & 3;
-        if (KLO && bt >= 4) {
+        if (LO == kLoCompact && bt >= 4) {
+            const _Float16 *lo = &X.Klo[0][0];
+            A0 = *reinterpret_cast<const half8 *>(lo + n * kLoStride + 8 * rq);
+            A1 = *reinterpret_cast<const half8 *>(lo + (16 + n) * kLoStride + 8 * rq);
+        } else if (KLO && bt >= 4) {
             A0 = *reinterpret_cast<const half8 *>(&X.Klo[n][32 * step + 8 * rq]);
             A1 = *reinterpret_cast<const half8 *>(&X.Klo[16 + n][32 * step + 8 * rq]);
         } else {
@@ -390,8 +435,9 @@ __device__ __forceinline__ void score_unit(const Tiles &X, const half8 (&Qf)[kQT
 #pragma unroll
         for (int qt = 0; qt < kQT; qt++) {
             const float4v start = KLO ? init[qt] : float4v{0.0f, 0.0f, 0.0f, 0.0f};
-            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], Qf[qt][step], bt == 0 ? start : S[0][qt], 0, 0, 0);
-            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], Qf[qt][step], bt == 0 ? start : S[1][qt], 0, 0, 0);
+            const half8 B = LO == kLoCompact && bt >= 4 ? Qlo[qt] : Qf[qt][step];
+            S[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A0[bt], B, bt == 0 ? start : S[0][qt], 0, 0, 0);
+            S[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[bt], B, bt == 0 ? start : S[1][qt], 0, 0, 0);
         }
         if constexpr (!std::is_same<Slice, NoSlice>::value) {
             slice(bt);
@@ -475,21 +521,21 @@ __device__ __forceinline__ bool unit_exceeds(const float4v (&S)[2][kQT], float i
 
 // Softmax weights of a unit against the unchanged reference (no mask), dealt out in kBatches shares so that a share
 // can be issued between two batches of another unit's score products.  PRE: the scores are the exponents themselves.
-template <bool PRE>
+template <bool PRE, int SHARES>
 struct CalmSoftmax {
     const float4v (&S)[2][kQT];
     float c;
     const float (&m)[kQT];
     float (&lsum)[kQT];
     half8 (&P)[kQT];
-    static constexpr int kShares = PRE ? 8 : 4;                 // = the batches of score_unit<KLO = PRE>
+    static constexpr int kShares = SHARES;                      // = the batches of the score products it rides with
     __device__ __forceinline__ void operator()(int share) const
     {
         typedef _Float16 half2 __attribute__((ext_vector_type(2)));
         const half2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-        for (int j = 0; j < 8 / kShares; j++) {
-            const int pair = share * (8 / kShares) + j, qt = pair >> 2, e = 2 * (pair & 3);     // elements e, e + 1 of query tile qt
+        for (int pair = 8 * share / kShares; pair < 8 * (share + 1) / kShares; pair++) {
+            const int qt = pair >> 2, e = 2 * (pair & 3);                                       // elements e, e + 1 of query tile qt
             const float s0 = S[e >> 2][qt][e & 3], s1 = S[e >> 2][qt][(e & 3) + 1];
             const float x0 = __builtin_amdgcn_exp2f(PRE ? s0 : fmaf(s0, c, -m[qt]));
             const float x1 = __builtin_amdgcn_exp2f(PRE ? s1 : fmaf(s1, c, -m[qt]));
@@ -521,6 +567,87 @@ __device__ __forceinline__ void output_rescale(const float (&alpha)[kQT], float4
         for (int ct = 0; ct < 8; ct++) O[ct][qt] *= alpha[qt];
 }
 
+// ---- pass 0 (per-channel quantized keys only): which channels of each cache keep the low parts of their keys.
+// A key rounded once to fp16 is off by up to 2^-11 of itself, and the logit by the sum over the channels of that times
+// the query's entry.  Per channel d this kernel estimates w_d = (mean square of the dequantized keys) x (mean square of
+// the queries): the keys' from the block metadata alone (a block's values of a channel lie in [z, z + s (2^bits - 1)],
+// taken as spread evenly), the queries' from up to 64 positions of every query head of the group.  The 32 channels of
+// largest w_d keep their low parts; if the w_d of all others add up to less than kSelectBudget, i.e. one fp16 rounding
+// of those channels moves a logit by less than 2^-11 / sqrt(3) * log2(e) / sqrt(D) * sqrt(kSelectBudget) = 6e-4 (root
+// mean square, in the exponent's units: below the 2^-11 by which the fp16 softmax weights are rounded anyway), the
+// cache takes the compact form; otherwise every channel keeps its low part.  Keys whose large channels are few
+// (the case the per-channel grouping is made for, Section 3.2) qualify; keys with a large offset on every channel do not.
+constexpr float kSelectBudget = 300.0f;
+constexpr int kSelectParts = 8;
+
+template <bool NARROW>
+__global__ __launch_bounds__(kD * kSelectParts) void prefill_select(PrefillArgs a)
+{
+    const int d = threadIdx.x & (kD - 1), part = threadIdx.x >> 7, local = blockIdx.x, bh = a.bh0 + local;
+    __shared__ float k2[kSelectParts][kD], q2[kSelectParts][kD], w[kD], rest[kD];
+    const float top = (float)((1 << a.lv.kbits) - 1);
+    float sk = 0.0f;
+    for (int u0 = part; u0 < a.n_blocks; u0 += 4 * kSelectParts) {
+        float sc[4], zp[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {                            // four blocks in flight
+            const int u = u0 + kSelectParts * k < a.n_blocks ? u0 + kSelectParts * k : u0;
+            const float *meta = a.lv.kmeta + ((size_t)bh * a.NB + u) * meta_words(NARROW);
+            sc[k] = NARROW ? half_bits(meta_scales16(meta)[d]) : meta[d];
+            zp[k] = half_bits(meta_zeros(meta, NARROW)[d]);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            if (u0 + kSelectParts * k < a.n_blocks) {
+                const float lo = zp[k], hi = fmaf(sc[k], top, lo);
+                sk += (lo * lo + lo * hi + hi * hi) * (1.0f / 3.0f);        // mean of x^2 over [lo, hi]
+            }
+        }
+    }
+    const int gq = a.Hq / a.Hkv, stride = (a.n_q + 63) / 64;
+    const int head0 = (bh / a.Hkv) * a.Hq + (bh % a.Hkv) * gq;
+    const int per_head = (a.n_q + stride - 1) / stride, samples = gq * per_head;
+    float sq = 0.0f;
+    for (int i0 = part; i0 < samples; i0 += 8 * kSelectParts) {
+        uint16_t x[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {                            // eight samples in flight
+            const int i = i0 + kSelectParts * k < samples ? i0 + kSelectParts * k : i0;
+            x[k] = a.q[((size_t)(head0 + i / per_head) * a.n_q + (size_t)(i % per_head) * stride) * kD + d];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const float v = i0 + kSelectParts * k < samples ? half_bits(x[k]) : 0.0f;
+            sq = fmaf(v, v, sq);
+        }
+    }
+    k2[part][d] = sk;
+    q2[part][d] = sq;
+    __syncthreads();
+    if (part == 0) {
+        float tk = 0.0f, tq = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kSelectParts; k++) { tk += k2[k][d]; tq += q2[k][d]; }
+        w[d] = (tk / (float)a.n_blocks) * (tq / (float)samples);
+    }
+    __syncthreads();
+    Select *sel = reinterpret_cast<Select *>(a.select) + local;
+    if (part == 0) {
+        const float mine = w[d];
+        int rank = 0;
+        for (int o = 0; o < kD; o++) rank += (w[o] > mine || (w[o] == mine && o < d)) ? 1 : 0;
+        sel->pos[d] = rank < 32 ? (uint8_t)rank : (uint8_t)255;
+        if (rank < 32) sel->chan[rank] = (uint8_t)d;
+        rest[d] = rank < 32 ? 0.0f : mine;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = 0.0f;
+        for (int o = 0; o < kD; o++) r += rest[o];
+        sel->compact = r < kSelectBudget ? 1u : 0u;              // (a sum that is not a number compares false: all channels)
+    }
+}
+
 // ---- pass 1: every packed unit of the (batch, kv head) caches [bh0, bh0 + n_bh) is dequantized once into the scratch
 // area, in the very layout the attention kernel keeps a unit in LDS (struct Tiles), so that pass 2 fetches plain copies.
 // KQ / VQ: the layer's keys / values are quantized (else fp16 rows in the code area).
@@ -532,8 +659,13 @@ __global__ __launch_bounds__(64 * kStagers) void prefill_dequantize(PrefillArgs 
     __shared__ __attribute__((aligned(16))) MetaSlab M[kStagers];
     Stage st;
     load_packed<KQ, VQ>(a, a.bh0 + local, u, T, tid, st);
+    const Select *sel = nullptr;
+    if (KQ && a.select) {
+        sel = reinterpret_cast<const Select *>(a.select) + local;
+        if (!sel->compact) sel = nullptr;
+    }
     Tiles &dst = *reinterpret_cast<Tiles *>(a.scratch + ((size_t)local * a.n_blocks + u) * sizeof(Tiles));
-    store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6]);
+    store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6], sel);
 }
 
 // A unit goes from the scratch area into an LDS buffer without passing through registers: a wave issues
@@ -552,17 +684,19 @@ __device__ __forceinline__ void fetch_piece(const uint8_t *unit, uint32_t offset
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(offset_of_lane), "s"(unit) : "memory", "m0");
 }
 
-// Wave `wave` fetches the pieces wave, wave + 8, ... of a unit; without low parts of the keys that tile is left out.
-template <bool KLO>
+// Wave `wave` fetches the pieces wave, wave + 8, ... of a unit.  Of the keys' low parts: none, the whole tile, or the
+// first kLoPieces KiB of it (the compact tile).
+template <int LO>
 __device__ __forceinline__ void fetch_unit(const uint8_t *unit, Tiles &L, int wave, int lane)
 {
-    constexpr int pieces = (KLO ? 3 : 2) * kTileKiB;
+    constexpr int lo_pieces = LO == kLoAll ? kTileKiB : LO == kLoCompact ? kLoPieces : 0;
+    constexpr int pieces = 2 * kTileKiB + lo_pieces;
     const uint32_t lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)reinterpret_cast<uint8_t *>(&L);
 #pragma unroll
     for (int i = 0; i < (pieces + kWaves - 1) / kWaves; i++) {
         const int p = wave + kWaves * i;                          // the same for all lanes of the wave
         if (p < pieces) {
-            const int off = 1024 * (KLO || p < kTileKiB ? p : p + kTileKiB);
+            const int off = 1024 * (p < kTileKiB + lo_pieces ? p : p - lo_pieces + kTileKiB);     // K^, low parts, then V^
             fetch_piece(unit, (uint32_t)(off + 16 * lane), lds + off);
         }
     }
@@ -581,28 +715,16 @@ __device__ __forceinline__ void wait_fetches() { asm volatile("s_waitcnt vmcnt(0
 // on each other), instead of waiting for each product's result in turn.
 constexpr int kBuffers = 5;
 
-template <bool KLO>
-__global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
+// LO: how the low parts of the keys come (score_unit); sel: the cache's selection record (kLoCompact).
+template <int LO>
+__device__ __forceinline__ void attend(const PrefillArgs &a, const Select *sel, int local, int jq, int rank)
 {
+    constexpr bool KLO = LO != kLoNone;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, rq = lane >> 4;
     const int tiles = (a.n_q + kQB - 1) / kQB;
     const int gq = a.Hq / a.Hkv;
-    // Work-groups go to the 8 XCDs in turn by their index, and each XCD has an L2 of its own: all query heads and
-    // query tiles that read one (batch, kv head) cache are given to one XCD (when the count divides), so that its
-    // units are fetched from memory once and then served by that L2.
-    int local, jq, rank;                                         // cache within this launch, query head within its group, order
-    if (a.n_bh % 8 == 0) {
-        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3, per = gq * tiles;
-        local = 8 * (k / per) + xcd;
-        jq = (k % per) % gq;
-        rank = (k % per) / gq;
-    } else {
-        local = blockIdx.x / (gq * tiles);
-        jq = (blockIdx.x / tiles) % gq;
-        rank = blockIdx.x % tiles;
-    }
     const int bh = a.bh0 + local;
     const int tile = tiles - 1 - rank;                           // the longest rows start first
     const int head = (bh / a.Hkv) * a.Hq + (bh % a.Hkv) * gq + jq;   // b * Hq + query head
@@ -623,7 +745,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
 
     // queries of this lane: iq[qt] = iw + 16 qt + n; past the end the last query is repeated and never stored
     int qpos[kQT];
-    half8 Qf[kQT][4];
+    half8 Qf[kQT][4], Qlo[kQT];
 #pragma unroll
     for (int qt = 0; qt < kQT; qt++) {
         const int i = iw + 16 * qt + n, ic = i < a.n_q ? i : a.n_q - 1;
@@ -631,6 +753,15 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         const uint16_t *row = a.q + ((size_t)head * a.n_q + ic) * kD;
 #pragma unroll
         for (int step = 0; step < 4; step++) Qf[qt][step] = __builtin_nontemporal_load(reinterpret_cast<const half8 *>(row + 32 * step + 8 * rq));
+        if constexpr (LO == kLoCompact) {
+            // the query's values at the channels of slots 8 rq .. 8 rq + 7: the operand that meets the compact tile
+            const u32x2 cw = *reinterpret_cast<const u32x2 *>(&sel->chan[8 * rq]);
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                Qlo[qt][e] = __builtin_bit_cast(_Float16, row[((e < 4 ? cw[0] : cw[1]) >> (8 * (e & 3))) & 127u]);
+        } else {
+            Qlo[qt] = half8{};
+        }
     }
 
     float4v O[8][kQT];
@@ -652,15 +783,19 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         const uint8_t *mine = a.scratch + (size_t)local * a.n_blocks * sizeof(Tiles);
         const int last = nb - 1;
         auto unit_at = [&](int u) { return mine + (size_t)(u < last ? u : last) * sizeof(Tiles); };
-        fetch_unit<KLO>(unit_at(0), L[0], wave, lane);
-        fetch_unit<KLO>(unit_at(1), L[1], wave, lane);
-        fetch_unit<KLO>(unit_at(2), L[2], wave, lane);
+        fetch_unit<LO>(unit_at(0), L[0], wave, lane);
+        fetch_unit<LO>(unit_at(1), L[1], wave, lane);
+        fetch_unit<LO>(unit_at(2), L[2], wave, lane);
         // The queries are first used under a condition; without this the compiler would keep their loads on its list
         // of pending ones inside the loop and wait there for everything in flight, the fetches just issued included.
 #pragma unroll
         for (int qt = 0; qt < kQT; qt++)
 #pragma unroll
             for (int step = 0; step < 4; step++) asm volatile("" ::"v"(Qf[qt][step]));
+        if constexpr (LO == kLoCompact) {
+#pragma unroll
+            for (int qt = 0; qt < kQT; qt++) asm volatile("" ::"v"(Qlo[qt]));
+        }
         wait_fetches();                                         // units 0, 1 and 2 are there
         __syncthreads();
         float4v S[2][kQT], Sn[2][kQT];
@@ -676,7 +811,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             }
         };
         set_base();
-        if (0 <= wlast) score_unit<KLO>(L[0], Qf, S, n, rq, init);
+        if (0 <= wlast) score_unit<LO>(L[0], Qf, Qlo, S, n, rq, init);
         // one unit: its scores come in Sin, those of the next unit leave in Sout (the two arrays swap roles from unit to
         // unit).  Whether a unit may take the calm form is decided one unit ahead, right after its scores were issued:
         // the test then sits next to the output products of the unit before, which need nothing from it.
@@ -693,14 +828,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
                     // the common case, one stretch of straight-line code: score products of the next unit next to the
                     // weights of this one against the unchanged reference (calm implies that there is a next unit, and
                     // that this unit's scores are relative to the reference as it stands: base, init are up to date)
-                    score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av, CalmSoftmax<KLO>{Sin, c, m, lsum, P});
+                    score_unit<LO>(X1, Qf, Qlo, Sout, n, rq, init, &X0, Av, CalmSoftmax<KLO, score_batches<LO>()>{Sin, c, m, lsum, P});
                 } else {
                     float bin[kQT];
 #pragma unroll
                     for (int qt = 0; qt < kQT; qt++) bin[qt] = base[qt];
                     if (ahead) {
                         set_base();
-                        score_unit<KLO>(X1, Qf, Sout, n, rq, init, &X0, Av);
+                        score_unit<LO>(X1, Qf, Qlo, Sout, n, rq, init, &X0, Av);
                     } else {
 #pragma unroll
                         for (int ct = 0; ct < 8; ct++) Av[ct] = value_operand(X0, ct, n, rq);
@@ -724,8 +859,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         int b0 = 0;                                              // buffer of unit u
         for (int u = 0; u < nb; u += 2) {
             const int b1 = after(b0), b2 = after(b1), b3 = after(b2), b4 = after(b3);
-            fetch_unit<KLO>(unit_at(u + 3), L[b3], wave, lane);  // buffers of units u - 2 and u - 1: all are done with them
-            fetch_unit<KLO>(unit_at(u + 4), L[b4], wave, lane);
+            fetch_unit<LO>(unit_at(u + 3), L[b3], wave, lane);  // buffers of units u - 2 and u - 1: all are done with them
+            fetch_unit<LO>(unit_at(u + 4), L[b4], wave, lane);
             step(u, L[b0], L[b1], S, Sn);
             if (u + 1 < nb) step(u + 1, L[b1], L[b2], Sn, S);
             wait_fetches();                                     // units u + 3 and u + 4 are there
@@ -743,7 +878,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
             float alpha[kQT];
             const float4v none[kQT] = {};
             const float nobase[kQT] = {};                       // fp16 rows: raw scores
-            score_unit<false>(L[0], Qf, S, n, rq, none);
+            score_unit<kLoNone>(L[0], Qf, Qlo, S, n, rq, none);
             softmax_unit<true, false>(S, c, u, qpos, nobase, m, lsum, P, alpha, rq);
             output_rescale(alpha, O);
             half8 Av[8];
@@ -771,23 +906,73 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
     }
 }
 
+// KQ: the layer's keys are quantized.  Each cache of such a layer is attended in the form its selection record names
+// (without records: low parts of all channels).
+template <bool KQ>
+__global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs a)
+{
+    const int tiles = (a.n_q + kQB - 1) / kQB;
+    const int gq = a.Hq / a.Hkv;
+    // Work-groups go to the 8 XCDs in turn by their index, and each XCD has an L2 of its own: all query heads and
+    // query tiles that read one (batch, kv head) cache are given to one XCD (when the count divides), so that its
+    // units are fetched from memory once and then served by that L2.
+    int local, jq, rank;                                         // cache within this launch, query head within its group, order
+    if (a.n_bh % 8 == 0) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3, per = gq * tiles;
+        local = 8 * (k / per) + xcd;
+        jq = (k % per) % gq;
+        rank = (k % per) / gq;
+    } else {
+        local = blockIdx.x / (gq * tiles);
+        jq = (blockIdx.x / tiles) % gq;
+        rank = blockIdx.x % tiles;
+    }
+    if constexpr (KQ) {
+        const Select *sel = a.select ? reinterpret_cast<const Select *>(a.select) + local : nullptr;
+        if (sel && __builtin_amdgcn_readfirstlane((int)sel->compact) != 0) attend<kLoCompact>(a, sel, local, jq, rank);
+        else attend<kLoAll>(a, nullptr, local, jq, rank);
+    } else {
+        attend<kLoNone>(a, nullptr, local, jq, rank);
+    }
+}
+
 }  // namespace
 
 
 size_t prefill_unit_bytes() { return sizeof(Tiles); }
+size_t prefill_select_bytes() { return sizeof(Select); }
+
+// Pass 0 for the caches [bh0, bh0 + n_bh) (a.select = their first record); only for layers whose keys are quantized
+// per channel and hold packed blocks.  ev_begin (may be null) receives the kernel's start.
+hipError_t launch_prefill_select(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin)
+{
+    if (!a.select || a.lv.kbits >= 16 || a.lv.kpt || a.n_blocks < 1 || a.n_bh < 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)a.n_bh), block(kD * kSelectParts);
+    auto launch = [&](auto kernel) {
+        if (ev_begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, nullptr, 0, a);
+        else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+    };
+    if (a.lv.narrow) launch(prefill_select<true>);
+    else launch(prefill_select<false>);
+    return hipGetLastError();
+}
 
 hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end)
 {
     const long long tiles = (a.n_q + kQB - 1) / kQB;
     const long long groups = tiles * a.n_bh * (a.Hq / a.Hkv);
     if (groups < 1 || groups > 0x7fffffffLL || a.n_bh < 1 || a.n_bh > 65535) return hipErrorInvalidConfiguration;
-    // pass 1 (its start stamps ev_begin when there is one; without packed units pass 2 does)
+    const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
+    // selection records only exist where launch_prefill_select could write them
+    if (a.select && !(kq && !a.lv.kpt && a.n_blocks > 0)) return hipErrorInvalidValue;
+    hipEvent_t begin = ev_begin;                                 // stamped by the start of the first kernel launched
     if (a.n_blocks > 0) {
+        // pass 1
         const dim3 grid((unsigned)a.n_blocks, (unsigned)a.n_bh), block(64 * kStagers);
-        const bool kq = a.lv.kbits < 16, vq = a.lv.vbits < 16;
         auto launch = [&](auto kernel) {
-            if (ev_begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, nullptr, 0, a);
+            if (begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, begin, nullptr, 0, a);
             else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+            begin = nullptr;
         };
         if (kq && vq) launch(prefill_dequantize<true, true>);
         else if (kq) launch(prefill_dequantize<true, false>);
@@ -799,19 +984,16 @@ hipError_t launch_prefill_attention(const PrefillArgs &a, hipStream_t s, hipEven
     // pass 2 (kBuffers tile buffers: more LDS than a kernel may declare statically)
     const dim3 grid((unsigned)groups), block(64 * kWaves);
     const size_t lds = kBuffers * sizeof(Tiles);
-    hipEvent_t b2 = a.n_blocks > 0 ? nullptr : ev_begin;
-    auto attend = [&](auto kernel) -> hipError_t {
+    auto attend_launch = [&](auto kernel) -> hipError_t {
         // the larger dynamic LDS size is asked for at every launch of either kernel, on whichever device is current:
         // a host-side setting, negligible next to a launch of milliseconds, and no process-wide state to keep
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        if (b2 || ev_end) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, b2, ev_end, 0, a);
+        if (begin || ev_end) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, begin, ev_end, 0, a);
         else hipLaunchKernelGGL(kernel, grid, block, lds, s, a);
-        return hipSuccess;
+        return hipGetLastError();
     };
-    const hipError_t e2 = a.lv.kbits < 16 ? attend(prefill_attention<true>) : attend(prefill_attention<false>);
-    if (e2 != hipSuccess) return e2;
-    return hipGetLastError();
+    return kq ? attend_launch(prefill_attention<true>) : attend_launch(prefill_attention<false>);
 }
 
 }  // namespace kvq

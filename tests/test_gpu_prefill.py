@@ -32,7 +32,7 @@ def assert_prefill_close(gpu_out, ora64, where=""):
     return rel
 
 
-def _run(kvq_mod, oracle_mod, w, n_q, meta=None, keys=None, max_tokens=None):
+def _run(kvq_mod, oracle_mod, w, n_q, meta=None, keys=None, max_tokens=None, low_parts=None):
     kw = {}
     if meta is not None:
         kw["meta_dtype"] = meta
@@ -45,6 +45,8 @@ def _run(kvq_mod, oracle_mod, w, n_q, meta=None, keys=None, max_tokens=None):
     K, V = W.kv_tokens(w, 0, 0, w.context)
     g.quantize_append(0, K.cuda(), V.cuda())
     o.quantize_append(0, K.numpy(), V.numpy())
+    if low_parts is not None:
+        g.set_prefill_options(low_parts)
     q = W.prefill_queries(w, 0, n_q)
     out = g.prefill_attention(0, q.cuda())
     o16, o64 = o.prefill_attention(0, q.numpy())
@@ -61,6 +63,37 @@ def test_all_precision_pairs_full_prompt(kvq_mod, oracle_mod, kb, vb):
     out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, w.context)
     assert g.layer_tokens(0) == (320, 51)
     assert_prefill_close(out, o64, "K%dV%d" % (kb, vb))
+    g.close()
+
+
+# keys: (channels multiplied, by how much, standard deviation of a per-channel offset)
+KEY_SHAPES = {"three large channels": (3, 12.0, 0.0), "no large channel": (0, 1.0, 0.0), "all channels 1.4x": (128, 1.4, 0.0),
+              "all channels 12x": (128, 12.0, 0.0), "offset on every channel": (0, 1.0, 20.0),
+              "large channels and offsets": (4, 12.0, 6.0)}
+
+
+@pytest.mark.parametrize("shape", list(KEY_SHAPES))
+@pytest.mark.parametrize("kb", [8, 4, 2])
+def test_low_parts_kept_for_all_channels_or_for_the_selected(kvq_mod, oracle_mod, shape, kb):
+    """The dequantized keys enter as two fp16 numbers; per cache the kernel keeps the second one for all channels or
+    for the 32 where it matters most (decided on the GPU from the stored metadata and the queries).  Whatever it decides
+    for keys of these kinds, the result meets the same bars as with the choice switched off (low_parts = 1)."""
+    n, mult, offs = KEY_SHAPES[shape]
+    w = W.Workload("lowparts", 1, 2, 8, 2, 128, 32 * 9 + 21, [kb], [4], seed=900 + kb, outlier_channels=n, outlier_scale=mult,
+                   key_bias_std=offs)
+    for low_parts in (0, 1):
+        out, o64, g, o, q = _run(kvq_mod, oracle_mod, w, w.context, low_parts=low_parts)
+        assert_prefill_close(out, o64, "%s K%d low_parts %d" % (shape, kb, low_parts))
+        g.close()
+
+
+def test_prefill_options_reject_unknown_values(kvq_mod):
+    g = kvq_mod.KVQ(1, 1, 4, 1, 128, 128, [4], [2])
+    for bad in (-1, 2):
+        with pytest.raises(kvq_mod.KVQError):
+            g.set_prefill_options(bad)
+    g.set_prefill_options(1)
+    g.set_prefill_options(0)
     g.close()
 
 
