@@ -248,23 +248,36 @@ def time_prefill_attention(torch, pkg, W, w, layer, reps=3, meta=None, keys=None
     cache.prefill_attention(0, q, out)
     torch.cuda.synchronize()
     hip = HipEvents()
-    evs = [(hip.create(), hip.create()) for _ in range(reps)]
-    for a, b in evs:
-        cache.set_kernel_events(a, b)
-        cache.prefill_attention(0, q, out)
-    cache.set_kernel_events(None, None)
-    torch.cuda.synchronize()
-    ms = [hip.elapsed_ms(a, b) for a, b in evs]
-    for a, b in evs:
-        hip.destroy(a)
-        hip.destroy(b)
-    avg = sum(ms) / len(ms)
+
+    def timed_calls(n):
+        evs = [(hip.create(), hip.create()) for _ in range(n)]
+        for a, b in evs:
+            cache.set_kernel_events(a, b)
+            cache.prefill_attention(0, q, out)
+        cache.set_kernel_events(None, None)
+        torch.cuda.synchronize()
+        ms = [hip.elapsed_ms(a, b) for a, b in evs]
+        for a, b in evs:
+            hip.destroy(a)
+            hip.destroy(b)
+        return sum(ms) / len(ms)
+
+    avg = timed_calls(reps)
+    # for reference, the same call with the per-cache choice of the key channels that keep their second fp16 number
+    # switched off (every channel keeps it): one call, not part of the figure
+    cache.set_prefill_options(1)
+    cache.prefill_attention(0, q, out)
+    all_channels_ms = timed_calls(1)
+    cache.set_prefill_options(0)
     flops = 4.0 * w.head_dim * (T * (T + 1) // 2) * w.batch * w.n_q_heads
     res = {"kernel": "prefill_attention<K%dV%d>" % (w.kbits[layer], w.vbits[layer]), "layer": layer, "queries": T,
            "launches_timed": reps, "avg_launch_ms": avg, "flops_per_launch": flops,
            "roofline": {"bound": "mfma", "achieved": flops / (avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": flops / (avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None},
-           "prompt_tokens_per_s_per_layer": w.batch * T / (avg * 1e-3)}
+           "prompt_tokens_per_s_per_layer": w.batch * T / (avg * 1e-3),
+           "low_parts": "second fp16 number of the dequantized keys kept per cache for all channels or for the 32 that need "
+                        "it (chosen on the GPU from the stored metadata and a sample of the queries)",
+           "ms_with_low_parts_of_all_channels": all_channels_ms}
     cache.close()
     del cache, q, out
     torch.cuda.empty_cache()
