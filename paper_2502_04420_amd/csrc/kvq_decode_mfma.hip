@@ -145,14 +145,13 @@ struct BlockStream {
     uint32_t l16, l8, l4;                    // this lane's byte offsets into 16-, 8- and 4-byte-per-lane pieces
 };
 
-// A resource of zero bytes: every load through it is out of range, touches no memory and returns zero.  The loop
-// issues its loads unconditionally (so that the number of loads behind a block is a constant); past the end of the
-// group's range they go through this resource.
-__device__ __forceinline__ i32x4 null_buffer() { return i32x4{0, 0, 0, 0x00020000}; }
+// The loop issues its loads unconditionally (so that the number of loads behind a block is a constant); past the end of
+// the group's range they go through a resource with no bytes in range: every load through it is out of range, touches
+// no memory and returns zero.
+// r, or r with no bytes in range: one scalar select
 __device__ __forceinline__ i32x4 pick(bool real, const i32x4 &r)
 {
-    const i32x4 z = null_buffer();
-    return i32x4{real ? r[0] : z[0], real ? r[1] : z[1], real ? r[2] : z[2], real ? r[3] : z[3]};
+    return i32x4{r[0], r[1], real ? r[2] : 0, r[3]};
 }
 
 __device__ __forceinline__ i32x4 buffer_words(const void *base, int bytes = 0x7fffffff)
@@ -386,13 +385,18 @@ struct ValueState {
 // ended 4 us behind the first ones (of 28) although all have the same work; with the priority tied to the progress a
 // wave that falls behind is served first until it has caught up (the spread between the first and the last tenth of
 // the waves to finish went from 6.3 us to 4.3 us).
-__device__ __forceinline__ void priority_by_blocks_left(int left, int total)
+// The priority is 3 for the first quarter of the sweep (set before it) and drops by one at the steps where another
+// quarter of the blocks is done: three scalar compares per step.
+struct PrioritySteps { int to2, to1, to0; };
+__device__ __forceinline__ PrioritySteps priority_steps(int total)
 {
-    const int q = __builtin_amdgcn_readfirstlane(4 * left > 3 * total ? 3 : 4 * left > 2 * total ? 2 : 4 * left > total ? 1 : 0);
-    if (q == 3) __builtin_amdgcn_s_setprio(3);
-    else if (q == 2) __builtin_amdgcn_s_setprio(2);
-    else if (q == 1) __builtin_amdgcn_s_setprio(1);
-    else __builtin_amdgcn_s_setprio(0);
+    return PrioritySteps{(total + 3) >> 2, (total + 1) >> 1, (3 * total + 3) >> 2};
+}
+__device__ __forceinline__ void priority_at_step(int i, const PrioritySteps &t)
+{
+    if (i == t.to0) __builtin_amdgcn_s_setprio(0);
+    else if (i == t.to1) __builtin_amdgcn_s_setprio(1);
+    else if (i == t.to2) __builtin_amdgcn_s_setprio(2);
 }
 
 // ------------------------------------------------------------------ key wave
@@ -801,6 +805,8 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
             // there are any) are in flight.
             // The sweep goes in chunks of kChunk steps (one register of exponent words each); a chunk starts at stage 0.
             await_exponents<(DK - 1) * NLK>(kexp);                         // the first chunk's: issued ahead of the first blocks
+            const PrioritySteps prio = priority_steps(n1);
+            if (n1 > 0) __builtin_amdgcn_s_setprio(3);
             for (int c0 = 0; c0 < n1; c0 += kChunk) {
                 if (c0 > 0) {
                     issue_exponents(kexp, KS, exp_offset(c0));
@@ -824,7 +830,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
 #pragma unroll
                         for (int d = 0; d < DK; d++) {
                             if (more) {
-                                priority_by_blocks_left(n1 - i, n1);
+                                priority_at_step(i, prio);
                                 issue_block<KB, NARROW, !kZB>(KS, i + DK - 1 < n1, blk1c(i + DK - 1), kr[(d + DK - 1) % DK]);
                                 if constexpr (kZB) await_loads_either<(DK - 1) * NLK, 4, KB>(kr[d], __builtin_amdgcn_readfirstlane(i == z0 ? 1 : 0));
                                 else await_block<KB, DK>(kr[d]);
@@ -841,6 +847,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
                     }
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int d = 0; d < DK; d++) await_loads<0, KB>(kr[d]);      // the empty loads past the end of the range, before
             await_exponents<0>(kexp);                                    // their registers go back to the compiler
@@ -930,6 +937,8 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
         wg_barrier();                                   // the key wave has produced the first unit
         if constexpr (kFast) {
             await_exponents<(DV - 1) * block_loads<VB>()>(vexp);
+            const PrioritySteps prio = priority_steps(n1);
+            if (n1 > 0) __builtin_amdgcn_s_setprio(3);
             for (int c0 = 0; c0 < n1; c0 += kChunk) {
                 if (c0 > 0) {
                     issue_exponents(vexp, VS, exp_offset(c0));
@@ -941,7 +950,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
 #pragma unroll
                     for (int d = 0; d < DV; d++) {
                         if (more) {
-                            priority_by_blocks_left(n1 - i, n1);
+                            priority_at_step(i, prio);
                             issue_block<VB, NARROW>(VS, i + DV - 1 < n1, blk1c(i + DV - 1), vr[(d + DV - 1) % DV]);
                             await_block<VB, DV>(vr[d]);
                             const uint32_t ew = (uint32_t)__builtin_amdgcn_readlane((int)vexp, i - c0);
@@ -957,6 +966,7 @@ __global__ __launch_bounds__(128, (resident_waves<KB, VB>())) void decode_mfma(D
                     }
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int d = 0; d < DV; d++) await_loads<0, VB>(vr[d]);
             await_exponents<0>(vexp);
