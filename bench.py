@@ -223,7 +223,7 @@ def time_workload(torch, pkg, W, w, steps, warmup, variant=0, splits=0, per_kern
 MFMA_F16_PEAK_TFLOPS = 2500.0     # MI355X dense fp16 matrix-core peak
 
 
-def time_prefill_attention(torch, pkg, W, w, layer, reps=3, meta=None, keys=None):
+def time_prefill_attention(torch, pkg, W, w, layer, reps=3, meta=None, keys=None, reference=True):
     """The prompt's own causal attention over the dequantized cache of one layer (every position a query), timed
     between HIP events stamped by the kernel's own dispatch.  Algorithmic flops: 4 * head_dim per (query, visible
     token) pair and query head."""
@@ -265,18 +265,20 @@ def time_prefill_attention(torch, pkg, W, w, layer, reps=3, meta=None, keys=None
     avg = timed_calls(reps)
     # for reference, the same call with the per-cache choice of the key channels that keep their second fp16 number
     # switched off (every channel keeps it): one call, not part of the figure
-    cache.set_prefill_options(1)
-    cache.prefill_attention(0, q, out)
-    all_channels_ms = timed_calls(1)
-    cache.set_prefill_options(0)
+    all_channels_ms = None
+    if reference:
+        cache.set_prefill_options(1)
+        cache.prefill_attention(0, q, out)
+        all_channels_ms = timed_calls(1)
+        cache.set_prefill_options(0)
     flops = 4.0 * w.head_dim * (T * (T + 1) // 2) * w.batch * w.n_q_heads
     res = {"kernel": "prefill_attention<K%dV%d>" % (w.kbits[layer], w.vbits[layer]), "layer": layer, "queries": T,
            "launches_timed": reps, "avg_launch_ms": avg, "flops_per_launch": flops,
            "roofline": {"bound": "mfma", "achieved": flops / (avg * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": flops / (avg * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None},
            "prompt_tokens_per_s_per_layer": w.batch * T / (avg * 1e-3),
-           "low_parts": "second fp16 number of the dequantized keys kept per cache for all channels or for the 32 that need "
-                        "it (chosen on the GPU from the stored metadata and a sample of the queries)",
+           "low_parts": "dequantized keys centred per channel; their second fp16 number kept per cache for all channels or for "
+                        "the 32 that need it (chosen on the GPU from the stored metadata and a sample of the queries)",
            "ms_with_low_parts_of_all_channels": all_channels_ms}
     cache.close()
     del cache, q, out
@@ -434,6 +436,9 @@ def main():
                          "enough bytes per launch for the kernels' steady state)")
     ap.add_argument("--no-prefill-attn", action="store_true",
                     help="skip the extra measurement of the prefill-stage attention kernel (one layer of the dominant pair)")
+    ap.add_argument("--no-prefill-reference", action="store_true",
+                    help="prefill attention: skip the extra call with the per-cache treatment of the keys switched off "
+                         "(used for profiling runs, whose per-kernel means would mix the two)")
     ap.add_argument("--only", default="", help="time just 'mix' or 'kv8' (used for profiling runs)")
     ap.add_argument("--no-extra-configs", action="store_true",
                     help="skip the two further benchmark configurations timed after the main one: the Qwen2.5-7B shape "
@@ -552,7 +557,8 @@ def main():
         dom_layers = [l for l in range(w_main.n_layers) if "K%dV%d" % (w_main.kbits[l], w_main.vbits[l]) == dom]
         out["prefill_attention"] = time_prefill_attention(
             torch, pkg, W, w_main, dom_layers[len(dom_layers) // 2],
-            meta=pkg.META_FP16 if args.meta == "fp16" else None, keys=pkg.KEYS_PER_TOKEN if KEYS_PER_TOKEN else None)
+            meta=pkg.META_FP16 if args.meta == "fp16" else None, keys=pkg.KEYS_PER_TOKEN if KEYS_PER_TOKEN else None,
+            reference=not args.no_prefill_reference)
         # HBM bytes of one call (all its launches: dequantization passes and attention passes), from the counter record
         rec = read_traffic("prefill_attention:" + w_main.name + ":" + dom + (":scales-fp16" if args.meta == "fp16" else "") +
                            (":keys-per-token" if KEYS_PER_TOKEN else ""))

@@ -190,12 +190,14 @@ int kvq_append_decode_attention(kvq_ctx *ctx, int32_t layer, const void *k_devic
  * of (batch, kv head) caches: one dequantizes their packed tokens once into a scratch area
  * inside the workspace (16 * floor(max_tokens / 32) * 27 KiB, counted by kvq_workspace_bytes:
  * 16 caches per pass at full length, more when the layer holds fewer tokens), one attends.  For
- * keys quantized per channel, one kernel in front of the passes decides per cache which channels
- * keep the second fp16 number of their keys: all, or (when one fp16 rounding of the others
- * moves a logit by less than the fp16 softmax weights are rounded by anyway, judged from the
- * stored scales and zero-points and a sample of the queries) only the 32 channels where it
- * matters most, which shortens the call by a seventh (kvq_set_prefill_options switches the
- * choice off).  With kernel events set (kvq_set_kernel_events) they receive the start of the
+ * keys quantized per channel, one kernel in front of the passes finds, per cache and from the
+ * stored scales and zero-points, the centre of every channel's keys, which is taken off the
+ * dequantized keys before they are rounded (a constant per channel moves all scores of a query
+ * alike, so the softmax is unchanged; the fp16 window's scores are lowered to match), and decides
+ * which channels keep the second fp16 number of their keys: all, or (when one fp16 rounding of
+ * the others moves a logit by less than the fp16 softmax weights are rounded by anyway, judged
+ * from the same metadata and a sample of the queries) only the 32 channels where it matters
+ * most, which shortens the call by a seventh (kvq_set_prefill_options switches both off).  With kernel events set (kvq_set_kernel_events) they receive the start of the
  * first and the end of the last of these kernels.
  */
 int kvq_prefill_attention(kvq_ctx *ctx, int32_t layer, const void *q_device, int32_t n_q, void *out_device);
@@ -245,9 +247,10 @@ int kvq_debug_split_plan(const kvq_config *cfg, int32_t layer, int32_t n_tokens,
 int kvq_set_decode_options(kvq_ctx *ctx, int32_t variant, int32_t splits);
 
 /*
- * Tuning knob of kvq_prefill_attention (optional).  low_parts: 0 = per cache, keep the second
- * fp16 number of the dequantized keys for all channels or for the 32 that need it (default, see
- * kvq_prefill_attention); 1 = for all channels of every cache.  Returns KVQ_EINVAL for other values.
+ * Tuning knob of kvq_prefill_attention (optional).  low_parts: 0 = per cache, centre the
+ * dequantized keys and keep their second fp16 number for all channels or for the 32 that need
+ * it (default, see kvq_prefill_attention); 1 = keys as dequantized, second number for all
+ * channels of every cache.  Returns KVQ_EINVAL for other values.
  */
 int kvq_set_prefill_options(kvq_ctx *ctx, int32_t low_parts);
 

@@ -7,10 +7,13 @@
 // chunk of (batch, kv head) caches at a time, behind one small kernel per call:
 //   0. prefill_select (keys quantized per channel): the low parts of the keys (below) cost a third of the matrix
 //      instructions, and they matter in the channels where keys and queries are large.  Per cache, from the stored
-//      scales and zero-points and a sample of the queries, the kernel picks the 32 channels where one fp16 rounding
-//      moves the logits most and checks that in all the others together it moves them by less than the fp16 softmax
-//      weights are rounded by anyway; then only those 32 keep their low parts (one batch of score products instead of
-//      four), otherwise all 128 do.
+//      scales and zero-points and a sample of the queries, the kernel (a) finds every channel's centre, which pass 1
+//      takes off the dequantized keys: a constant per channel moves all scores of a query alike and the softmax does
+//      not see it, so an offset that a channel's keys share no longer costs fp16 precision (the window's fp16 rows keep
+//      theirs; their scores are lowered by q . centre instead); (b) picks the 32 channels where one fp16 rounding of
+//      the centred keys moves the logits most and checks that in all the others together it moves them by less than
+//      the fp16 softmax weights are rounded by anyway; then only those 32 keep their low parts (one batch of score
+//      products instead of four), otherwise all 128 do.
 //   1. prefill_dequantize: every packed unit (32 tokens) of the chunk is dequantized once, X^ = fma(code, s, z) in
 //      fp32, into a scratch area as fp16, in the layout the attention kernel keeps a unit in LDS: K^ as
 //      [token][channel], V^ transposed as [channel][token].  Dequantized keys are multiplied by the softmax constant
@@ -71,8 +74,9 @@ struct Select {
     uint8_t chan[32];         // the channel of a slot
     uint32_t compact;         // 0: every channel keeps its remainder (Tiles::Klo as declared)
     uint8_t pad[92];
+    float centre[kD];         // per channel: subtracted from every dequantized key of the cache before it is rounded
 };
-static_assert(sizeof(Select) == 256, "one record per cache");
+static_assert(sizeof(Select) == 768, "one record per cache");
 constexpr int kLoStride = 32 + 8;       // halves per row of the compact tile: 80 bytes = 20 banks, the 16-byte reads of a wave
                                         // (16 rows x 4 pieces) fall on every bank exactly four times
 constexpr int kLoPieces = 3;            // KiB of the compact tile that are fetched (32 rows x 80 bytes = 2.5 KiB)
@@ -236,15 +240,25 @@ __device__ __forceinline__ void slab_meta8(const uint32_t *scales, const uint16_
 
 // kscale: the softmax constant log2(e) / sqrt(D), multiplied into the dequantized keys in fp32 before they are split
 // into two fp16 numbers: the attention kernel's score products then come out in the exponent's units.
-// sel: the cache's selection record when its low parts go into the compact tile, else null
+// rec: the cache's selection record or null; compact: its low parts go into the compact tile
 template <int BITS, bool KPT>
 __device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, const MetaSlab &M, int tid, u32x4 c, float kscale,
-                                                const Select *sel = nullptr)
+                                                const Select *rec, bool compact)
 {
     const int l = tid & 63, cb = tid >> 6, n = l & 15, kq = l >> 4;
     const bool narrow = lv.narrow != 0;
     float s[8], z[8];
-    if constexpr (!KPT) slab_meta8(M.ks, M.kz, narrow, 8 * kq, s, z);          // one (s, z) per channel
+    if constexpr (!KPT) {
+        slab_meta8(M.ks, M.kz, narrow, 8 * kq, s, z);                          // one (s, z) per channel
+        if (rec) {
+            // the channel's centre goes off with the zero-point: a constant per channel moves every score of a query
+            // alike, which the softmax does not see (window tokens: see attend)
+            const float4 c0 = *reinterpret_cast<const float4 *>(&rec->centre[32 * cb + 8 * kq]);
+            const float4 c1 = *reinterpret_cast<const float4 *>(&rec->centre[32 * cb + 8 * kq + 4]);
+            z[0] -= c0.x; z[1] -= c0.y; z[2] -= c0.z; z[3] -= c0.w;
+            z[4] -= c1.x; z[5] -= c1.y; z[6] -= c1.z; z[7] -= c1.w;
+        }
+    }
 #pragma unroll
     for (int th = 0; th < 2; th++) {
         const int t = 16 * th + n;
@@ -262,8 +276,8 @@ __device__ __forceinline__ void store_key_codes(const LayerView &lv, Tiles &L, c
         *reinterpret_cast<u32x4 *>(&L.K[t][32 * cb + 8 * kq]) = pack8(x);
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] -= (float)(_Float16)x[e];
-        if (sel) {
-            const u32x2 pw = *reinterpret_cast<const u32x2 *>(&sel->pos[32 * cb + 8 * kq]);
+        if (compact) {
+            const u32x2 pw = *reinterpret_cast<const u32x2 *>(&rec->pos[32 * cb + 8 * kq]);
             _Float16 *row = &L.Klo[0][0] + t * kLoStride;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
@@ -323,8 +337,9 @@ __device__ __forceinline__ void load_packed(const PrefillArgs &a, int bh, int u,
 }
 
 template <bool KQ, bool VQ>
-__device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, const Stage &st, Tiles &L, MetaSlab &M, const Select *sel)
+__device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, const Stage &st, Tiles &L, MetaSlab &M, const Select *rec)
 {
+    const bool compact = rec && rec->compact != 0;
     if constexpr (KQ || VQ) {
         wave_lds_sync();                                   // the slab's readers of the unit before are done
         store_meta_piece(M, tid & 63, st.m);
@@ -332,13 +347,13 @@ __device__ __forceinline__ void store_packed(const PrefillArgs &a, int tid, cons
     }
     if constexpr (KQ) {
         if (a.lv.kpt) {
-            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
-            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
-            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            if (a.lv.kbits == 8) store_key_codes<8, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
+            else if (a.lv.kbits == 4) store_key_codes<4, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
+            else store_key_codes<2, true>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
         } else {
-            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
-            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
-            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, sel);
+            if (a.lv.kbits == 8) store_key_codes<8, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
+            else if (a.lv.kbits == 4) store_key_codes<4, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
+            else store_key_codes<2, false>(a.lv, L, M, tid, st.k0, a.scale_log2e, rec, compact);
         }
     } else {
         store_key_rows(L, tid, st.k0, st.k1);
@@ -465,7 +480,8 @@ constexpr float kCalm = 8.0f;
 // Online softmax in base 2 of the unit's scores, exact form: weights P (fp16, already in the operand order of the output
 // product), reference m, partial sums lsum, and the factors alpha by which the accumulators shrink.  Returns whether
 // some reference moved (in any lane).
-// PRE: the scores are in the exponent's units and relative to base[qt] (score_unit with KLO); otherwise raw, times c.
+// PRE: the scores are in the exponent's units and relative to base[qt] (score_unit with KLO); otherwise raw: the
+// exponent is score * c + base[qt].
 // MASK: the unit reaches beyond some query's position.
 template <bool MASK, bool PRE>
 __device__ __forceinline__ bool softmax_unit(const float4v (&S)[2][kQT], float c, int u, const int (&qpos)[kQT], const float (&base)[kQT],
@@ -486,12 +502,12 @@ __device__ __forceinline__ bool softmax_unit(const float4v (&S)[2][kQT], float c
         mx = fmaxf(mx, xor_lanes(mx, 16));
         mx = fmaxf(mx, xor_lanes(mx, 32));
         // unit 0 holds token 0, which every query sees: the reference is finite from the start
-        const float top = PRE ? mx + base[qt] : mx * c;
+        const float top = PRE ? mx + base[qt] : fmaf(mx, c, base[qt]);
         const float mn = top > m[qt] + kCalm ? top : m[qt];              // m = -inf at the start: moves
         moved |= mn != m[qt];
         alpha[qt] = __builtin_amdgcn_exp2f(m[qt] - mn);
         m[qt] = mn;
-        const float shift = PRE ? base[qt] - mn : -mn;
+        const float shift = base[qt] - mn;
 #pragma unroll
         for (int e = 0; e < 8; e++) x[e] = __builtin_amdgcn_exp2f(PRE ? x[e] + shift : fmaf(x[e], c, shift));
         P[qt] = half8{(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3],
@@ -569,14 +585,16 @@ __device__ __forceinline__ void output_rescale(const float (&alpha)[kQT], float4
 
 // ---- pass 0 (per-channel quantized keys only): which channels of each cache keep the low parts of their keys.
 // A key rounded once to fp16 is off by up to 2^-11 of itself, and the logit by the sum over the channels of that times
-// the query's entry.  Per channel d this kernel estimates w_d = (mean square of the dequantized keys) x (mean square of
-// the queries): the keys' from the block metadata alone (a block's values of a channel lie in [z, z + s (2^bits - 1)],
+// the query's entry.  Per channel d this kernel estimates the centre of the dequantized keys (the mean of the blocks'
+// midpoints, rounded to fp16) and w_d = (mean square of the keys about that centre) x (mean square of the queries):
+// the keys' from the block metadata alone (a block's values of a channel lie in [z, z + s (2^bits - 1)],
 // taken as spread evenly), the queries' from up to 64 positions of every query head of the group.  The 32 channels of
 // largest w_d keep their low parts; if the w_d of all others add up to less than kSelectBudget, i.e. one fp16 rounding
 // of those channels moves a logit by less than 2^-11 / sqrt(3) * log2(e) / sqrt(D) * sqrt(kSelectBudget) = 6e-4 (root
 // mean square, in the exponent's units: below the 2^-11 by which the fp16 softmax weights are rounded anyway), the
 // cache takes the compact form; otherwise every channel keeps its low part.  Keys whose large channels are few
-// (the case the per-channel grouping is made for, Section 3.2) qualify; keys with a large offset on every channel do not.
+// (the case the per-channel grouping is made for, Section 3.2) qualify, and so do keys with a large offset on every
+// channel (the offsets are centred away); keys that are large and widely spread on many channels do not.
 constexpr float kSelectBudget = 300.0f;
 constexpr int kSelectParts = 8;
 
@@ -584,9 +602,9 @@ template <bool NARROW>
 __global__ __launch_bounds__(kD * kSelectParts) void prefill_select(PrefillArgs a)
 {
     const int d = threadIdx.x & (kD - 1), part = threadIdx.x >> 7, local = blockIdx.x, bh = a.bh0 + local;
-    __shared__ float k2[kSelectParts][kD], q2[kSelectParts][kD], w[kD], rest[kD];
+    __shared__ float k1[kSelectParts][kD], k2[kSelectParts][kD], q2[kSelectParts][kD], w[kD], rest[kD];
     const float top = (float)((1 << a.lv.kbits) - 1);
-    float sk = 0.0f;
+    float sk = 0.0f, sm = 0.0f;
     for (int u0 = part; u0 < a.n_blocks; u0 += 4 * kSelectParts) {
         float sc[4], zp[4];
 #pragma unroll
@@ -601,6 +619,7 @@ __global__ __launch_bounds__(kD * kSelectParts) void prefill_select(PrefillArgs 
             if (u0 + kSelectParts * k < a.n_blocks) {
                 const float lo = zp[k], hi = fmaf(sc[k], top, lo);
                 sk += (lo * lo + lo * hi + hi * hi) * (1.0f / 3.0f);        // mean of x^2 over [lo, hi]
+                sm += 0.5f * (lo + hi);
             }
         }
     }
@@ -621,17 +640,24 @@ __global__ __launch_bounds__(kD * kSelectParts) void prefill_select(PrefillArgs 
             sq = fmaf(v, v, sq);
         }
     }
+    k1[part][d] = sm;
     k2[part][d] = sk;
     q2[part][d] = sq;
     __syncthreads();
+    Select *sel = reinterpret_cast<Select *>(a.select) + local;
     if (part == 0) {
-        float tk = 0.0f, tq = 0.0f;
+        float tm = 0.0f, tk = 0.0f, tq = 0.0f;
 #pragma unroll
-        for (int k = 0; k < kSelectParts; k++) { tk += k2[k][d]; tq += q2[k][d]; }
-        w[d] = (tk / (float)a.n_blocks) * (tq / (float)samples);
+        for (int k = 0; k < kSelectParts; k++) { tm += k1[k][d]; tk += k2[k][d]; tq += q2[k][d]; }
+        // the channel's centre: the mean of its blocks' midpoints, as an fp16 number (the zero-points are fp16 numbers, so
+        // zero-point minus centre is exact in fp32).  What counts from here on is the keys' spread about it.
+        const float centre = (float)(_Float16)(tm / (float)a.n_blocks);
+        const float centre_ok = fabsf(centre) < 65504.0f ? centre : 0.0f;
+        sel->centre[d] = centre_ok;
+        const float spread = fmaxf(tk / (float)a.n_blocks - centre_ok * (2.0f * tm / (float)a.n_blocks - centre_ok), 0.0f);
+        w[d] = spread * (tq / (float)samples);
     }
     __syncthreads();
-    Select *sel = reinterpret_cast<Select *>(a.select) + local;
     if (part == 0) {
         const float mine = w[d];
         int rank = 0;
@@ -659,13 +685,9 @@ __global__ __launch_bounds__(64 * kStagers) void prefill_dequantize(PrefillArgs 
     __shared__ __attribute__((aligned(16))) MetaSlab M[kStagers];
     Stage st;
     load_packed<KQ, VQ>(a, a.bh0 + local, u, T, tid, st);
-    const Select *sel = nullptr;
-    if (KQ && a.select) {
-        sel = reinterpret_cast<const Select *>(a.select) + local;
-        if (!sel->compact) sel = nullptr;
-    }
+    const Select *rec = KQ && a.select ? reinterpret_cast<const Select *>(a.select) + local : nullptr;
     Tiles &dst = *reinterpret_cast<Tiles *>(a.scratch + ((size_t)local * a.n_blocks + u) * sizeof(Tiles));
-    store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6], sel);
+    store_packed<KQ, VQ>(a, tid, st, dst, M[tid >> 6], rec);
 }
 
 // A unit goes from the scratch area into an LDS buffer without passing through registers: a wave issues
@@ -715,9 +737,10 @@ __device__ __forceinline__ void wait_fetches() { asm volatile("s_waitcnt vmcnt(0
 // on each other), instead of waiting for each product's result in turn.
 constexpr int kBuffers = 5;
 
-// LO: how the low parts of the keys come (score_unit); sel: the cache's selection record (kLoCompact).
+// LO: how the low parts of the keys come (score_unit); rec: the cache's selection record or null (never null with
+// kLoCompact).
 template <int LO>
-__device__ __forceinline__ void attend(const PrefillArgs &a, const Select *sel, int local, int jq, int rank)
+__device__ __forceinline__ void attend(const PrefillArgs &a, const Select *rec, int local, int jq, int rank)
 {
     constexpr bool KLO = LO != kLoNone;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -755,12 +778,38 @@ __device__ __forceinline__ void attend(const PrefillArgs &a, const Select *sel, 
         for (int step = 0; step < 4; step++) Qf[qt][step] = __builtin_nontemporal_load(reinterpret_cast<const half8 *>(row + 32 * step + 8 * rq));
         if constexpr (LO == kLoCompact) {
             // the query's values at the channels of slots 8 rq .. 8 rq + 7: the operand that meets the compact tile
-            const u32x2 cw = *reinterpret_cast<const u32x2 *>(&sel->chan[8 * rq]);
+            const u32x2 cw = *reinterpret_cast<const u32x2 *>(&rec->chan[8 * rq]);
 #pragma unroll
             for (int e = 0; e < 8; e++)
                 Qlo[qt][e] = __builtin_bit_cast(_Float16, row[((e < 4 ? cw[0] : cw[1]) >> (8 * (e & 3))) & 127u]);
         } else {
             Qlo[qt] = half8{};
+        }
+    }
+
+    // Packed keys come with their channel's centre taken off (prefill_dequantize), which lowers every packed score of a
+    // query by q . centre; the scores of the window's fp16 rows are lowered by the same amount here, so that the softmax
+    // sees all of a query's scores moved alike.  woff = minus that amount in the exponent's units.
+    float woff[kQT];
+#pragma unroll
+    for (int qt = 0; qt < kQT; qt++) woff[qt] = 0.0f;
+    if constexpr (KLO) {
+        if (rec) {
+#pragma unroll
+            for (int qt = 0; qt < kQT; qt++) {
+                float dot = 0.0f;
+#pragma unroll
+                for (int step = 0; step < 4; step++) {
+                    const float4 c0 = *reinterpret_cast<const float4 *>(&rec->centre[32 * step + 8 * rq]);
+                    const float4 c1 = *reinterpret_cast<const float4 *>(&rec->centre[32 * step + 8 * rq + 4]);
+                    const float cen[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+                    for (int e = 0; e < 8; e++) dot = fmaf((float)Qf[qt][step][e], cen[e], dot);
+                }
+                dot += xor_lanes(dot, 16);
+                dot += xor_lanes(dot, 32);
+                woff[qt] = -c * dot;
+            }
         }
     }
 
@@ -877,9 +926,8 @@ __device__ __forceinline__ void attend(const PrefillArgs &a, const Select *sel, 
             half8 P[kQT];
             float alpha[kQT];
             const float4v none[kQT] = {};
-            const float nobase[kQT] = {};                       // fp16 rows: raw scores
-            score_unit<kLoNone>(L[0], Qf, Qlo, S, n, rq, none);
-            softmax_unit<true, false>(S, c, u, qpos, nobase, m, lsum, P, alpha, rq);
+            score_unit<kLoNone>(L[0], Qf, Qlo, S, n, rq, none);                 // fp16 rows: raw scores
+            softmax_unit<true, false>(S, c, u, qpos, woff, m, lsum, P, alpha, rq);
             output_rescale(alpha, O);
             half8 Av[8];
 #pragma unroll
@@ -928,9 +976,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void prefill_attention(PrefillArgs 
         rank = blockIdx.x % tiles;
     }
     if constexpr (KQ) {
-        const Select *sel = a.select ? reinterpret_cast<const Select *>(a.select) + local : nullptr;
-        if (sel && __builtin_amdgcn_readfirstlane((int)sel->compact) != 0) attend<kLoCompact>(a, sel, local, jq, rank);
-        else attend<kLoAll>(a, nullptr, local, jq, rank);
+        const Select *rec = a.select ? reinterpret_cast<const Select *>(a.select) + local : nullptr;
+        if (rec && __builtin_amdgcn_readfirstlane((int)rec->compact) != 0) attend<kLoCompact>(a, rec, local, jq, rank);
+        else attend<kLoAll>(a, rec, local, jq, rank);
     } else {
         attend<kLoNone>(a, nullptr, local, jq, rank);
     }

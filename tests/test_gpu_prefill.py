@@ -203,6 +203,41 @@ def test_llama_shape_full_prompt_sampled_rows(kvq_mod, oracle_mod):
     assert worst > 0
 
 
+def test_qwen_shape_prompt_with_key_offsets_sampled_rows(kvq_mod, oracle_mod):
+    """The Qwen2.5-7B shape (28 query / 4 kv heads, keys with a large offset on every channel), batch 4, a prompt of
+    8192 + 19 tokens (a 51-token fp16 window behind 255 packed units), K4V2.  The kernel takes the offsets off the
+    packed keys and lowers the window's scores by the matching amount; sampled (batch, kv head) pairs at sampled
+    positions, the window's among them, against the oracle, with the choice of low-part channels on and off."""
+    w = W.named("qwen7b", "K4V2", 4, 8192 + 19)
+    layer, (kb, vb) = 1, (4, 2)
+    T, gq = w.context, w.n_q_heads // w.n_kv_heads
+    g = kvq_mod.KVQ(1, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, T + 64, [kb], [vb])
+    for t0 in range(0, T, 2048):
+        K, V = W.kv_tokens(w, layer, t0, min(T, t0 + 2048), device="cuda:0")
+        g.quantize_append(0, K, V)
+    del K, V
+    assert g.layer_tokens(0) == (8160, 51)
+    q = torch.empty(w.batch, w.n_q_heads, T, w.head_dim, dtype=torch.float16, device="cuda:0")
+    for h0 in range(0, w.n_q_heads, gq):
+        q[:, h0:h0 + gq] = W.prefill_queries(w, layer, T, device="cuda:0", heads=(h0, gq))
+    pos = [0, 1, 31, 32, 33, 255, 256, 1000, 4095, 4096, 8159, 8160, 8161, 8191, 8192, 8200, T - 2, T - 1]
+    for low_parts in (0, 1):
+        g.set_prefill_options(low_parts)
+        out = g.prefill_attention(0, q)
+        torch.cuda.synchronize()
+        for bh in (0, 6, 15):                       # (b, h) = (0, 0), (1, 2), (3, 3)
+            b, h = divmod(bh, w.n_kv_heads)
+            Kc, Vc = W.kv_tokens(w, layer, 0, T, bh=torch.tensor([bh]))
+            o = oracle_mod.OracleCache(1, 1, gq, 1, w.head_dim, [kb], [vb])
+            o.quantize_append(0, Kc.numpy()[None], Vc.numpy()[None])
+            assert o.tokens(0) == g.layer_tokens(0)
+            qs = q[b, h * gq:(h + 1) * gq][:, pos].cpu().numpy()[None]
+            o16, o64 = o.prefill_attention_at(0, np.ascontiguousarray(qs), pos)
+            assert_prefill_close(out[b, h * gq:(h + 1) * gq][:, pos][None], o64, "bh %d low_parts %d" % (bh, low_parts))
+            o.close()
+    g.close()
+
+
 def test_llama_heads_32k_prompt_sampled_rows(kvq_mod, oracle_mod):
     """A 32768-token prompt (Llama-3.1-8B heads, batch 3 = 24 caches, i.e. two passes; K8V4 layer): 1023 packed units per
     cache and 128 query tiles per head.  Sampled (batch, kv head) pairs at sampled positions against the oracle."""
