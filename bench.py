@@ -373,6 +373,10 @@ def extra_configs(torch, pkg, W, args):
     rq8 = time_workload(torch, pkg, W, wq8, 16, 2, args.variant, args.splits)
     out["qwen7b-B8-T32768"] = dict(summary(rq, wq), steps=16, warmup=2, kv8=summary(rq8, wq8),
                                    speedup_vs_kv8=rq["tokens_per_s"] / rq8["tokens_per_s"])
+    if not args.no_prefill_attn:
+        # the prompt's own attention on this shape (keys with a large offset on every channel), one K4V2 layer
+        out["qwen7b-B8-T32768"]["prefill_attention"] = time_prefill_attention(torch, pkg, W, wq, 1, reps=2,
+                                                                              reference=not args.no_prefill_reference)
     w2 = W.config2(16, 4096)
     r2 = time_workload(torch, pkg, W, w2, 32, 4, args.variant, args.splits)
     out["llama8b-B16-T4096-K8V8"] = dict(summary(r2, w2), steps=32, warmup=4)
