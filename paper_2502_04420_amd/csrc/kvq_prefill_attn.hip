@@ -664,7 +664,7 @@ __global__ __launch_bounds__(kD * kSelectParts) void prefill_select(PrefillArgs 
         for (int o = 0; o < kD; o++) rank += (w[o] > mine || (w[o] == mine && o < d)) ? 1 : 0;
         sel->pos[d] = rank < 32 ? (uint8_t)rank : (uint8_t)255;
         if (rank < 32) sel->chan[rank] = (uint8_t)d;
-        rest[d] = rank < 32 ? 0.0f : mine;
+        rest[d] = rank < 32 && mine == mine ? 0.0f : mine;       // (not a number: stays one, and the sum below with it)
     }
     __syncthreads();
     if (threadIdx.x == 0) {
